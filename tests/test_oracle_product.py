@@ -1,0 +1,196 @@
+"""Pins for the oracle's integer products, shifted accumulation and whole path.
+
+Anchors: numpy's int64 matmul (a library routine the oracle does not use),
+exact integer products of integer-valued inputs, a brute-force re-evaluation in
+exact rationals with Python's correctly rounded Fraction -> float conversion,
+the error bound of Section 5.2, and metamorphic identities that hold bit for bit.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2409_13313_amd import inputs
+
+U = 2.0 ** -53
+
+
+def int_slices(rng, k, rows, cols, bound):
+    return rng.integers(-bound, bound + 1, size=(k, rows, cols)).astype(np.int8)
+
+
+def test_chunk_equals_int64_matmul_of_slices():
+    rng = np.random.Generator(np.random.PCG64(1))
+    k, m, n, p = 6, 9, 70, 11
+    SA, SB = int_slices(rng, k, m, n, 64), int_slices(rng, k, n, p, 64)
+    for (g, s0, s1) in [(2, 1, 1), (5, 1, 4), (5, 2, 3), (7, 1, 6), (7, 3, 3), (7, 5, 6)]:
+        want = sum(SA[s - 1].astype(np.int64) @ SB[g - s - 1].astype(np.int64) for s in range(s0, s1 + 1))
+        got = oracle.group_chunk(SA, SB, g, s0, s1)
+        assert got.dtype == np.int32 and np.array_equal(got, want)
+    assert np.array_equal(oracle.pair_product(SA, SB, 2, 3), SA[1].astype(np.int64) @ SB[2].astype(np.int64))
+    # not symmetric in (s, t): a transposed operand or swapped index fails here
+    assert not np.array_equal(oracle.pair_product(SA, SB, 2, 3), oracle.pair_product(SA, SB, 3, 2))
+
+
+def test_int32_bound_of_section_5_2_is_tight_for_r_products_and_detected_beyond():
+    # n = 2^14, beta = 7 => r = 8.  With every slice entry at the paper's bound
+    # 2^beta - 1 = 127, 8 products fit INT32 and 9 do not.
+    n = 16384
+    beta, r = oracle.params(n)
+    assert (beta, r) == (7, 8)
+    SA = np.full((9, 1, n), 127, dtype=np.int8)
+    SB = np.full((9, n, 1), 127, dtype=np.int8)
+    C = oracle.group_chunk(SA, SB, 9, 1, 8)
+    assert C[0, 0] == 8 * n * 127 * 127 < 2 ** 31
+    SB[:] = -127
+    assert oracle.group_chunk(SA, SB, 9, 1, 8)[0, 0] == -8 * n * 127 * 127
+    with pytest.raises(OverflowError):
+        oracle.group_chunk(SA, SB, 10, 1, 9)
+
+
+def test_accumulate_is_exact_scaling_plus_one_rounded_add():
+    rng = np.random.Generator(np.random.PCG64(2))
+    m, p, beta, g = 5, 7, 7, 4
+    C = rng.integers(-2 ** 31, 2 ** 31, size=(m, p)).astype(np.int32)
+    C[0, 0] = 0
+    eA = rng.integers(-40, 40, size=m).astype(np.int32)
+    eB = rng.integers(-40, 40, size=p).astype(np.int32)
+    D0 = rng.standard_normal((m, p))
+    D = D0.copy()
+    oracle.accumulate(D, C, eA, eB, beta, g, first=False)
+    for i in range(m):
+        for j in range(p):
+            want = Fraction(float(D0[i, j])) + Fraction(int(C[i, j])) * Fraction(2) ** (int(eA[i]) + int(eB[j]) + 2 - beta * g)
+            assert D[i, j] == float(want)          # Fraction -> float is correctly rounded
+    D = np.full((m, p), np.nan)
+    oracle.accumulate(D, C, eA, eB, beta, g, first=True)
+    assert D[0, 0] == 0.0 and not np.signbit(D[0, 0])
+    assert np.array_equal(D, np.ldexp(C.astype(np.float64), (eA[:, None] + eB[None, :] + 2 - beta * g)))
+
+
+def brute_force_alg6(A, B, k):
+    """Algorithm 6 re-walked in exact rationals from the oracle's slices, with
+    one correctly rounded FP64 addition per chunk; also returns the exact sum
+    of all kept products (no rounding) and the sum of their magnitudes."""
+    m, n = A.shape
+    p = B.shape[1]
+    beta, r = oracle.params(n)
+    SA, eA = oracle.split_rows(A, k, beta)
+    SB, eB = oracle.split_cols(B, k, beta)
+    SA64, SB64 = SA.astype(np.int64), SB.astype(np.int64)
+    D = [[0.0] * p for _ in range(m)]
+    exact = [[Fraction(0)] * p for _ in range(m)]
+    mag = [[Fraction(0)] * p for _ in range(m)]
+    w = 0
+    for g in range(2, k + 2):
+        q, C = 0, np.zeros((m, p), dtype=np.int64)
+        for s in range(1, g):
+            q += 1
+            C += SA64[s - 1] @ SB64[g - s - 1]
+            if q == r or s == g - 1:
+                w += 1
+                for i in range(m):
+                    for j in range(p):
+                        term = Fraction(int(C[i, j])) * Fraction(2) ** (int(eA[i]) + int(eB[j]) + 2 - beta * g)
+                        D[i][j] = float(Fraction(D[i][j]) + term)
+                        exact[i][j] += term
+                        mag[i][j] += abs(term)
+                q, C = 0, np.zeros((m, p), dtype=np.int64)
+    return np.array(D), exact, mag, w, beta, r
+
+
+@pytest.mark.parametrize("m,n,p,k,phi", [(3, 5, 4, 6, 0.5), (2, 40, 3, 9, 2.0), (4, 17, 2, 13, 4.0),
+                                         (2, 65536, 2, 5, 1.0),      # r = 2: several chunks per group
+                                         (1, 2 ** 17 + 3, 2, 4, 0.5)])  # beta = 6, r = 2
+def test_whole_path_equals_brute_force_walk(m, n, p, k, phi):
+    A, B = inputs.phi_pair(m, n, p, phi, seed=21)
+    D, w_oracle = oracle.dgemm(A, B, k, return_addends=True)
+    Dbf, exact, mag, w, beta, r = brute_force_alg6(A, B, k)
+    assert w_oracle == w == oracle.count_addends(k, r)
+    assert np.array_equal(D, Dbf)
+    # order-independent check: D is within (w-1) u sum|terms| of the unrounded sum (eq. (error_sum))
+    for i in range(m):
+        for j in range(p):
+            assert abs(Fraction(float(D[i, j])) - exact[i][j]) <= (w - 1) * Fraction(U) * mag[i][j] * Fraction(101, 100)
+
+
+@pytest.mark.parametrize("k", [1, 2, 5, 9])
+def test_small_integer_inputs_give_the_exact_product_for_every_k(k):
+    # |a|, |b| <= 64 with the row/column maximum pinned to 64: one non-zero slice each.
+    A, B = inputs.small_int_pair(23, 300, 19, 64, seed=4)
+    A[:, 0] = 64.0
+    B[0, :] = -64.0
+    want = A.astype(np.int64) @ B.astype(np.int64)
+    assert np.array_equal(oracle.dgemm(A, B, k), want.astype(np.float64))
+
+
+def test_two_slice_integers_are_exact_from_k_3():
+    A, B = inputs.small_int_pair(11, 64, 13, 2 ** 13, seed=5)
+    A[:, 0] = 2.0 ** 13
+    B[0, :] = 2.0 ** 13
+    want = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)
+    assert np.array_equal(oracle.dgemm(A, B, 3), want)
+    assert not np.array_equal(oracle.dgemm(A, B, 1), want)
+
+
+def test_k1_is_a_single_scaled_integer_gemm():
+    A, B = inputs.phi_pair(12, 50, 9, 1.0, seed=6)
+    beta, _ = oracle.params(50)
+    SA, eA = oracle.split_rows(A, 1, beta)
+    SB, eB = oracle.split_cols(B, 1, beta)
+    P = SA[0].astype(np.int64) @ SB[0].astype(np.int64)
+    want = np.ldexp(P.astype(np.float64), eA[:, None] + eB[None, :] + 2 - 2 * beta)
+    assert np.array_equal(oracle.dgemm(A, B, 1), want)
+
+
+def test_metamorphic_identities_hold_bit_for_bit():
+    A, B = inputs.phi_pair(14, 96, 10, 2.0, seed=7)
+    k = 9
+    D = oracle.dgemm(A, B, k)
+    # power-of-two row / column scaling
+    sr = 2.0 ** np.arange(-7, 7)[:, None]
+    sc = 2.0 ** np.arange(5, -5, -1)[None, :]
+    assert np.array_equal(oracle.dgemm(A * sr, B * sc, k), D * sr * sc)
+    # sign symmetry of round-to-nearest-even
+    assert np.array_equal(oracle.dgemm(-A, B, k), -D)
+    # transposition (r >= k here, so each group is one chunk on both sides)
+    assert oracle.params(96)[1] >= k
+    assert np.array_equal(oracle.dgemm(np.ascontiguousarray(B.T), np.ascontiguousarray(A.T), k), D.T)
+    # permuting the inner index
+    perm = np.random.Generator(np.random.PCG64(8)).permutation(96)
+    assert np.array_equal(oracle.dgemm(np.ascontiguousarray(A[:, perm]), np.ascontiguousarray(B[perm]), k), D)
+    # sub-matrix evaluation is the same numbers
+    I, J = [0, 5, 13], [9, 2]
+    assert np.array_equal(oracle.dgemm_sub(A, B, k, I, J), D[np.ix_(I, J)])
+
+
+@pytest.mark.parametrize("phi", [0.5, 2.0])
+def test_error_bound_of_section_5_2_and_decay_with_k(phi):
+    m = n = p = 96
+    A, B = inputs.phi_pair(m, n, p, phi, seed=9)
+    hi, lo = oracle.dot2_gemm(A, B)
+    absAB = np.abs(A) @ np.abs(B)
+    beta, r = oracle.params(n)
+    gA = np.ldexp(1.0, np.floor(np.log2(np.abs(A).max(axis=1))).astype(np.int32))   # ufp of row max
+    fB = np.ldexp(1.0, np.floor(np.log2(np.abs(B).max(axis=0))).astype(np.int32))   # ufp of column max
+    prev = np.inf
+    for k in range(1, 13):
+        D = oracle.dgemm(A, B, k)
+        err = np.abs((D - hi) - lo)
+        w = oracle.count_addends(k, r)
+        bound = 4 * (k + 1) * n * 2.0 ** (-beta * k) * np.outer(gA, fB) + (w - 1) * U * absAB
+        assert (err <= bound * 1.001 + 4 * U * U * absAB).all()
+        e = err.max()
+        assert e <= prev * 1.0001 or e <= 16 * U * absAB.max()     # non-increasing until the FP64 floor
+        prev = min(prev, e)
+    assert prev <= 16 * U * absAB.max()
+
+
+def test_more_slices_than_needed_match_fp64_quality():
+    # Section 4.1: with enough slices the result is comparable to an FP64 product.
+    A, B = inputs.phi_pair(64, 64, 64, 0.5, seed=10)
+    hi, lo = oracle.dot2_gemm(A, B)
+    e_fp64 = np.abs((A @ B - hi) - lo).max()
+    e_oz = np.abs((oracle.dgemm(A, B, 10) - hi) - lo).max()
+    assert e_oz <= 2 * e_fp64

@@ -1,0 +1,138 @@
+/*
+ * ozimmu.h - C ABI of the gfx950 (MI355X) library that emulates FP64 matrix
+ * multiplication D = A B on the INT8 matrix cores with the Ozaki scheme in its
+ * "ozIMMU_H" form: round-to-nearest INT8 slices with one power-of-two scale
+ * per row of A / column of B (Algorithm 8 of the paper), INT8 x INT8 -> INT32
+ * products of the slice pairs (s, t) with s + t <= k + 1, products that share
+ * a shift summed in INT32 in chunks of at most r (Algorithm 6, eq.
+ * (errfreesum), eq. (def_r)), and one shifted FP64 addition per chunk.
+ *
+ * Conventions
+ *   - A is m x n, B is n x p, D is m x p: n is the INNER dimension (paper's
+ *     notation, Section 1).  All three are row-major with leading dimensions
+ *     lda >= n, ldb >= p, ldd >= p counted in elements.
+ *   - Every pointer marked "device" is memory of the current HIP device,
+ *     owned by the caller; the library allocates nothing and keeps no state
+ *     between calls.  A and B are never modified.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*); no
+ *     call synchronises with the host.  Buffers must stay alive until the
+ *     stream has run the work.
+ *   - Every function returns OZIMMU_OK (0) or a negative status; nothing is
+ *     enqueued when an argument check fails.  Inputs are assumed finite with
+ *     no overflow / underflow in the scaling (the paper's standing assumption,
+ *     Section 5); NaN / Inf inputs give unspecified numbers, never a fault.
+ */
+#ifndef OZIMMU_H
+#define OZIMMU_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OZIMMU_MAX_SLICES 20
+
+enum {
+    OZIMMU_OK = 0,
+    OZIMMU_ERR_NULL = -1,       /* a required pointer is NULL */
+    OZIMMU_ERR_DIM = -2,        /* negative size, leading dimension too small, n > 2^29 (beta < 1) */
+    OZIMMU_ERR_SLICES = -3,     /* k outside 1..OZIMMU_MAX_SLICES, or g / s range invalid */
+    OZIMMU_ERR_WORKSPACE = -4,  /* workspace too small or misaligned (needs 256-byte alignment) */
+    OZIMMU_ERR_HIP = -5         /* a kernel launch reported a HIP error */
+};
+
+/* Human-readable text for a status code (static storage, host). */
+const char *ozimmu_status_string(int status);
+
+/* beta = min(7, floor((31 - log2 n)/2))   [eq. (beta)]  and
+ * r = max(1, 2^(31 - 2 beta - ceil(log2 n)))   [eq. (def_r)], host, pure.
+ * Returns OZIMMU_ERR_DIM for n < 1 or n > 2^29. */
+int ozimmu_params(int64_t n, int *beta, int64_t *r);
+
+/* Number of FP64 additions per element of D (= number of INT32 chunks the
+ * schedule of Algorithm 6 produces) for inner dimension n and k slices; host. */
+int64_t ozimmu_num_chunks(int64_t n, int k);
+
+/* Bytes of the packed INT8 slice stack of a matrix with `rows` scaled vectors
+ * (m for A, p for B) of inner length n and k slices; host.  The packed layout
+ * is private to the library (tile-major, see ozimmu_export_slices). */
+size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k);
+
+/* Bytes of device workspace ozimmu_dgemm needs; host. */
+size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k);
+
+/* D <- A B with k slices: steps (i)-(iv) of the scheme (Section 1) as
+ * Algorithm 8 (split) followed by Algorithm 6 (grouped accumulation).
+ *   A, B, D      device, FP64, row-major (see above); D is overwritten.
+ *   k            number of slices, 1..OZIMMU_MAX_SLICES.
+ *   workspace    device, >= ozimmu_workspace_bytes(m,n,p,k) bytes, 256-byte aligned.
+ * m, n or p equal to 0 is valid: nothing is computed, and for n == 0 (m, p > 0)
+ * D is set to +0. */
+int ozimmu_dgemm(int64_t m, int64_t n, int64_t p,
+                 const double *A, int64_t lda,
+                 const double *B, int64_t ldb,
+                 double *D, int64_t ldd,
+                 int k, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- phase-level entry points (the same kernels ozimmu_dgemm runs) ---- */
+
+/* Steps (i): eA[i] = ceil(log2 max_j |a_ij|) (0 for an all-zero row) and the k
+ * INT8 slices of A on the grids 2^(eA[i] + 1 - s beta), s = 1..k, rounded to
+ * nearest-even   [Algorithm 8].
+ *   A       device, m x n row-major, lda >= n.
+ *   SA      device, ozimmu_slices_bytes(m, n, k) bytes, 256-byte aligned, packed.
+ *   eA      device, int32[m].
+ * beta is derived from n. */
+int ozimmu_split_A(int64_t m, int64_t n, const double *A, int64_t lda, int k,
+                   int8_t *SA, int32_t *eA, void *stream);
+
+/* Step (ii): the same for the COLUMNS of B (B is split as the transpose of
+ * the split of B^T, Section 2): eB[j] = ceil(log2 max_i |b_ij|), slices packed
+ * with the inner index contiguous.
+ *   B       device, n x p row-major, ldb >= p.
+ *   SB      device, ozimmu_slices_bytes(p, n, k) bytes, 256-byte aligned, packed.
+ *   eB      device, int32[p]. */
+int ozimmu_split_B(int64_t n, int64_t p, const double *B, int64_t ldb, int k,
+                   int8_t *SB, int32_t *eB, void *stream);
+
+/* Step (iii) for one chunk: C'' <- sum_{s = s0..s1} A''_s B''_{g-s} in INT32
+ *                                              [Algorithm 6, lines 7-9].
+ * s0 == s1 gives the single pair product A''_s B''_{g-s} of Algorithm 4.
+ *   SA, SB  device, packed slice stacks holding kA / kB slices.
+ *   C       device, int32 m x p row-major, ldc >= p, overwritten.
+ * Requires 1 <= s0 <= s1 <= kA and 1 <= g - s1, g - s0 <= kB.  The caller is
+ * responsible for s1 - s0 + 1 <= r (no INT32 overflow, Section 5.2). */
+int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p,
+                      const int8_t *SA, int kA, const int8_t *SB, int kB,
+                      int g, int s0, int s1,
+                      int32_t *C, int64_t ldc, void *stream);
+
+/* Step (iv) for one chunk: D <- D + 2^(2 - beta g) diag(2^eA) FP64(C'') diag(2^eB)
+ *                                              [Algorithm 6, line 11].
+ * first != 0: D is taken to be zero and is overwritten (Algorithm 6, line 3).
+ * beta is passed explicitly (it depends on n, which this call does not see). */
+int ozimmu_accumulate(int64_t m, int64_t p, const int32_t *C, int64_t ldc,
+                      const int32_t *eA, const int32_t *eB, int beta, int g, int first,
+                      double *D, int64_t ldd, void *stream);
+
+/* Steps (iii)+(iv) for one chunk in one kernel: the INT32 chunk sum stays in
+ * registers and is converted, scaled and added to D in the GEMM epilogue
+ * (this is what ozimmu_dgemm launches once per chunk). */
+int ozimmu_gemm_group_accumulate(int64_t m, int64_t n, int64_t p,
+                                 const int8_t *SA, int kA, const int8_t *SB, int kB,
+                                 int g, int s0, int s1,
+                                 const int32_t *eA, const int32_t *eB, int first,
+                                 double *D, int64_t ldd, void *stream);
+
+/* Unpack a packed slice stack into the canonical order out[s][row][l]
+ * (int8, k x rows x n, dense): for A that is A''_s[i][l]; for B it is
+ * B''_s[l][j] stored at out[s][j][l].  Debug / test helper. */
+int ozimmu_export_slices(int64_t rows, int64_t n, int k, const int8_t *packed,
+                         int8_t *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OZIMMU_H */

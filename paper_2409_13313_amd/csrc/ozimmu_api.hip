@@ -1,0 +1,234 @@
+// C ABI of the library (declared in include/ozimmu.h): argument checks, the
+// host-side schedule of Algorithm 6 (groups g = 2..k+1, chunks of at most r
+// consecutive s), workspace carving and kernel launches.  No allocation, no
+// host synchronisation, no state between calls.
+#include "../../include/ozimmu.h"
+#include "ozimmu_kernels.h"
+#include "ozimmu_layout.h"
+
+namespace {
+
+constexpr int64_t MAX_OUTER = (int64_t)1 << 22;   // keeps every grid dimension within HIP limits
+constexpr int64_t MAX_INNER = (int64_t)1 << 29;   // beta >= 1 (Section 2)
+
+inline int64_t align256(int64_t x) { return (x + 255) / 256 * 256; }
+
+int beta_of(int64_t n)
+{
+    // floor((31 - log2 n)/2) >= b  <=>  n * 4^b <= 2^31
+    int beta = 0;
+    while (beta < 7 && (n << (2 * (beta + 1))) <= ((int64_t)1 << 31)) ++beta;
+    return beta;
+}
+
+int64_t r_of(int64_t n, int beta)
+{
+    int L = 0;  // ceil(log2 n)
+    while (((int64_t)1 << L) < n) ++L;
+    const int ex = 31 - 2 * beta - L;
+    return ex > 0 ? ((int64_t)1 << ex) : 1;
+}
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? OZIMMU_OK : OZIMMU_ERR_HIP; }
+
+int check_gemm_args(int64_t m, int64_t n, int64_t p, const void* SA, int kA, const void* SB, int kB, int g, int s0,
+                    int s1)
+{
+    if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
+    if (kA < 1 || kA > OZIMMU_MAX_SLICES || kB < 1 || kB > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
+    if (s0 < 1 || s1 < s0 || s1 > kA || g - s1 < 1 || g - s0 > kB) return OZIMMU_ERR_SLICES;
+    if (m == 0 || n == 0 || p == 0) return OZIMMU_OK;
+    if (!SA || !SB) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(SA) % 256 || reinterpret_cast<uintptr_t>(SB) % 256) return OZIMMU_ERR_WORKSPACE;
+    return OZIMMU_OK;
+}
+
+ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, int g, int s0, int s1)
+{
+    ozk::GemmArgs a{};
+    a.SA = SA;
+    a.SB = SB;
+    a.strideA = ozl::slice_bytes(m, n);
+    a.strideB = ozl::slice_bytes(p, n);
+    a.KT = (int)(ozl::inner_padded(n) / ozl::TILE_K);
+    a.g = g;
+    a.s0 = s0;
+    a.s1 = s1;
+    a.m = m;
+    a.p = p;
+    return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ozimmu_status_string(int status)
+{
+    switch (status) {
+        case OZIMMU_OK: return "ok";
+        case OZIMMU_ERR_NULL: return "null pointer argument";
+        case OZIMMU_ERR_DIM: return "invalid dimension or leading dimension";
+        case OZIMMU_ERR_SLICES: return "invalid slice count or slice range";
+        case OZIMMU_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case OZIMMU_ERR_HIP: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+int ozimmu_params(int64_t n, int* beta, int64_t* r)
+{
+    if (n < 1 || n > MAX_INNER) return OZIMMU_ERR_DIM;
+    const int b = beta_of(n);
+    if (beta) *beta = b;
+    if (r) *r = r_of(n, b);
+    return OZIMMU_OK;
+}
+
+int64_t ozimmu_num_chunks(int64_t n, int k)
+{
+    if (n < 1 || n > MAX_INNER || k < 1) return 0;
+    const int64_t r = r_of(n, beta_of(n));
+    int64_t w = 0;
+    for (int g = 2; g <= k + 1; ++g) w += ((g - 1) + r - 1) / r;
+    return w;
+}
+
+size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k)
+{
+    if (rows < 0 || n < 0 || k < 0) return 0;
+    return (size_t)k * (size_t)ozl::slice_bytes(rows, n);
+}
+
+size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k)
+{
+    if (m < 0 || n < 0 || p < 0 || k < 0) return 0;
+    return (size_t)(align256(4 * m) + align256(4 * p)) + ozimmu_slices_bytes(m, n, k) + ozimmu_slices_bytes(p, n, k);
+}
+
+int ozimmu_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int8_t* SA, int32_t* eA, void* stream)
+{
+    if (m < 0 || n < 0 || m > MAX_OUTER || n > MAX_INNER || lda < n) return OZIMMU_ERR_DIM;
+    if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
+    if (m == 0 || n == 0) return OZIMMU_OK;
+    if (!A || !SA || !eA) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(SA) % 256) return OZIMMU_ERR_WORKSPACE;
+    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), SA, eA, (hipStream_t)stream));
+}
+
+int ozimmu_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int8_t* SB, int32_t* eB, void* stream)
+{
+    if (p < 0 || n < 0 || p > MAX_OUTER || n > MAX_INNER || ldb < p) return OZIMMU_ERR_DIM;
+    if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
+    if (p == 0 || n == 0) return OZIMMU_OK;
+    if (!B || !SB || !eB) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(SB) % 256) return OZIMMU_ERR_WORKSPACE;
+    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), SB, eB, (hipStream_t)stream));
+}
+
+int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA, const int8_t* SB, int kB, int g,
+                      int s0, int s1, int32_t* C, int64_t ldc, void* stream)
+{
+    int st = check_gemm_args(m, n, p, SA, kA, SB, kB, g, s0, s1);
+    if (st != OZIMMU_OK) return st;
+    if (ldc < p) return OZIMMU_ERR_DIM;
+    if (m == 0 || p == 0 || n == 0) return OZIMMU_OK;
+    if (!C) return OZIMMU_ERR_NULL;
+    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, s0, s1);
+    a.C = C;
+    a.ldc = ldc;
+    return hip_status(ozk::launch_gemm(a, 0, (hipStream_t)stream));
+}
+
+int ozimmu_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA, const int32_t* eB,
+                      int beta, int g, int first, double* D, int64_t ldd, void* stream)
+{
+    if (m < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || ldc < p || ldd < p) return OZIMMU_ERR_DIM;
+    if (beta < 1 || beta > 7 || g < 2 || g > 2 * OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
+    if (m == 0 || p == 0) return OZIMMU_OK;
+    if (!C || !eA || !eB || !D) return OZIMMU_ERR_NULL;
+    return hip_status(
+        ozk::launch_accumulate(m, p, C, ldc, eA, eB, 2 - beta * g, first, D, ldd, (hipStream_t)stream));
+}
+
+int ozimmu_gemm_group_accumulate(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA, const int8_t* SB, int kB,
+                                 int g, int s0, int s1, const int32_t* eA, const int32_t* eB, int first, double* D,
+                                 int64_t ldd, void* stream)
+{
+    int st = check_gemm_args(m, n, p, SA, kA, SB, kB, g, s0, s1);
+    if (st != OZIMMU_OK) return st;
+    if (ldd < p) return OZIMMU_ERR_DIM;
+    if (m == 0 || p == 0 || n == 0) return OZIMMU_OK;
+    if (!eA || !eB || !D) return OZIMMU_ERR_NULL;
+    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, s0, s1);
+    a.D = D;
+    a.ldd = ldd;
+    a.eA = eA;
+    a.eB = eB;
+    a.shift = 2 - beta_of(n) * g;
+    a.first = first;
+    return hip_status(ozk::launch_gemm(a, 1, (hipStream_t)stream));
+}
+
+int ozimmu_export_slices(int64_t rows, int64_t n, int k, const int8_t* packed, int8_t* out, void* stream)
+{
+    if (rows < 0 || n < 0 || rows > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
+    if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
+    if (rows == 0 || n == 0) return OZIMMU_OK;
+    if (!packed || !out) return OZIMMU_ERR_NULL;
+    return hip_status(ozk::launch_export(rows, n, k, packed, out, (hipStream_t)stream));
+}
+
+int ozimmu_dgemm(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
+                 double* D, int64_t ldd, int k, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
+    if (lda < n || ldb < p || ldd < p) return OZIMMU_ERR_DIM;
+    if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
+    if (m == 0 || p == 0) return OZIMMU_OK;
+    if (!D) return OZIMMU_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    if (n == 0) return hip_status(ozk::launch_fill_zero_f64(m, p, D, ldd, st));
+    if (!A || !B || !workspace) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < ozimmu_workspace_bytes(m, n, p, k))
+        return OZIMMU_ERR_WORKSPACE;
+
+    const int beta = beta_of(n);
+    const int64_t r = r_of(n, beta);
+    char* ws = static_cast<char*>(workspace);
+    int32_t* eA = reinterpret_cast<int32_t*>(ws);
+    ws += align256(4 * m);
+    int32_t* eB = reinterpret_cast<int32_t*>(ws);
+    ws += align256(4 * p);
+    int8_t* SA = reinterpret_cast<int8_t*>(ws);
+    ws += ozimmu_slices_bytes(m, n, k);
+    int8_t* SB = reinterpret_cast<int8_t*>(ws);
+
+    hipError_t e = ozk::launch_split_A(m, n, A, lda, k, beta, SA, eA, st);
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+    e = ozk::launch_split_B(n, p, B, ldb, k, beta, SB, eB, st);
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+
+    ozk::GemmArgs a = make_args(m, n, p, SA, SB, 0, 0, 0);
+    a.D = D;
+    a.ldd = ldd;
+    a.eA = eA;
+    a.eB = eB;
+    int first = 1;
+    for (int g = 2; g <= k + 1; ++g) {                       // groups in ascending order (Algorithm 6, line 4)
+        for (int64_t s0 = 1; s0 <= g - 1; s0 += r) {         // chunks of at most r products (lines 8-13)
+            const int64_t s1 = (s0 + r - 1 < g - 1) ? s0 + r - 1 : g - 1;
+            a.g = g;
+            a.s0 = (int)s0;
+            a.s1 = (int)s1;
+            a.shift = 2 - beta * g;
+            a.first = first;
+            e = ozk::launch_gemm(a, 1, st);
+            if (e != hipSuccess) return OZIMMU_ERR_HIP;
+            first = 0;
+        }
+    }
+    return OZIMMU_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,42 @@
+// Internal launcher declarations (host side).  Every launcher enqueues on
+// `stream`, checks nothing (the C-ABI layer validates) and returns the HIP
+// error of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace ozk {
+
+// Step (i): row exponents + slices of A (Algorithm 8).
+hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta,
+                          int8_t* SA, int32_t* eA, hipStream_t st);
+// Step (ii): column exponents + slices of B (Algorithm 8 applied to B^T).
+hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta,
+                          int8_t* SB, int32_t* eB, hipStream_t st);
+hipError_t launch_export(int64_t rows, int64_t n, int k, const int8_t* packed, int8_t* out, hipStream_t st);
+
+struct GemmArgs {
+    const int8_t* SA;      // packed stack of A slices
+    const int8_t* SB;      // packed stack of B slices
+    int64_t strideA;       // bytes per A slice
+    int64_t strideB;       // bytes per B slice
+    int KT;                // inner tiles per slice
+    int g, s0, s1;         // chunk: sum over s = s0..s1 of A''_s B''_{g-s}
+    int64_t m, p;          // valid output extent
+    int32_t* C;            // INT32 output (mode 0)
+    int64_t ldc;
+    double* D;             // FP64 accumulate target (mode 1)
+    int64_t ldd;
+    const int32_t* eA;
+    const int32_t* eB;
+    int shift;             // 2 - beta * g
+    int first;             // D is zero: overwrite
+};
+// Step (iii) (+ (iv) when fused != 0) for one chunk (Algorithm 6).
+hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st);
+// Step (iv) alone.
+hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA,
+                             const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st);
+hipError_t launch_fill_zero_f64(int64_t m, int64_t p, double* D, int64_t ldd, hipStream_t st);
+
+}  // namespace ozk

@@ -1,0 +1,311 @@
+// Steps (i) and (ii) of the scheme: power-of-two scale exponents and INT8
+// slices, written in the packed tile-major layout of ozimmu_layout.h.
+//
+// What is computed (Algorithm 8 of the paper, with its scale mu'' = 2^e * 2^(1-beta)):
+//   e      = ceil(log2 max |x|) over a row of A / a column of B (0 if all zero)
+//   slice s (s = 1..k) of x = the integer nearest (ties to even) to
+//            remainder / 2^(e + 1 - s beta), remainder reduced accordingly.
+// How: instead of the printed (x + sigma) - sigma trick the kernels scale once,
+//   y_1 = x * 2^(beta - 1 - e)  (exact, |y_1| <= 2^(beta-1)),
+//   q_s = rint(y_s)             (v_rndne_f64: round half to even),
+//   y_{s+1} = (y_s - q_s) * 2^beta   (both exact),
+// which yields the same integers: y_s is remainder / grid_s at every step.
+// Both kernels are HBM-bound: 8 bytes read (A twice when its row does not stay
+// in cache) and k bytes written per element.
+#include "ozimmu_kernels.h"
+#include "ozimmu_layout.h"
+
+namespace {
+
+using namespace ozl;
+
+// ceil(log2 x) key of a positive finite double given as its bit pattern,
+// monotone in x so that maxima can be taken on keys:
+// key = 2 * (t + 1100) + (f != 0.5) with x = f * 2^t, f in [0.5, 1); 0 for x == 0.
+__device__ inline uint32_t exp_key(uint64_t absbits)
+{
+    if (absbits == 0) return 0u;
+    double x = __longlong_as_double((long long)absbits);
+    int t;
+    double f = frexp(x, &t);
+    return (uint32_t)(2 * (t + 1100) + (f != 0.5 ? 1 : 0));
+}
+__device__ inline int key_to_exp(uint32_t key)
+{
+    if (key == 0u) return 0;
+    int t = (int)(key >> 1) - 1100;
+    return (key & 1u) ? t : t - 1;
+}
+
+__device__ inline uint64_t abs_bits(double x)
+{
+    return (uint64_t)__double_as_longlong(x) & 0x7fffffffffffffffull;
+}
+
+__device__ inline uint64_t wave_max_u64(uint64_t v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        uint64_t o = __shfl_xor(v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// k slices of 4 consecutive inner elements, packed one dword per slice.
+// y[] enters as x * 2^(beta-1-e).  out advances by slice_stride bytes per slice.
+__device__ inline void emit_slices4(double y0, double y1, double y2, double y3, int k, double two_beta,
+                                    int8_t* out, int64_t slice_stride)
+{
+    for (int s = 0; s < k; ++s) {
+        double q0 = __builtin_rint(y0), q1 = __builtin_rint(y1), q2 = __builtin_rint(y2), q3 = __builtin_rint(y3);
+        uint32_t w = ((uint32_t)(int)q0 & 0xffu) | (((uint32_t)(int)q1 & 0xffu) << 8) |
+                     (((uint32_t)(int)q2 & 0xffu) << 16) | (((uint32_t)(int)q3 & 0xffu) << 24);
+        *reinterpret_cast<uint32_t*>(out) = w;
+        out += slice_stride;
+        y0 = (y0 - q0) * two_beta;
+        y1 = (y1 - q1) * two_beta;
+        y2 = (y2 - q2) * two_beta;
+        y3 = (y3 - q3) * two_beta;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// A: one workgroup per padded row.  Pass 1 reduces max |a_ij| over the row,
+// pass 2 re-reads the row (from L2 / Infinity Cache when it is still there)
+// and writes the k slices.  Thread t handles 4 consecutive inner elements per
+// 1024-element sweep, so a wave reads 2 KiB contiguous and writes two full
+// 128-byte lines per slice.
+// ---------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const double* __restrict__ A, int64_t lda,
+                                                 int k, int beta, int8_t* __restrict__ SA, int32_t* __restrict__ eA,
+                                                 int64_t Npad, int64_t slice_stride)
+{
+    const int64_t R = blockIdx.x;
+    const int t = threadIdx.x;
+    const int64_t KT = Npad / TILE_K;
+    __shared__ uint64_t wmax[4];
+    __shared__ int e_sh;
+
+    if (R >= m) {  // padding row: zeros in every slice
+        for (int64_t l = 4 * t; l < Npad; l += 1024)
+            for (int s = 0; s < k; ++s)
+                *reinterpret_cast<uint32_t*>(SA + s * slice_stride + packed_offset(R, l, KT)) = 0u;
+        return;
+    }
+    const double* row = A + R * lda;
+
+    uint64_t mx = 0;
+    for (int64_t l = 4 * t; l < n; l += 1024) {
+        double v[4];
+        if (VEC && l + 3 < n) {
+            double2 a = *reinterpret_cast<const double2*>(row + l);
+            double2 b = *reinterpret_cast<const double2*>(row + l + 2);
+            v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (l + j < n) ? row[l + j] : 0.0;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint64_t b = abs_bits(v[j]);
+            mx = b > mx ? b : mx;
+        }
+    }
+    mx = wave_max_u64(mx);
+    if ((t & 63) == 0) wmax[t >> 6] = mx;
+    __syncthreads();
+    if (t == 0) {
+        uint64_t a = wmax[0];
+        for (int w = 1; w < 4; ++w) a = wmax[w] > a ? wmax[w] : a;
+        int e = key_to_exp(exp_key(a));
+        e_sh = e;
+        eA[R] = e;
+    }
+    __syncthreads();
+    const int sc = beta - 1 - e_sh;
+    const double two_beta = (double)(1 << beta);
+
+    for (int64_t l = 4 * t; l < Npad; l += 1024) {
+        double v[4];
+        if (VEC && l + 3 < n) {
+            double2 a = *reinterpret_cast<const double2*>(row + l);
+            double2 b = *reinterpret_cast<const double2*>(row + l + 2);
+            v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (l + j < n) ? row[l + j] : 0.0;
+        }
+        emit_slices4(ldexp(v[0], sc), ldexp(v[1], sc), ldexp(v[2], sc), ldexp(v[3], sc), k, two_beta,
+                     SA + packed_offset(R, l, KT), slice_stride);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// B, pass 1: column maxima.  A workgroup covers 64 columns x LCH inner rows;
+// lane = column, so each wave reads 512 contiguous bytes per inner row.  The
+// per-column maximum is merged into keys[] with a 32-bit atomic max (order
+// free, hence deterministic).
+// ---------------------------------------------------------------------------
+constexpr int LCH = 512;
+
+__global__ __launch_bounds__(256) void k_colmax_B(int64_t n, int64_t p, const double* __restrict__ B, int64_t ldb,
+                                                  uint32_t* __restrict__ keys)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t j = (int64_t)blockIdx.y * 64 + lane;
+    const int64_t l0 = (int64_t)blockIdx.x * LCH;
+    const int64_t l1 = l0 + LCH < n ? l0 + LCH : n;
+    __shared__ uint64_t part[4][64];
+    uint64_t mx = 0;
+    if (j < p) {
+        for (int64_t l = l0 + w; l < l1; l += 4) {
+            uint64_t b = abs_bits(B[l * ldb + j]);
+            mx = b > mx ? b : mx;
+        }
+    }
+    part[w][lane] = mx;
+    __syncthreads();
+    if (w == 0 && j < p) {
+        for (int q = 1; q < 4; ++q) mx = part[q][lane] > mx ? part[q][lane] : mx;
+        uint32_t key = exp_key(mx);
+        if (key) atomicMax(keys + j, key);
+    }
+}
+
+__global__ void k_fill_u32(int64_t count, uint32_t* x, uint32_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) x[i] = v;
+}
+
+__global__ void k_decode_keys(int64_t count, int32_t* e)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) e[i] = key_to_exp((uint32_t)e[i]);
+}
+
+// ---------------------------------------------------------------------------
+// B, pass 2: slices, transposed so that the inner index becomes contiguous.
+// A workgroup handles 128 inner rows x 64 columns.  Reads: lane = column
+// (512 contiguous bytes per wave and inner row).  Each thread keeps its 32
+// remainders in registers, emits slices in batches of SBATCH through LDS
+// (row pitch 33 dwords: conflict-free column-wise dword stores), and the
+// batch is written out with lane = 16-byte chunk along the inner index, i.e.
+// 64 full 128-byte lines (8 KiB contiguous) per slice.
+// ---------------------------------------------------------------------------
+constexpr int SBATCH = 4;
+constexpr int PITCH = 33;  // dwords per column row in LDS (32 data + 1 pad)
+
+__global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const double* __restrict__ B, int64_t ldb,
+                                                 int k, int beta, int8_t* __restrict__ SB,
+                                                 const int32_t* __restrict__ eB, int64_t Npad, int64_t slice_stride)
+{
+    __shared__ uint32_t tile[SBATCH][64 * PITCH];
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int64_t l0 = (int64_t)blockIdx.x * TILE_K;  // inner offset of this tile
+    const int64_t j0 = (int64_t)blockIdx.y * 64;      // first column (= packed row)
+    const int64_t j = j0 + lane;
+    const int64_t KT = Npad / TILE_K;
+    const double two_beta = (double)(1 << beta);
+
+    double y[32];
+    {
+        const bool col_ok = j < p;
+        const int sc = beta - 1 - (col_ok ? eB[j] : 0);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            int64_t l = l0 + w * 32 + i;
+            double v = (col_ok && l < n) ? B[l * ldb + j] : 0.0;
+            y[i] = ldexp(v, sc);
+        }
+    }
+    // write-out mapping: 8 lanes per column row, 32 column rows per pass
+    const int oc = t & 7, orow = t >> 3;
+
+    for (int sb = 0; sb < k; sb += SBATCH) {
+        const int ns = (k - sb) < SBATCH ? (k - sb) : SBATCH;
+        for (int s = 0; s < ns; ++s) {
+#pragma unroll
+            for (int ii = 0; ii < 8; ++ii) {
+                uint32_t wv = 0;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    double q = __builtin_rint(y[4 * ii + b]);
+                    wv |= ((uint32_t)(int)q & 0xffu) << (8 * b);
+                    y[4 * ii + b] = (y[4 * ii + b] - q) * two_beta;
+                }
+                tile[s][lane * PITCH + w * 8 + ii] = wv;
+            }
+        }
+        __syncthreads();
+        for (int s = 0; s < ns; ++s) {
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                int jr = orow + 32 * pass;
+                const uint32_t* src = &tile[s][jr * PITCH + oc * 4];
+                uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
+                int8_t* dst = SB + (int64_t)(sb + s) * slice_stride + packed_offset(j0 + jr, l0 + oc * CHUNK, KT);
+                *reinterpret_cast<uint4*>(dst) = v;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Unpack: one thread per output byte, out[s][row][l].
+__global__ __launch_bounds__(256) void k_export(int64_t rows, int64_t n, int k, const int8_t* __restrict__ packed,
+                                                int8_t* __restrict__ out, int64_t KT, int64_t slice_stride)
+{
+    int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int64_t total = (int64_t)k * rows * n;
+    if (idx >= total) return;
+    int64_t l = idx % n, R = (idx / n) % rows, s = idx / (n * rows);
+    out[idx] = packed[s * slice_stride + packed_offset(R, l, KT)];
+}
+
+}  // namespace
+
+namespace ozk {
+
+hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int8_t* SA,
+                          int32_t* eA, hipStream_t st)
+{
+    const int64_t Rpad = ozl::rows_padded(m), Npad = ozl::inner_padded(n);
+    const int64_t stride = Rpad * Npad;
+    const bool vec = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 2 == 0);
+    dim3 grid((unsigned)Rpad), block(256);
+    if (vec)
+        hipLaunchKernelGGL(k_split_A<true>, grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
+    else
+        hipLaunchKernelGGL(k_split_A<false>, grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int8_t* SB,
+                          int32_t* eB, hipStream_t st)
+{
+    const int64_t Rpad = ozl::rows_padded(p), Npad = ozl::inner_padded(n);
+    const int64_t stride = Rpad * Npad;
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p,
+                       reinterpret_cast<uint32_t*>(eB), 0u);
+    dim3 gmax((unsigned)((n + LCH - 1) / LCH), (unsigned)((p + 63) / 64));
+    hipLaunchKernelGGL(k_colmax_B, gmax, dim3(256), 0, st, n, p, B, ldb, reinterpret_cast<uint32_t*>(eB));
+    hipLaunchKernelGGL(k_decode_keys, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
+    dim3 grid((unsigned)(Npad / ozl::TILE_K), (unsigned)(Rpad / 64));
+    hipLaunchKernelGGL(k_split_B, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, SB, eB, Npad, stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_export(int64_t rows, int64_t n, int k, const int8_t* packed, int8_t* out, hipStream_t st)
+{
+    const int64_t Rpad = ozl::rows_padded(rows), Npad = ozl::inner_padded(n);
+    const int64_t total = (int64_t)k * rows * n;
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_export, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, rows, n, k, packed, out,
+                       Npad / ozl::TILE_K, Rpad * Npad);
+    return hipGetLastError();
+}
+
+}  // namespace ozk

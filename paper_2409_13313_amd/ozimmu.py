@@ -1,0 +1,184 @@
+"""Thin Python binding of the C-ABI HIP library (include/ozimmu.h).
+
+Argument marshalling only: every function forwards device pointers of torch
+tensors and the current HIP stream to the entry point of the same name.  There
+is no CPU fallback: importing this module without the built library, or calling
+it without a GPU, raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libozimmu.so")
+MAX_SLICES = 20
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2409_13313_amd.build` (needs hipcc)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+_i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+
+_lib.ozimmu_status_string.argtypes = [_int]
+_lib.ozimmu_status_string.restype = ctypes.c_char_p
+_lib.ozimmu_params.argtypes = [_i64, ctypes.POINTER(_int), ctypes.POINTER(_i64)]
+_lib.ozimmu_params.restype = _int
+_lib.ozimmu_num_chunks.argtypes = [_i64, _int]
+_lib.ozimmu_num_chunks.restype = _i64
+_lib.ozimmu_slices_bytes.argtypes = [_i64, _i64, _int]
+_lib.ozimmu_slices_bytes.restype = _sz
+_lib.ozimmu_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
+_lib.ozimmu_workspace_bytes.restype = _sz
+_lib.ozimmu_dgemm.argtypes = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _vp, _sz, _vp]
+_lib.ozimmu_dgemm.restype = _int
+_lib.ozimmu_split_A.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp]
+_lib.ozimmu_split_A.restype = _int
+_lib.ozimmu_split_B.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp]
+_lib.ozimmu_split_B.restype = _int
+_lib.ozimmu_gemm_group.argtypes = [_i64, _i64, _i64, _vp, _int, _vp, _int, _int, _int, _int, _vp, _i64, _vp]
+_lib.ozimmu_gemm_group.restype = _int
+_lib.ozimmu_accumulate.argtypes = [_i64, _i64, _vp, _i64, _vp, _vp, _int, _int, _int, _vp, _i64, _vp]
+_lib.ozimmu_accumulate.restype = _int
+_lib.ozimmu_gemm_group_accumulate.argtypes = [_i64, _i64, _i64, _vp, _int, _vp, _int, _int, _int, _int,
+                                              _vp, _vp, _int, _vp, _i64, _vp]
+_lib.ozimmu_gemm_group_accumulate.restype = _int
+_lib.ozimmu_export_slices.argtypes = [_i64, _i64, _int, _vp, _vp, _vp]
+_lib.ozimmu_export_slices.restype = _int
+
+EXPORTS = ["ozimmu_status_string", "ozimmu_params", "ozimmu_num_chunks", "ozimmu_slices_bytes",
+           "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
+           "ozimmu_accumulate", "ozimmu_gemm_group_accumulate", "ozimmu_export_slices"]
+
+
+class OzimmuError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"ozimmu status {status}: {status_string(status)}")
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise OzimmuError(status)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError("tensor must live on the GPU")
+    if t.dtype != dtype:
+        raise ValueError(f"expected {dtype}, got {t.dtype}")
+    return t
+
+
+def _ld(t: torch.Tensor) -> int:
+    """Leading dimension of a 2-D row-major view (last stride must be 1)."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("expected a 2-D tensor with unit stride along rows")
+    return t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0), 1)
+
+
+def status_string(status: int) -> str:
+    return _lib.ozimmu_status_string(status).decode()
+
+
+def params(n: int) -> Tuple[int, int]:
+    beta, r = _int(0), _i64(0)
+    _check(_lib.ozimmu_params(n, ctypes.byref(beta), ctypes.byref(r)))
+    return beta.value, r.value
+
+
+def num_chunks(n: int, k: int) -> int:
+    return int(_lib.ozimmu_num_chunks(n, k))
+
+
+def slices_bytes(rows: int, n: int, k: int) -> int:
+    return int(_lib.ozimmu_slices_bytes(rows, n, k))
+
+
+def workspace_bytes(m: int, n: int, p: int, k: int) -> int:
+    return int(_lib.ozimmu_workspace_bytes(m, n, p, k))
+
+
+def alloc_workspace(m: int, n: int, p: int, k: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(workspace_bytes(m, n, p, k), 256), dtype=torch.uint8, device=device)
+
+
+def dgemm(A: torch.Tensor, B: torch.Tensor, k: int, D: Optional[torch.Tensor] = None,
+          workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """D = A B emulated with k INT8 slices on the matrix cores."""
+    _dev(A, torch.float64), _dev(B, torch.float64)
+    m, n = A.shape
+    n2, p = B.shape
+    if n != n2:
+        raise ValueError("inner dimensions differ")
+    if D is None:
+        D = torch.empty((m, p), dtype=torch.float64, device=A.device)
+    _dev(D, torch.float64)
+    if workspace is None:
+        workspace = alloc_workspace(m, n, p, k, A.device)
+    _check(_lib.ozimmu_dgemm(m, n, p, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), D.data_ptr(), _ld(D), k,
+                             workspace.data_ptr(), workspace.numel(), _stream()))
+    return D
+
+
+def split_A(A: torch.Tensor, k: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(packed slice stack, int32 row exponents) of A."""
+    _dev(A, torch.float64)
+    m, n = A.shape
+    SA = torch.empty(max(slices_bytes(m, n, k), 256), dtype=torch.int8, device=A.device)
+    eA = torch.empty(m, dtype=torch.int32, device=A.device)
+    _check(_lib.ozimmu_split_A(m, n, A.data_ptr(), _ld(A), k, SA.data_ptr(), eA.data_ptr(), _stream()))
+    return SA, eA
+
+
+def split_B(B: torch.Tensor, k: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(packed slice stack, int32 column exponents) of B."""
+    _dev(B, torch.float64)
+    n, p = B.shape
+    SB = torch.empty(max(slices_bytes(p, n, k), 256), dtype=torch.int8, device=B.device)
+    eB = torch.empty(p, dtype=torch.int32, device=B.device)
+    _check(_lib.ozimmu_split_B(n, p, B.data_ptr(), _ld(B), k, SB.data_ptr(), eB.data_ptr(), _stream()))
+    return SB, eB
+
+
+def gemm_group(m: int, n: int, p: int, SA: torch.Tensor, kA: int, SB: torch.Tensor, kB: int,
+               g: int, s0: int, s1: int, C: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if C is None:
+        C = torch.empty((m, p), dtype=torch.int32, device=SA.device)
+    _dev(C, torch.int32)
+    _check(_lib.ozimmu_gemm_group(m, n, p, SA.data_ptr(), kA, SB.data_ptr(), kB, g, s0, s1,
+                                  C.data_ptr(), _ld(C), _stream()))
+    return C
+
+
+def accumulate(C: torch.Tensor, eA: torch.Tensor, eB: torch.Tensor, beta: int, g: int, first: bool,
+               D: torch.Tensor) -> torch.Tensor:
+    _dev(C, torch.int32), _dev(D, torch.float64), _dev(eA, torch.int32), _dev(eB, torch.int32)
+    m, p = D.shape
+    _check(_lib.ozimmu_accumulate(m, p, C.data_ptr(), _ld(C), eA.data_ptr(), eB.data_ptr(), beta, g,
+                                  1 if first else 0, D.data_ptr(), _ld(D), _stream()))
+    return D
+
+
+def gemm_group_accumulate(m: int, n: int, p: int, SA: torch.Tensor, kA: int, SB: torch.Tensor, kB: int,
+                          g: int, s0: int, s1: int, eA: torch.Tensor, eB: torch.Tensor, first: bool,
+                          D: torch.Tensor) -> torch.Tensor:
+    _dev(D, torch.float64)
+    _check(_lib.ozimmu_gemm_group_accumulate(m, n, p, SA.data_ptr(), kA, SB.data_ptr(), kB, g, s0, s1,
+                                             eA.data_ptr(), eB.data_ptr(), 1 if first else 0,
+                                             D.data_ptr(), _ld(D), _stream()))
+    return D
+
+
+def export_slices(rows: int, n: int, k: int, packed: torch.Tensor) -> torch.Tensor:
+    """Canonical int8 [k][rows][n] view of a packed stack (for B: [k][p][n])."""
+    out = torch.empty((k, rows, n), dtype=torch.int8, device=packed.device)
+    _check(_lib.ozimmu_export_slices(rows, n, k, packed.data_ptr(), out.data_ptr(), _stream()))
+    return out

@@ -1,0 +1,71 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its host-only functions agree with the paper's formulas."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2409_13313_amd", "libozimmu.so")
+HEADER = os.path.join(ROOT, "include", "ozimmu.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.skip("libozimmu.so not built (run __graft_entry__.build())")
+    return ctypes.CDLL(LIB)
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ozimmu_[a-z_A-Z0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_host_functions(lib):
+    lib.ozimmu_params.argtypes = [ctypes.c_int64, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int64)]
+    lib.ozimmu_num_chunks.argtypes = [ctypes.c_int64, ctypes.c_int]
+    lib.ozimmu_num_chunks.restype = ctypes.c_int64
+    lib.ozimmu_status_string.restype = ctypes.c_char_p
+    for n in [1, 2, 3, 255, 256, 257, 1024, 5000, 16384, 65536, 2 ** 17, 2 ** 17 + 1, 2 ** 20, 2 ** 29]:
+        beta, r = ctypes.c_int(), ctypes.c_int64()
+        assert lib.ozimmu_params(n, ctypes.byref(beta), ctypes.byref(r)) == 0
+        want_beta = min(7, math.floor((31 - math.log2(n)) / 2))                   # eq. (beta)
+        want_r = max(1, 2 ** (31 - 2 * want_beta - math.ceil(math.log2(n))))     # eq. (def_r)
+        assert (beta.value, r.value) == (want_beta, want_r)
+        for k in (1, 5, 8, 14, 20):
+            w = math.ceil(k / want_r) * (k - (want_r / 2) * ((k - 1) // want_r))  # Section 5.2
+            assert lib.ozimmu_num_chunks(n, k) == w
+    assert lib.ozimmu_params(2 ** 29 + 1, None, None) < 0
+    assert lib.ozimmu_params(0, None, None) < 0
+    assert lib.ozimmu_status_string(0) == b"ok"
+    assert b"workspace" in lib.ozimmu_status_string(-4)
+
+
+def test_argument_checks_need_no_gpu(lib):
+    i64, vp = ctypes.c_int64, ctypes.c_void_p
+    lib.ozimmu_dgemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ctypes.c_int, vp, ctypes.c_size_t, vp]
+    lib.ozimmu_workspace_bytes.argtypes = [i64, i64, i64, ctypes.c_int]
+    lib.ozimmu_workspace_bytes.restype = ctypes.c_size_t
+    fake = 4096  # never dereferenced: every call below fails validation first
+    assert lib.ozimmu_dgemm(-1, 4, 4, fake, 4, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -2
+    assert lib.ozimmu_dgemm(4, 4, 4, fake, 3, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -2      # lda < n
+    assert lib.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 0, fake, 1 << 30, None) == -3      # k < 1
+    assert lib.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 21, fake, 1 << 30, None) == -3     # k > max
+    assert lib.ozimmu_dgemm(4, 4, 4, None, 4, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -1      # null A
+    assert lib.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 8, fake, 16, None) == -4           # workspace too small
+    assert lib.ozimmu_dgemm(4, 2 ** 29 + 1, 4, fake, 2 ** 30, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -2
+    assert lib.ozimmu_dgemm(0, 4, 4, None, 4, None, 4, None, 4, 8, None, 0, None) == 0             # empty: nothing to do
+    # workspace = exponents + k padded slices of A and of B
+    assert lib.ozimmu_workspace_bytes(256, 128, 256, 8) == 2 * 1024 + 2 * 8 * 256 * 128
+    assert lib.ozimmu_workspace_bytes(257, 129, 1, 3) == 1280 + 256 + 3 * 512 * 256 + 3 * 256 * 256

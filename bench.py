@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the emulated FP64 GEMM (ozimmu_dgemm) on one MI355X.
+
+A step is one pass of the whole hot path (split A, split B, every chunk GEMM
+with its fused shifted FP64 accumulation) over one pair of seeded synthetic
+matrices that are already resident in HBM.  The headline workload is the
+square case m = n = p = 16384 with k = 8 slices; the metric is effective FP64
+TFLOP/s = 2 m n p / time.  One JSON line is printed on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA peak, 5.0 POP/s
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--size", type=int, nargs="*", default=[16384], help="m n p (one value = square)")
+    ap.add_argument("--k", type=int, default=8)
+    ap.add_argument("--phi", type=float, default=0.5)
+    ap.add_argument("--extra-k", type=str, default="12,14", help="further slice counts timed with 2 steps each")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-accuracy", action="store_true")
+    ap.add_argument("--no-native", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding code); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2409_13313_amd import inputs, ozimmu
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+
+    if len(args.size) == 1:
+        m = n = p = args.size[0]
+    else:
+        m, n, p = args.size
+    k = args.k
+    beta, r = ozimmu.params(n)
+    w = ozimmu.num_chunks(n, k)
+    pairs = k * (k + 1) // 2
+
+    t0 = time.perf_counter()
+    A, B = inputs.phi_pair(m, n, p, args.phi, seed=0)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    D = torch.empty((m, p), dtype=torch.float64, device="cuda")
+    extra_ks = [int(x) for x in args.extra_k.split(",") if x.strip()] if args.extra_k else []
+    ws = ozimmu.alloc_workspace(m, n, p, max([k] + extra_ks))
+    torch.cuda.synchronize()
+    log(f"inputs {m}x{n}x{p} phi={args.phi} generated and uploaded in {time.perf_counter() - t0:.1f}s; "
+        f"beta={beta} r={r} chunks={w} pairs={pairs}")
+
+    def new_events(count):
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(count)]
+        for trio in evs:
+            for ev in trio:
+                ev.record()          # creates the HIP handle
+        torch.cuda.synchronize()
+        return evs
+
+    def timed(kk, steps, warmup):
+        evs = new_events(steps)
+        for _ in range(warmup):
+            ozimmu.dgemm(dA, dB, kk, D=D, workspace=ws)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(steps):
+            ozimmu.dgemm_profiled(dA, dB, kk, D, ws, evs[i])
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t) * 1e3 / steps
+        split_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / steps
+        gemm_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / steps
+        return wall_ms, split_ms, gemm_ms
+
+    wall_ms, split_ms, gemm_ms = timed(k, args.steps, args.warmup)
+    flops = 2.0 * m * n * p
+    value = flops / (wall_ms * 1e-3) / 1e12
+    int_ops = flops * pairs
+    gemm_tops = int_ops / (gemm_ms * 1e-3) / 1e12
+    split_bytes = 8.0 * (m * n + n * p) + float(k) * (m * n + n * p)
+    log(f"k={k}: {wall_ms:.2f} ms/step  -> {value:.1f} TFLOP/s effective; split {split_ms:.2f} ms "
+        f"({split_bytes / split_ms / 1e6:.0f} GB/s algorithmic), chunk GEMMs {gemm_ms:.2f} ms ({gemm_tops:.0f} TOP/s)")
+
+    result = {
+        "metric": "emulated DGEMM TFLOPS (2mnp/s) at n=16384 vs k; INT8 MFMA utilisation %",
+        "value": round(value, 3),
+        "unit": "TFLOP/s (effective FP64, 2mnp/t)",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8 products, int32 chunk sums, f64 accumulation",
+        "data": "synthetic",
+        "config": {"workload": f"square FP64 GEMM m=n=p={n}, phi={args.phi}, seed 0, k={k} slices (ozIMMU_H)"
+                   if m == n == p else f"FP64 GEMM m={m} n={n} p={p}, phi={args.phi}, seed 0, k={k} slices",
+                   "m": m, "n": n, "p": p, "k": k, "phi": args.phi, "beta": beta, "r": r,
+                   "int8_products": pairs, "fp64_addends": w},
+        "phases_ms": {"split_A_and_B": round(split_ms, 4), "chunk_gemm_with_fused_accumulation": round(gemm_ms, 4)},
+        "int8_mfma_utilisation_pct": round(100.0 * gemm_tops / PEAK_INT8_TOPS, 2),
+        "roofline": {
+            "kernel": "k_gemm<1> (INT8 MFMA chunk GEMM + fused FP64 accumulation)",
+            "bound": "mfma",
+            "achieved": round(gemm_tops, 2),
+            "peak": PEAK_INT8_TOPS,
+            "unit": "TOP/s",
+            "frac": round(gemm_tops / PEAK_INT8_TOPS, 4),
+            "launches_per_step": w,
+            "avg_launch_ms": round(gemm_ms / w, 4),
+            "ops_per_launch": int_ops / w,
+            "traffic": None,
+        },
+        "split_hbm": {"algorithmic_GBps": round(split_bytes / split_ms / 1e6, 1), "peak_GBps": PEAK_HBM_GBS,
+                      "frac": round(split_bytes / split_ms / 1e6 / PEAK_HBM_GBS, 4)},
+    }
+
+    per_k = {str(k): round(value, 3)}
+    for kk in extra_ks:
+        wms, sms, gms = timed(kk, 2, 1)
+        per_k[str(kk)] = round(flops / (wms * 1e-3) / 1e12, 3)
+        log(f"k={kk}: {wms:.2f} ms/step -> {per_k[str(kk)]:.1f} TFLOP/s (split {sms:.2f} ms, GEMMs {gms:.2f} ms, "
+            f"{flops * kk * (kk + 1) / 2 / gms / 1e9:.0f} TOP/s)")
+    result["tflops_vs_k"] = per_k
+
+    if not args.no_native:
+        for _ in range(1):
+            torch.mm(dA, dB, out=D)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        reps = 2
+        for _ in range(reps):
+            torch.mm(dA, dB, out=D)
+        torch.cuda.synchronize()
+        nat_ms = (time.perf_counter() - t) * 1e3 / reps
+        result["native_fp64_dgemm"] = {"ms": round(nat_ms, 3), "tflops": round(flops / nat_ms / 1e9, 3),
+                                       "what": "torch.mm on the same float64 device buffers"}
+        log(f"native FP64 torch.mm: {nat_ms:.2f} ms -> {flops / nat_ms / 1e9:.1f} TFLOP/s")
+
+    if not (args.no_accuracy and args.no_cpu_baseline):
+        import oracle
+
+    if not args.no_accuracy:
+        # error against a compensated (Dot2) product on sampled rows / columns, relative to (|A||B|)_ij
+        S = min(96, m, p)
+        I = inputs.sample_indices(m, S, seed=1)
+        J = inputs.sample_indices(p, S, seed=2)
+        Asub, Bsub = np.ascontiguousarray(A[I]), np.ascontiguousarray(B[:, J])
+        hi, lo = oracle.dot2_gemm(Asub, Bsub)
+        absab = np.abs(Asub) @ np.abs(Bsub)
+        tI, tJ = torch.from_numpy(I).cuda(), torch.from_numpy(J).cuda()
+        acc = {}
+        for kk in [k] + extra_ks:
+            ozimmu.dgemm(dA, dB, kk, D=D, workspace=ws)
+            got = D[tI][:, tJ].cpu().numpy()
+            acc[f"ozimmu_k{kk}"] = float((np.abs((got - hi) - lo) / absab).max())
+        if not args.no_native:
+            torch.mm(dA, dB, out=D)
+            got = D[tI][:, tJ].cpu().numpy()
+            acc["native_fp64"] = float((np.abs((got - hi) - lo) / absab).max())
+        result["accuracy_max_err_over_absA_absB"] = {"sample": f"{S}x{S} entries vs Dot2", **acc}
+        log("accuracy:", acc)
+
+    if not args.no_cpu_baseline:
+        # the oracle, untuned, on a bounded sample of the same workload: rows I and columns J of D
+        S0 = min(64, m, p)
+        I0 = inputs.sample_indices(m, S0, seed=3)
+        J0 = inputs.sample_indices(p, S0, seed=4)
+        t = time.perf_counter()
+        oracle.dgemm_sub(A, B, k, I0, J0)
+        t_probe = time.perf_counter() - t
+        # cost ~ S^2 (products) + S (split); aim at about 15 s
+        S = int(min(m, p, max(S0, S0 * (15.0 / max(t_probe, 1e-3)) ** 0.5)))
+        S = max(S0, min(S, 1024))
+        I1 = inputs.sample_indices(m, S, seed=5)
+        J1 = inputs.sample_indices(p, S, seed=6)
+        t = time.perf_counter()
+        oracle.dgemm_sub(A, B, k, I1, J1)
+        t_cpu = time.perf_counter() - t
+        cpu_tflops = 2.0 * S * S * n / t_cpu / 1e12
+        result["cpu_baseline"] = {"value": round(cpu_tflops, 6), "unit": "TFLOP/s (effective FP64, 2mnp/t)",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": f"D[I,J] with |I|=|J|={S} of the {m}x{n}x{p} k={k} workload "
+                                            f"({t_cpu:.1f} s of CPU time; full inner dimension n={n})"}
+        log(f"cpu oracle: {S}x{S} sample in {t_cpu:.1f}s -> {cpu_tflops * 1e3:.2f} GFLOP/s effective on "
+            f"{oracle.num_threads()} threads")
+
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

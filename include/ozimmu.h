@@ -76,6 +76,18 @@ int ozimmu_dgemm(int64_t m, int64_t n, int64_t p,
                  double *D, int64_t ldd,
                  int k, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ozimmu_dgemm with phase markers for profiling: caller-created HIP events
+ * (hipEvent_t passed as void*, any may be NULL) are recorded on `stream`
+ * before the first kernel (events[0]), after the split kernels of steps (i),
+ * (ii) (events[1]) and after the last chunk kernel of steps (iii), (iv)
+ * (events[2]).  events == NULL behaves exactly like ozimmu_dgemm. */
+int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p,
+                          const double *A, int64_t lda,
+                          const double *B, int64_t ldb,
+                          double *D, int64_t ldd,
+                          int k, void *workspace, size_t workspace_bytes, void *stream,
+                          void *const *events);
+
 /* ---- phase-level entry points (the same kernels ozimmu_dgemm runs) ---- */
 
 /* Steps (i): eA[i] = ceil(log2 max_j |a_ij|) (0 for an all-zero row) and the k

@@ -182,6 +182,13 @@ int ozimmu_export_slices(int64_t rows, int64_t n, int k, const int8_t* packed, i
 int ozimmu_dgemm(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
                  double* D, int64_t ldd, int k, void* workspace, size_t workspace_bytes, void* stream)
 {
+    return ozimmu_dgemm_profiled(m, n, p, A, lda, B, ldb, D, ldd, k, workspace, workspace_bytes, stream, nullptr);
+}
+
+int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B,
+                          int64_t ldb, double* D, int64_t ldd, int k, void* workspace, size_t workspace_bytes,
+                          void* stream, void* const* events)
+{
     if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
     if (lda < n || ldb < p || ldd < p) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
@@ -204,9 +211,16 @@ int ozimmu_dgemm(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, 
     ws += ozimmu_slices_bytes(m, n, k);
     int8_t* SB = reinterpret_cast<int8_t*>(ws);
 
-    hipError_t e = ozk::launch_split_A(m, n, A, lda, k, beta, SA, eA, st);
+    auto mark = [&](int i) -> hipError_t {
+        return (events && events[i]) ? hipEventRecord((hipEvent_t)events[i], st) : hipSuccess;
+    };
+    hipError_t e = mark(0);
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+    e = ozk::launch_split_A(m, n, A, lda, k, beta, SA, eA, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     e = ozk::launch_split_B(n, p, B, ldb, k, beta, SB, eB, st);
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+    e = mark(1);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
     ozk::GemmArgs a = make_args(m, n, p, SA, SB, 0, 0, 0);
@@ -228,7 +242,7 @@ int ozimmu_dgemm(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, 
             first = 0;
         }
     }
-    return OZIMMU_OK;
+    return hip_status(mark(2));
 }
 
 }  // extern "C"

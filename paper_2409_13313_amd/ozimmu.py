@@ -35,6 +35,9 @@ _lib.ozimmu_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
 _lib.ozimmu_workspace_bytes.restype = _sz
 _lib.ozimmu_dgemm.argtypes = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _vp, _sz, _vp]
 _lib.ozimmu_dgemm.restype = _int
+_lib.ozimmu_dgemm_profiled.argtypes = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _vp, _sz, _vp,
+                                       ctypes.POINTER(_vp)]
+_lib.ozimmu_dgemm_profiled.restype = _int
 _lib.ozimmu_split_A.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_split_A.restype = _int
 _lib.ozimmu_split_B.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp]
@@ -50,7 +53,7 @@ _lib.ozimmu_export_slices.argtypes = [_i64, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_export_slices.restype = _int
 
 EXPORTS = ["ozimmu_status_string", "ozimmu_params", "ozimmu_num_chunks", "ozimmu_slices_bytes",
-           "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
+           "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_dgemm_profiled", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
            "ozimmu_accumulate", "ozimmu_gemm_group_accumulate", "ozimmu_export_slices"]
 
 
@@ -125,6 +128,20 @@ def dgemm(A: torch.Tensor, B: torch.Tensor, k: int, D: Optional[torch.Tensor] = 
         workspace = alloc_workspace(m, n, p, k, A.device)
     _check(_lib.ozimmu_dgemm(m, n, p, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), D.data_ptr(), _ld(D), k,
                              workspace.data_ptr(), workspace.numel(), _stream()))
+    return D
+
+
+def dgemm_profiled(A: torch.Tensor, B: torch.Tensor, k: int, D: torch.Tensor, workspace: torch.Tensor,
+                   events) -> torch.Tensor:
+    """dgemm that records three torch.cuda.Event objects (start, after split,
+    end) on the current stream; the events must have been recorded once before
+    so that their HIP handles exist."""
+    _dev(A, torch.float64), _dev(B, torch.float64), _dev(D, torch.float64)
+    m, n = A.shape
+    p = B.shape[1]
+    handles = (_vp * 3)(*[_vp(ev.cuda_event) if ev is not None else _vp(None) for ev in events])
+    _check(_lib.ozimmu_dgemm_profiled(m, n, p, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), D.data_ptr(), _ld(D), k,
+                                      workspace.data_ptr(), workspace.numel(), _stream(), handles))
     return D
 
 

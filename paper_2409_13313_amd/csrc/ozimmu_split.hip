@@ -71,34 +71,31 @@ __device__ inline void emit_slices4(double y0, double y1, double y2, double y3, 
 }
 
 // ---------------------------------------------------------------------------
-// A: one workgroup per padded row.  Pass 1 reduces max |a_ij| over the row,
+// A: one wave per padded row, four consecutive rows per workgroup (their 64-byte
+// segments are adjacent in a packed tile, so the workgroup's stores fill whole
+// 128-byte lines).  Pass 1 reduces max |a_ij| over the row inside the wave,
 // pass 2 re-reads the row (from L2 / Infinity Cache when it is still there)
-// and writes the k slices.  Thread t handles 4 consecutive inner elements per
-// 1024-element sweep, so a wave reads 2 KiB contiguous and writes two full
-// 128-byte lines per slice.
+// and writes the k slices.  A lane handles 4 consecutive inner elements per
+// 256-element sweep: the wave reads 2 KiB contiguous per sweep.
 // ---------------------------------------------------------------------------
 template <bool VEC>
 __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const double* __restrict__ A, int64_t lda,
                                                  int k, int beta, int8_t* __restrict__ SA, int32_t* __restrict__ eA,
                                                  int64_t Npad, int64_t slice_stride)
 {
-    const int64_t R = blockIdx.x;
-    const int t = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int64_t R = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t KT = Npad / TILE_K;
-    __shared__ uint64_t wmax[4];
-    __shared__ int e_sh;
 
     if (R >= m) {  // padding row: zeros in every slice
-        for (int64_t l = 4 * t; l < Npad; l += 1024)
+        for (int64_t l = 4 * lane; l < Npad; l += 256)
             for (int s = 0; s < k; ++s)
                 *reinterpret_cast<uint32_t*>(SA + s * slice_stride + packed_offset(R, l, KT)) = 0u;
         return;
     }
     const double* row = A + R * lda;
 
-    uint64_t mx = 0;
-    for (int64_t l = 4 * t; l < n; l += 1024) {
-        double v[4];
+    auto load4 = [&](int64_t l, double* v) {
         if (VEC && l + 3 < n) {
             double2 a = *reinterpret_cast<const double2*>(row + l);
             double2 b = *reinterpret_cast<const double2*>(row + l + 2);
@@ -107,6 +104,12 @@ __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const dou
 #pragma unroll
             for (int j = 0; j < 4; ++j) v[j] = (l + j < n) ? row[l + j] : 0.0;
         }
+    };
+
+    uint64_t mx = 0;
+    for (int64_t l = 4 * lane; l < n; l += 256) {
+        double v[4];
+        load4(l, v);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             uint64_t b = abs_bits(v[j]);
@@ -114,29 +117,14 @@ __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const dou
         }
     }
     mx = wave_max_u64(mx);
-    if ((t & 63) == 0) wmax[t >> 6] = mx;
-    __syncthreads();
-    if (t == 0) {
-        uint64_t a = wmax[0];
-        for (int w = 1; w < 4; ++w) a = wmax[w] > a ? wmax[w] : a;
-        int e = key_to_exp(exp_key(a));
-        e_sh = e;
-        eA[R] = e;
-    }
-    __syncthreads();
-    const int sc = beta - 1 - e_sh;
+    const int e = key_to_exp(exp_key(mx));
+    if (lane == 0) eA[R] = e;
+    const int sc = beta - 1 - e;
     const double two_beta = (double)(1 << beta);
 
-    for (int64_t l = 4 * t; l < Npad; l += 1024) {
+    for (int64_t l = 4 * lane; l < Npad; l += 256) {
         double v[4];
-        if (VEC && l + 3 < n) {
-            double2 a = *reinterpret_cast<const double2*>(row + l);
-            double2 b = *reinterpret_cast<const double2*>(row + l + 2);
-            v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y;
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = (l + j < n) ? row[l + j] : 0.0;
-        }
+        load4(l, v);
         emit_slices4(ldexp(v[0], sc), ldexp(v[1], sc), ldexp(v[2], sc), ldexp(v[3], sc), k, two_beta,
                      SA + packed_offset(R, l, KT), slice_stride);
     }
@@ -193,7 +181,7 @@ __global__ void k_decode_keys(int64_t count, int32_t* e)
 // remainders in registers, emits slices in batches of SBATCH through LDS
 // (row pitch 33 dwords: conflict-free column-wise dword stores), and the
 // batch is written out with lane = 16-byte chunk along the inner index, i.e.
-// 64 full 128-byte lines (8 KiB contiguous) per slice.
+// full 128-byte lines (two adjacent rows of a tile) per slice.
 // ---------------------------------------------------------------------------
 constexpr int SBATCH = 4;
 constexpr int PITCH = 33;  // dwords per column row in LDS (32 data + 1 pad)
@@ -204,7 +192,7 @@ __global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const dou
 {
     __shared__ uint32_t tile[SBATCH][64 * PITCH];
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-    const int64_t l0 = (int64_t)blockIdx.x * TILE_K;  // inner offset of this tile
+    const int64_t l0 = (int64_t)blockIdx.x * KPAD;  // inner offset of this block (128 inner rows)
     const int64_t j0 = (int64_t)blockIdx.y * 64;      // first column (= packed row)
     const int64_t j = j0 + lane;
     const int64_t KT = Npad / TILE_K;
@@ -275,7 +263,7 @@ hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, in
     const int64_t Rpad = ozl::rows_padded(m), Npad = ozl::inner_padded(n);
     const int64_t stride = Rpad * Npad;
     const bool vec = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 2 == 0);
-    dim3 grid((unsigned)Rpad), block(256);
+    dim3 grid((unsigned)(Rpad / 4)), block(256);
     if (vec)
         hipLaunchKernelGGL(k_split_A<true>, grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
     else
@@ -293,7 +281,7 @@ hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, in
     dim3 gmax((unsigned)((n + LCH - 1) / LCH), (unsigned)((p + 63) / 64));
     hipLaunchKernelGGL(k_colmax_B, gmax, dim3(256), 0, st, n, p, B, ldb, reinterpret_cast<uint32_t*>(eB));
     hipLaunchKernelGGL(k_decode_keys, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
-    dim3 grid((unsigned)(Npad / ozl::TILE_K), (unsigned)(Rpad / 64));
+    dim3 grid((unsigned)(Npad / ozl::KPAD), (unsigned)(Rpad / 64));
     hipLaunchKernelGGL(k_split_B, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, SB, eB, Npad, stride);
     return hipGetLastError();
 }

@@ -33,6 +33,10 @@ extern "C" {
 #endif
 
 #define OZIMMU_MAX_SLICES 20
+/* Bytes of device scratch the chunk GEMM entry points need (scheduling counters
+ * of the persistent kernel; contents on entry are irrelevant).  Calls that may
+ * run at the same time must not share a scratch area. */
+#define OZIMMU_SCRATCH_BYTES 512
 
 enum {
     OZIMMU_OK = 0,
@@ -114,12 +118,13 @@ int ozimmu_split_B(int64_t n, int64_t p, const double *B, int64_t ldb, int k,
  * s0 == s1 gives the single pair product A''_s B''_{g-s} of Algorithm 4.
  *   SA, SB  device, packed slice stacks holding kA / kB slices.
  *   C       device, int32 m x p row-major, ldc >= p, overwritten.
+ *   scratch device, OZIMMU_SCRATCH_BYTES bytes, 4-byte aligned.
  * Requires 1 <= s0 <= s1 <= kA and 1 <= g - s1, g - s0 <= kB.  The caller is
  * responsible for s1 - s0 + 1 <= r (no INT32 overflow, Section 5.2). */
 int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p,
                       const int8_t *SA, int kA, const int8_t *SB, int kB,
                       int g, int s0, int s1,
-                      int32_t *C, int64_t ldc, void *stream);
+                      int32_t *C, int64_t ldc, void *scratch, void *stream);
 
 /* Step (iv) for one chunk: D <- D + 2^(2 - beta g) diag(2^eA) FP64(C'') diag(2^eB)
  *                                              [Algorithm 6, line 11].
@@ -131,12 +136,12 @@ int ozimmu_accumulate(int64_t m, int64_t p, const int32_t *C, int64_t ldc,
 
 /* Steps (iii)+(iv) for one chunk in one kernel: the INT32 chunk sum stays in
  * registers and is converted, scaled and added to D in the GEMM epilogue
- * (this is what ozimmu_dgemm launches once per chunk). */
+ * (ozimmu_dgemm runs the same kernel once, over every chunk of the schedule). */
 int ozimmu_gemm_group_accumulate(int64_t m, int64_t n, int64_t p,
                                  const int8_t *SA, int kA, const int8_t *SB, int kB,
                                  int g, int s0, int s1,
                                  const int32_t *eA, const int32_t *eB, int first,
-                                 double *D, int64_t ldd, void *stream);
+                                 double *D, int64_t ldd, void *scratch, void *stream);
 
 /* Unpack a packed slice stack into the canonical order out[s][row][l]
  * (int8, k x rows x n, dense): for A that is A''_s[i][l]; for B it is

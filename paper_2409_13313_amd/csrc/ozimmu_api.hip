@@ -5,6 +5,7 @@
 #include "../../include/ozimmu.h"
 #include "ozimmu_kernels.h"
 #include "ozimmu_layout.h"
+#include <cstdlib>
 
 namespace {
 
@@ -43,7 +44,15 @@ int check_gemm_args(int64_t m, int64_t n, int64_t p, const void* SA, int kA, con
     return OZIMMU_OK;
 }
 
-ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, int g, int s0, int s1)
+int env_int(const char* name, int dflt)
+{
+    const char* v = getenv(name);
+    return v ? atoi(v) : dflt;
+}
+
+// single chunk (s0 > 0): g, s = s0..s1; full schedule (s0 == 0): g = g_lo..g_hi, chunks of r
+ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, int g_lo, int g_hi,
+                        int r, int s0, int s1, void* scratch)
 {
     ozk::GemmArgs a{};
     a.SA = SA;
@@ -51,11 +60,19 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
     a.strideA = ozl::slice_bytes(m, n);
     a.strideB = ozl::slice_bytes(p, n);
     a.KT = (int)(ozl::inner_padded(n) / ozl::TILE_K);
-    a.g = g;
+    a.g_lo = g_lo;
+    a.g_hi = g_hi;
+    a.r = r;
     a.s0 = s0;
     a.s1 = s1;
     a.m = m;
     a.p = p;
+    a.beta = beta_of(n);
+    a.sync = static_cast<unsigned*>(scratch);
+    static const int sync_every = env_int("OZIMMU_SYNC_EVERY", 0);
+    static const int spin_limit = env_int("OZIMMU_SPIN_LIMIT", 64);
+    a.sync_every = (sync_every > 0 && (sync_every & (sync_every - 1)) == 0) ? sync_every : 0;
+    a.spin_limit = spin_limit;
     return a;
 }
 
@@ -103,7 +120,8 @@ size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k)
 size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k)
 {
     if (m < 0 || n < 0 || p < 0 || k < 0) return 0;
-    return (size_t)(align256(4 * m) + align256(4 * p)) + ozimmu_slices_bytes(m, n, k) + ozimmu_slices_bytes(p, n, k);
+    return (size_t)(align256(OZIMMU_SCRATCH_BYTES) + align256(4 * m) + align256(4 * p)) +
+           ozimmu_slices_bytes(m, n, k) + ozimmu_slices_bytes(p, n, k);
 }
 
 int ozimmu_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int8_t* SA, int32_t* eA, void* stream)
@@ -127,14 +145,15 @@ int ozimmu_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, in
 }
 
 int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA, const int8_t* SB, int kB, int g,
-                      int s0, int s1, int32_t* C, int64_t ldc, void* stream)
+                      int s0, int s1, int32_t* C, int64_t ldc, void* scratch, void* stream)
 {
     int st = check_gemm_args(m, n, p, SA, kA, SB, kB, g, s0, s1);
     if (st != OZIMMU_OK) return st;
     if (ldc < p) return OZIMMU_ERR_DIM;
     if (m == 0 || p == 0 || n == 0) return OZIMMU_OK;
-    if (!C) return OZIMMU_ERR_NULL;
-    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, s0, s1);
+    if (!C || !scratch) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(scratch) % 4) return OZIMMU_ERR_WORKSPACE;
+    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch);
     a.C = C;
     a.ldc = ldc;
     return hip_status(ozk::launch_gemm(a, 0, (hipStream_t)stream));
@@ -153,19 +172,19 @@ int ozimmu_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const
 
 int ozimmu_gemm_group_accumulate(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA, const int8_t* SB, int kB,
                                  int g, int s0, int s1, const int32_t* eA, const int32_t* eB, int first, double* D,
-                                 int64_t ldd, void* stream)
+                                 int64_t ldd, void* scratch, void* stream)
 {
     int st = check_gemm_args(m, n, p, SA, kA, SB, kB, g, s0, s1);
     if (st != OZIMMU_OK) return st;
     if (ldd < p) return OZIMMU_ERR_DIM;
     if (m == 0 || p == 0 || n == 0) return OZIMMU_OK;
-    if (!eA || !eB || !D) return OZIMMU_ERR_NULL;
-    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, s0, s1);
+    if (!eA || !eB || !D || !scratch) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(scratch) % 4) return OZIMMU_ERR_WORKSPACE;
+    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch);
     a.D = D;
     a.ldd = ldd;
     a.eA = eA;
     a.eB = eB;
-    a.shift = 2 - beta_of(n) * g;
     a.first = first;
     return hip_status(ozk::launch_gemm(a, 1, (hipStream_t)stream));
 }
@@ -203,6 +222,8 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p, const double* A, int6
     const int beta = beta_of(n);
     const int64_t r = r_of(n, beta);
     char* ws = static_cast<char*>(workspace);
+    void* scratch = ws;
+    ws += align256(OZIMMU_SCRATCH_BYTES);
     int32_t* eA = reinterpret_cast<int32_t*>(ws);
     ws += align256(4 * m);
     int32_t* eB = reinterpret_cast<int32_t*>(ws);
@@ -223,25 +244,17 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p, const double* A, int6
     e = mark(1);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
-    ozk::GemmArgs a = make_args(m, n, p, SA, SB, 0, 0, 0);
+    // one persistent launch runs the whole schedule of Algorithm 6: groups g = 2..k+1 in ascending
+    // order, each in chunks of at most r consecutive s, one fused FP64 accumulation per chunk
+    const int r_eff = (int)(r < k ? r : k);
+    ozk::GemmArgs a = make_args(m, n, p, SA, SB, 2, k + 1, r_eff, 0, 0, scratch);
     a.D = D;
     a.ldd = ldd;
     a.eA = eA;
     a.eB = eB;
-    int first = 1;
-    for (int g = 2; g <= k + 1; ++g) {                       // groups in ascending order (Algorithm 6, line 4)
-        for (int64_t s0 = 1; s0 <= g - 1; s0 += r) {         // chunks of at most r products (lines 8-13)
-            const int64_t s1 = (s0 + r - 1 < g - 1) ? s0 + r - 1 : g - 1;
-            a.g = g;
-            a.s0 = (int)s0;
-            a.s1 = (int)s1;
-            a.shift = 2 - beta * g;
-            a.first = first;
-            e = ozk::launch_gemm(a, 1, st);
-            if (e != hipSuccess) return OZIMMU_ERR_HIP;
-            first = 0;
-        }
-    }
+    a.first = 1;
+    e = ozk::launch_gemm(a, 1, st);
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
     return hip_status(mark(2));
 }
 

@@ -40,19 +40,12 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // A tile + B tile = 32 KiB
 constexpr int NLOAD = TILE_BYTES / (256 * 16);    // 16-byte copies per thread and operand tile = 4
 
-// Map the linear workgroup id to an output tile so that (a) the workgroups
-// resident on one XCD (ids congruent mod 8 land on the same XCD) own a
-// contiguous range of tiles and (b) consecutive tiles of that range form
-// GROUP-row bands walked column by column, which keeps the operand working
-// set of the 32 CUs of an XCD inside its private 4 MiB L2.
+// Linear tile order: bands of GROUP tile rows, each walked column by column, so
+// that 32 consecutive tiles form an 8 x 4 patch (8 A tiles + 4 B tiles per stage).
 constexpr int NXCD = 8;
 constexpr int GROUP = 8;
-__device__ inline void tile_of_block(int bid, int TM, int TP, int& tm, int& tp)
+__device__ inline void tile_of_linear(int lin, int TM, int TP, int& tm, int& tp)
 {
-    const int T = TM * TP;
-    const int xcd = bid % NXCD, idx = bid / NXCD;
-    const int base = T / NXCD, rem = T % NXCD;
-    const int lin = xcd * base + (xcd < rem ? xcd : rem) + idx;
     const int width = GROUP * TP;
     const int band = lin / width;
     const int first = band * GROUP;
@@ -77,6 +70,30 @@ __device__ inline void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Soft barrier between the workgroups of one XCD ("team").  They share one L2 and
+// stream the same A / B tiles; the L2 holds only some twenty stages of the team's
+// working set, so operand reuse in L2 lives on the team advancing in lockstep.
+// Nothing but timing depends on it: a workgroup that has waited `spin_limit`
+// polls goes on alone, so the barrier always ends.  Called by every thread;
+// thread 0 arrives and polls, the rest meet it at the next s_barrier.
+__device__ inline void team_arrive_and_wait(unsigned* ctr, unsigned target, int spin_limit)
+{
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int i = 0; i < spin_limit; ++i) {
+            if (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+    }
+}
+
+// Persistent kernel: gridDim.x workgroups (one per CU), workgroup b belongs to
+// XCD b % 8 (hardware dispatch order) and is member b / 8 of that XCD's team.
+// The tiles of the output are split into 8 contiguous ranges, one per XCD, in
+// band order (GROUP tile rows walked column by column); in round q the team
+// works on tiles q*team .. q*team+team-1 of its range, i.e. an 8 x 4 patch
+// whose A and B tiles are shared through the XCD's L2.  For its tile a
+// workgroup runs every chunk of the schedule in the order of Algorithm 6.
 template <int MODE, int NS>
 __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
 {
@@ -85,37 +102,14 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int lr = lane & 31, lh = lane >> 5;
-    int tm, tp;
-    tile_of_block(blockIdx.x, TM, TP, tm, tp);
 
     const int KT = a.KT;
-    const int nstage = (a.s1 - a.s0 + 1) * KT;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
     const uint32_t voff = (uint32_t)t * 16u;
     const uint32_t m0_wave = lds_base + (uint32_t)wave * 1024u;
-
-    // pointers of the next stage to copy (advanced stage by stage; they stop at the last stage,
-    // so the copies issued past the end re-read valid memory into buffers nobody reads)
-    int cp_kt = 0, cp_it = 0;
-    const int8_t* cp_a = a.SA + (int64_t)(a.s0 - 1) * a.strideA + (int64_t)tm * KT * TILE_BYTES;
-    const int8_t* cp_b = a.SB + (int64_t)(a.g - a.s0 - 1) * a.strideB + (int64_t)tp * KT * TILE_BYTES;
-    // moving on to the next slice pair of the chunk: A slice s -> s+1, B slice g-s -> g-s-1, inner tile KT-1 -> 0
+    // moving on to the next slice pair of a chunk: A slice s -> s+1, B slice g-s -> g-s-1, inner tile KT-1 -> 0
     const int64_t wrapA = a.strideA - (int64_t)(KT - 1) * TILE_BYTES;
     const int64_t wrapB = -a.strideB - (int64_t)(KT - 1) * TILE_BYTES;
-    auto issue_copy = [&](int buf) {
-        const uint32_t m0 = m0_wave + (uint32_t)buf * STAGE_BYTES;
-#pragma unroll
-        for (int j = 0; j < NLOAD; ++j) copy16_to_lds(m0 + j * 4096, voff, cp_a + j * 4096);
-#pragma unroll
-        for (int j = 0; j < NLOAD; ++j) copy16_to_lds(m0 + TILE_BYTES + j * 4096, voff, cp_b + j * 4096);
-        // branch-free advance (all scalar)
-        const bool adv = cp_it + 1 < nstage;
-        const bool wrap = adv && (cp_kt + 1 == KT);
-        cp_it += adv ? 1 : 0;
-        cp_kt = wrap ? 0 : cp_kt + (adv ? 1 : 0);
-        cp_a += wrap ? wrapA : (adv ? (int64_t)TILE_BYTES : 0);
-        cp_b += wrap ? wrapB : (adv ? (int64_t)TILE_BYTES : 0);
-    };
 
     // per-lane fragment offsets inside a stage: row = w*128 + i*32 + lane%32, logical chunk = kk*2 + lane/32;
     // i*32 rows = i*2048 bytes and does not change the swizzle, so only kk needs its own offset
@@ -129,94 +123,181 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
         }
     }
     typedef __attribute__((address_space(3))) const v4i* lds_v4i_ptr;
-    auto fetch = [&](v4i* fa, v4i* fb, int buf, int kk) {
-        const uint32_t pa = fragA[kk] + (uint32_t)buf * STAGE_BYTES;
-        const uint32_t pb = fragB[kk] + (uint32_t)buf * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            fa[i] = *(lds_v4i_ptr)(uintptr_t)(pa + i * 2048);
-            fb[i] = *(lds_v4i_ptr)(uintptr_t)(pb + i * 2048);
-        }
-    };
+    // team geometry
+    const int nwg = gridDim.x, bid = blockIdx.x;
+    const int xcd = bid % NXCD, member = bid / NXCD;
+    const int team = nwg / NXCD + (xcd < nwg % NXCD ? 1 : 0);
+    const int T = TM * TP;
+    const int tiles_base = T / NXCD, tiles_rem = T % NXCD;
+    const int range_off = xcd * tiles_base + (xcd < tiles_rem ? xcd : tiles_rem);
+    const int range_cnt = tiles_base + (xcd < tiles_rem ? 1 : 0);
+    unsigned* const sync_ctr = a.sync + xcd * 16;
+    unsigned sync_target = 0;
+    // sync_every is a power of two (or 0: never inside a chunk)
+    const int sync_mask = a.sync_every > 0 ? a.sync_every - 1 : 0x7fffffff;
 
-    v16i acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (v16i){0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    for (int local = member; local < range_cnt; local += team) {
+        const int round_first = local - member;
+        const unsigned participants = (unsigned)((range_cnt - round_first) < team ? (range_cnt - round_first) : team);
+        int tm, tp;
+        tile_of_linear(range_off + local, TM, TP, tm, tp);
+        const int64_t row0 = (int64_t)tm * 256 + wm * 128;
+        const int64_t col0 = (int64_t)tp * 256 + wn * 128;
+        int first = a.first;
 
-    // MFMAs of one k-step for A row tiles i0 .. i0+1 (8 of the 16)
-    auto math_half = [&](const v4i* fa, const v4i* fb, int i0) {
-#pragma unroll
-        for (int i = i0; i < i0 + 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    };
-    // ask the scheduler for the pattern 1 LDS read : 2 MFMA over a k-step (8 reads, 16 MFMAs)
-    auto interleave = [&]() {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // MFMA
-        }
-    };
+        for (int g = a.g_lo; g <= a.g_hi; ++g) {
+            const int s_lo = a.s0 > 0 ? a.s0 : 1;
+            const int s_hi = a.s0 > 0 ? a.s1 : g - 1;
+            for (int c0 = s_lo; c0 <= s_hi; c0 += a.r) {
+                const int c1 = (c0 + a.r - 1 < s_hi) ? c0 + a.r - 1 : s_hi;  // chunk: s = c0..c1
+                const int nstage = (c1 - c0 + 1) * KT;
 
-    v4i fa0[4], fb0[4], fa1[4], fb1[4];
+                // Copy cursors: tile pointers of the next stage to copy, one per operand (the B half of a
+                // stage is issued half an iteration after its A half).  They stop at the last stage, so the
+                // copies issued past the end re-read valid memory into buffers nobody reads.
+                struct Cursor {
+                    const int8_t* ptr;
+                    int kt, it;
+                };
+                Cursor ca = {a.SA + (int64_t)(c0 - 1) * a.strideA + (int64_t)tm * rowblock_bytes(KT), 0, 0};
+                Cursor cb = {a.SB + (int64_t)(g - c0 - 1) * a.strideB + (int64_t)tp * rowblock_bytes(KT), 0, 0};
+                auto advance = [&](Cursor& c, int64_t wrap_step) {  // branch-free, all scalar
+                    const bool adv = c.it + 1 < nstage;
+                    const bool wrap = adv && (c.kt + 1 == KT);
+                    c.it += adv ? 1 : 0;
+                    c.kt = wrap ? 0 : c.kt + (adv ? 1 : 0);
+                    c.ptr += wrap ? wrap_step : (adv ? (int64_t)TILE_BYTES : 0);
+                };
+                // one 16-byte-per-lane copy (quarter q of a tile) of the A / B tile under the cursor into ring buffer `buf`
+                auto copy_a = [&](int buf, int q) {
+                    copy16_to_lds(m0_wave + (uint32_t)buf * STAGE_BYTES + q * 4096, voff, ca.ptr + q * 4096);
+                };
+                auto copy_b = [&](int buf, int q) {
+                    copy16_to_lds(m0_wave + (uint32_t)buf * STAGE_BYTES + TILE_BYTES + q * 4096, voff, cb.ptr + q * 4096);
+                };
 
-    // prologue: stages 0 .. NS-2 in flight, stage 0 landed and visible, its first fragments fetched
+                v16i acc[4][4];
 #pragma unroll
-    for (int sidx = 0; sidx < NS - 1; ++sidx) issue_copy(sidx);
-    wait_vmcnt<2 * NLOAD * (NS - 2)>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    fetch(fa0, fb0, 0, 0);
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = (v16i){0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                // the 4 MFMAs of A row tile i for one k-step
+                auto math_row = [&](const v4i* fa, const v4i* fb, int i) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                };
+                // fragment i of A and of B for k-step kk of ring buffer `buf`
+                auto fetch_one = [&](v4i* fa, v4i* fb, int buf, int kk, int i) {
+                    fa[i] = *(lds_v4i_ptr)(uintptr_t)(fragA[kk] + (uint32_t)buf * STAGE_BYTES + i * 2048);
+                    fb[i] = *(lds_v4i_ptr)(uintptr_t)(fragB[kk] + (uint32_t)buf * STAGE_BYTES + i * 2048);
+                };
 
-    int buf = 0;
-    for (int it = 0; it < nstage; ++it) {
-        const int buf_next = (buf + 1 == NS) ? 0 : buf + 1;
-        const int buf_prev = (buf == 0) ? NS - 1 : buf - 1;
-        // k-step 0 of stage it; fragments of k-step 1 on their way
-        fetch(fa1, fb1, buf, 1);
-        math_half(fa0, fb0, 0);
-        math_half(fa0, fb0, 2);
-        interleave();
-        // stage it+1 complete in LDS for every wave
-        wait_vmcnt<2 * NLOAD * (NS - 3)>();
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        // k-step 1 of stage it; first fragments of stage it+1 on their way; refill the freed buffer
-        fetch(fa0, fb0, buf_next, 0);
-        math_half(fa1, fb1, 0);
-        issue_copy(buf_prev);
-        math_half(fa1, fb1, 2);
-        buf = buf_next;
-    }
-    wait_vmcnt<0>();  // no copy may still be writing LDS when the workgroup retires
+                v4i fa0[4], fb0[4], fa1[4], fb1[4];
 
-    // Epilogue.  Accumulator register r of tile (i, j) in lane l holds output
-    // row 8*(r/4) + 4*(l/32) + r%4 and column l%32 of that 32 x 32 tile.
-    const int64_t row0 = (int64_t)tm * 256 + wm * 128;
-    const int64_t col0 = (int64_t)tp * 256 + wn * 128;
+                // prologue: every wave is past the math of the previous chunk (the LDS ring is free),
+                // stages 0 .. NS-3 and the A half of stage NS-2 go in flight, the team lines up, stage 0
+                // lands, first fragments fetched
+                __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int64_t col = col0 + j * 32 + lr;
-        if (col >= a.p) continue;
-        int eb = 0;
-        if (MODE == 1) eb = a.eB[col] + a.shift;
+                for (int sidx = 0; sidx < NS - 1; ++sidx) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+                    for (int q = 0; q < NLOAD; ++q) copy_a(sidx, q);
+                    advance(ca, wrapA);
+                    if (sidx < NS - 2) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = row0 + i * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-                if (row >= a.m) continue;
-                if (MODE == 0) {
-                    a.C[row * a.ldc + col] = acc[i][j][r];
-                } else {
-                    const double term = ldexp((double)acc[i][j][r], a.eA[row] + eb);
-                    double* d = a.D + row * a.ldd + col;
-                    *d = a.first ? term : (*d + term);
+                        for (int q = 0; q < NLOAD; ++q) copy_b(sidx, q);
+                        advance(cb, wrapB);
+                    }
                 }
+                sync_target += participants;
+                team_arrive_and_wait(sync_ctr, sync_target, a.spin_limit);
+                wait_vmcnt<NLOAD*(2 * (NS - 2) - 1)>();
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int i = 0; i < 4; ++i) fetch_one(fa0, fb0, 0, 0, i);
+
+                // Main loop.  Per stage: 32 MFMAs, 16 fragment fetches and 8 copies, interleaved as
+                // (2 fetches, 4 MFMAs, 1 copy) so that no copy or fetch ever waits behind a burst of its
+                // own kind while the matrix pipe runs dry.
+                int buf = 0;  // ring buffer of stage it
+                for (int it = 0; it < nstage; ++it) {
+                    const int buf_next = (buf + 1 == NS) ? 0 : buf + 1;
+                    const int buf_prev = (buf == 0) ? NS - 1 : buf - 1;
+                    const int buf_b = (buf + NS - 2 >= NS) ? buf - 2 : buf + NS - 2;  // buffer of stage it+NS-2
+                    // k-step 0 of stage it; fragments of k-step 1 on their way; B half of stage it+NS-2
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        fetch_one(fa1, fb1, buf, 1, q);
+                        math_row(fa0, fb0, q);
+#ifndef OZ_NOCOPY
+                        copy_b(buf_b, q);
+#endif
+                    }
+                    advance(cb, wrapB);
+                    if (((it + 1) & sync_mask) == 0 && it + 1 < nstage) {  // every sync_every stages
+                        sync_target += participants;
+                        team_arrive_and_wait(sync_ctr, sync_target, a.spin_limit);
+                    }
+                    // stage it+1 complete in LDS for every wave; every wave done reading stage it-1
+                    wait_vmcnt<2 * NLOAD * (NS - 3)>();
+#ifndef OZ_NOBARRIER
+                    __builtin_amdgcn_s_barrier();
+#endif
+                    asm volatile("" ::: "memory");
+                    // k-step 1 of stage it; first fragments of stage it+1 on their way; A half of stage
+                    // it+NS-1 into the buffer of stage it-1
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        fetch_one(fa0, fb0, buf_next, 0, q);
+                        math_row(fa1, fb1, q);
+#ifndef OZ_NOCOPY
+                        copy_a(buf_prev, q);
+#endif
+                    }
+                    advance(ca, wrapA);
+                    buf = buf_next;
+                }
+                wait_vmcnt<0>();  // no copy may still be writing LDS when the ring is reused or the workgroup retires
+
+                // Epilogue.  Accumulator register r of tile (i, j) in lane l holds output
+                // row 8*(r/4) + 4*(l/32) + r%4 and column l%32 of that 32 x 32 tile.  Addresses are a
+                // wave-uniform base plus a 32-bit lane offset, rebuilt for every chunk (the empty asm
+                // keeps the compiler from hoisting 64 element addresses per lane out of the chunk loops).
+                const int shift = 2 - a.beta * g;
+                int64_t er0 = row0, ec0 = col0;
+                asm volatile("" : "+s"(er0), "+s"(ec0));
+                const bool lane_col_ok[4] = {ec0 + lr < a.p, ec0 + 32 + lr < a.p, ec0 + 64 + lr < a.p,
+                                             ec0 + 96 + lr < a.p};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    int eb = 0;
+                    if (MODE == 1 && lane_col_ok[j]) eb = a.eB[ec0 + j * 32 + lr] + shift;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int64_t urow = er0 + i * 32 + 8 * (r / 4) + (r % 4);  // uniform part of the row
+                            const bool ok = lane_col_ok[j] && (urow + 4 * lh < a.m);
+                            if (MODE == 0) {
+                                int32_t* base = a.C + urow * a.ldc + ec0 + j * 32;
+                                const uint32_t off = (uint32_t)(4 * lh) * (uint32_t)a.ldc + (uint32_t)lr;
+                                if (ok) base[off] = acc[i][j][r];
+                            } else {
+                                double* base = a.D + urow * a.ldd + ec0 + j * 32;
+                                const uint32_t off = (uint32_t)(4 * lh) * (uint32_t)a.ldd + (uint32_t)lr;
+                                if (ok) {
+                                    const double term = ldexp((double)acc[i][j][r], a.eA[urow + 4 * lh] + eb);
+                                    base[off] = first ? term : (base[off] + term);
+                                }
+                            }
+                        }
+                        // one 32 x 32 tile at a time keeps the epilogue's loads within the register budget
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                first = 0;
             }
         }
     }
@@ -245,7 +326,13 @@ __global__ __launch_bounds__(256) void k_zero_f64(int64_t m, int64_t p, double* 
     if (j < p && i < m) D[i * ldd + j] = 0.0;
 }
 
-constexpr int NSTAGES = 4;
+// zero the soft-barrier counters (a kernel rather than a memset so that the call can be captured in a graph)
+__global__ void k_fill_u32_gemm(unsigned* x) { x[threadIdx.x] = 0u; }
+
+#ifndef OZ_NS
+#define OZ_NS 4
+#endif
+constexpr int NSTAGES = OZ_NS;
 
 }  // namespace
 
@@ -256,6 +343,7 @@ hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st)
     const int TM = (int)(ozl::rows_padded(a.m) / ozl::TILE_R), TP = (int)(ozl::rows_padded(a.p) / ozl::TILE_R);
     const size_t smem = (size_t)NSTAGES * STAGE_BYTES;
     static bool attr_set[64] = {false};
+    static int num_cu[64] = {0};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     if (!attr_set[dev]) {
@@ -265,9 +353,16 @@ hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<1, NSTAGES>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
+        e = hipDeviceGetAttribute(&num_cu[dev], hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
         attr_set[dev] = true;
     }
-    dim3 grid((unsigned)(TM * TP)), block(256);
+    // one workgroup per CU (the LDS ring allows no second one), never more workgroups than tiles
+    const int64_t tiles = (int64_t)TM * TP;
+    int nwg = num_cu[dev] > 0 ? num_cu[dev] : 1;
+    if (tiles < nwg) nwg = (int)tiles;
+    hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(NXCD * 16), 0, st, a.sync);
+    dim3 grid((unsigned)nwg), block(256);
     if (fused)
         hipLaunchKernelGGL((k_gemm<1, NSTAGES>), grid, block, smem, st, a, TM, TP);
     else

@@ -21,18 +21,25 @@ struct GemmArgs {
     int64_t strideA;       // bytes per A slice
     int64_t strideB;       // bytes per B slice
     int KT;                // inner tiles per slice
-    int g, s0, s1;         // chunk: sum over s = s0..s1 of A''_s B''_{g-s}
+    // chunk schedule: for g = g_lo..g_hi, chunks of at most r consecutive s out of s_lo(g)..s_hi(g);
+    // s_lo = 1, s_hi = g-1 for the full schedule of Algorithm 6; a single chunk sets g_lo == g_hi
+    // and gives its own s range in s0, s1 (s0 > 0)
+    int g_lo, g_hi, r;
+    int s0, s1;
     int64_t m, p;          // valid output extent
-    int32_t* C;            // INT32 output (mode 0)
+    int32_t* C;            // INT32 output (mode 0, single chunk only)
     int64_t ldc;
     double* D;             // FP64 accumulate target (mode 1)
     int64_t ldd;
     const int32_t* eA;
     const int32_t* eB;
-    int shift;             // 2 - beta * g
-    int first;             // D is zero: overwrite
+    int beta;              // shift of group g is 2 - beta * g
+    int first;             // D is zero before the first chunk: overwrite
+    unsigned* sync;        // 8 x 16 zeroed counters (one cache line apart) for the per-XCD soft barrier
+    int sync_every;        // stages between soft barriers inside a chunk (0: only at chunk start)
+    int spin_limit;        // polls before a soft barrier gives up
 };
-// Step (iii) (+ (iv) when fused != 0) for one chunk (Algorithm 6).
+// Steps (iii) (+ (iv) when fused != 0) for the chunks of the schedule (Algorithm 6).
 hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st);
 // Step (iv) alone.
 hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA,

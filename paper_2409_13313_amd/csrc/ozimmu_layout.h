@@ -26,11 +26,20 @@ constexpr int KPAD = 128;                    // inner padding granule
 constexpr int CHUNK = 16;                    // bytes per MFMA operand fetch
 constexpr int NCHUNK = TILE_K / CHUNK;       // 4
 constexpr int TILE_BYTES = TILE_R * TILE_K;  // 16 KiB
+#ifndef OZ_ROWPAD
+#define OZ_ROWPAD 0
+#endif
+constexpr int ROWPAD = OZ_ROWPAD;            // bytes of padding after the tiles of one row block
 
 __host__ __device__ inline int64_t round_up(int64_t x, int64_t q) { return (x + q - 1) / q * q; }
 __host__ __device__ inline int64_t rows_padded(int64_t rows) { return round_up(rows, TILE_R); }
 __host__ __device__ inline int64_t inner_padded(int64_t n) { return round_up(n, KPAD); }
-__host__ __device__ inline int64_t slice_bytes(int64_t rows, int64_t n) { return rows_padded(rows) * inner_padded(n); }
+// bytes from one row block (TILE_R rows, all inner tiles) to the next
+__host__ __device__ inline int64_t rowblock_bytes(int64_t KT) { return KT * TILE_BYTES + ROWPAD; }
+__host__ __device__ inline int64_t slice_bytes(int64_t rows, int64_t n)
+{
+    return rows_padded(rows) / TILE_R * rowblock_bytes(inner_padded(n) / TILE_K);
+}
 
 __host__ __device__ inline int swizzle(int r, int c) { return c ^ ((r >> 2) & 3); }
 
@@ -40,7 +49,7 @@ __host__ __device__ inline int64_t packed_offset(int64_t R, int64_t l, int64_t K
     int64_t rt = R / TILE_R, kt = l / TILE_K;
     int r = (int)(R % TILE_R), lk = (int)(l % TILE_K);
     int c = lk / CHUNK, b = lk % CHUNK;
-    return ((rt * KT + kt) * TILE_R + r) * TILE_K + swizzle(r, c) * CHUNK + b;
+    return rt * rowblock_bytes(KT) + ((kt * TILE_R + r) * TILE_K + swizzle(r, c) * CHUNK + b);
 }
 
 }  // namespace ozl

@@ -261,7 +261,7 @@ hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, in
                           int32_t* eA, hipStream_t st)
 {
     const int64_t Rpad = ozl::rows_padded(m), Npad = ozl::inner_padded(n);
-    const int64_t stride = Rpad * Npad;
+    const int64_t stride = ozl::slice_bytes(m, n);
     const bool vec = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 2 == 0);
     dim3 grid((unsigned)(Rpad / 4)), block(256);
     if (vec)
@@ -275,7 +275,7 @@ hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, in
                           int32_t* eB, hipStream_t st)
 {
     const int64_t Rpad = ozl::rows_padded(p), Npad = ozl::inner_padded(n);
-    const int64_t stride = Rpad * Npad;
+    const int64_t stride = ozl::slice_bytes(p, n);
     hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p,
                        reinterpret_cast<uint32_t*>(eB), 0u);
     dim3 gmax((unsigned)((n + LCH - 1) / LCH), (unsigned)((p + 63) / 64));
@@ -292,7 +292,7 @@ hipError_t launch_export(int64_t rows, int64_t n, int k, const int8_t* packed, i
     const int64_t total = (int64_t)k * rows * n;
     if (total == 0) return hipSuccess;
     hipLaunchKernelGGL(k_export, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, rows, n, k, packed, out,
-                       Npad / ozl::TILE_K, Rpad * Npad);
+                       Npad / ozl::TILE_K, ozl::slice_bytes(rows, n));
     return hipGetLastError();
 }
 

@@ -16,6 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libozimmu.so")
 MAX_SLICES = 20
+SCRATCH_BYTES = 512
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2409_13313_amd.build` (needs hipcc)")
@@ -42,12 +43,12 @@ _lib.ozimmu_split_A.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_split_A.restype = _int
 _lib.ozimmu_split_B.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_split_B.restype = _int
-_lib.ozimmu_gemm_group.argtypes = [_i64, _i64, _i64, _vp, _int, _vp, _int, _int, _int, _int, _vp, _i64, _vp]
+_lib.ozimmu_gemm_group.argtypes = [_i64, _i64, _i64, _vp, _int, _vp, _int, _int, _int, _int, _vp, _i64, _vp, _vp]
 _lib.ozimmu_gemm_group.restype = _int
 _lib.ozimmu_accumulate.argtypes = [_i64, _i64, _vp, _i64, _vp, _vp, _int, _int, _int, _vp, _i64, _vp]
 _lib.ozimmu_accumulate.restype = _int
 _lib.ozimmu_gemm_group_accumulate.argtypes = [_i64, _i64, _i64, _vp, _int, _vp, _int, _int, _int, _int,
-                                              _vp, _vp, _int, _vp, _i64, _vp]
+                                              _vp, _vp, _int, _vp, _i64, _vp, _vp]
 _lib.ozimmu_gemm_group_accumulate.restype = _int
 _lib.ozimmu_export_slices.argtypes = [_i64, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_export_slices.restype = _int
@@ -165,13 +166,20 @@ def split_B(B: torch.Tensor, k: int) -> Tuple[torch.Tensor, torch.Tensor]:
     return SB, eB
 
 
+def alloc_scratch(device="cuda") -> torch.Tensor:
+    return torch.empty(SCRATCH_BYTES, dtype=torch.uint8, device=device)
+
+
 def gemm_group(m: int, n: int, p: int, SA: torch.Tensor, kA: int, SB: torch.Tensor, kB: int,
-               g: int, s0: int, s1: int, C: Optional[torch.Tensor] = None) -> torch.Tensor:
+               g: int, s0: int, s1: int, C: Optional[torch.Tensor] = None,
+               scratch: Optional[torch.Tensor] = None) -> torch.Tensor:
     if C is None:
         C = torch.empty((m, p), dtype=torch.int32, device=SA.device)
     _dev(C, torch.int32)
+    if scratch is None:
+        scratch = alloc_scratch(SA.device)
     _check(_lib.ozimmu_gemm_group(m, n, p, SA.data_ptr(), kA, SB.data_ptr(), kB, g, s0, s1,
-                                  C.data_ptr(), _ld(C), _stream()))
+                                  C.data_ptr(), _ld(C), scratch.data_ptr(), _stream()))
     return C
 
 
@@ -186,11 +194,13 @@ def accumulate(C: torch.Tensor, eA: torch.Tensor, eB: torch.Tensor, beta: int, g
 
 def gemm_group_accumulate(m: int, n: int, p: int, SA: torch.Tensor, kA: int, SB: torch.Tensor, kB: int,
                           g: int, s0: int, s1: int, eA: torch.Tensor, eB: torch.Tensor, first: bool,
-                          D: torch.Tensor) -> torch.Tensor:
+                          D: torch.Tensor, scratch: Optional[torch.Tensor] = None) -> torch.Tensor:
     _dev(D, torch.float64)
+    if scratch is None:
+        scratch = alloc_scratch(SA.device)
     _check(_lib.ozimmu_gemm_group_accumulate(m, n, p, SA.data_ptr(), kA, SB.data_ptr(), kB, g, s0, s1,
                                              eA.data_ptr(), eB.data_ptr(), 1 if first else 0,
-                                             D.data_ptr(), _ld(D), _stream()))
+                                             D.data_ptr(), _ld(D), scratch.data_ptr(), _stream()))
     return D
 
 

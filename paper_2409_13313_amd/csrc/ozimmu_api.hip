@@ -69,9 +69,7 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
     a.p = p;
     a.beta = beta_of(n);
     a.sync = static_cast<unsigned*>(scratch);
-    static const int sync_every = env_int("OZIMMU_SYNC_EVERY", 0);
     static const int spin_limit = env_int("OZIMMU_SPIN_LIMIT", 64);
-    a.sync_every = (sync_every > 0 && (sync_every & (sync_every - 1)) == 0) ? sync_every : 0;
     a.spin_limit = spin_limit;
     return a;
 }

@@ -29,6 +29,7 @@
 // not track them; the vmcnt waits that order them are written out below.
 #include "ozimmu_kernels.h"
 #include "ozimmu_layout.h"
+#include <type_traits>
 
 namespace {
 
@@ -56,11 +57,14 @@ __device__ inline void tile_of_linear(int lin, int TM, int TP, int& tm, int& tp)
 }
 
 // One 16-byte-per-lane copy global -> LDS: lane i of the wave writes LDS bytes
-// [m0 + 16 i, m0 + 16 i + 16) with the 16 bytes at gbase + voff (voff per lane).
-__device__ inline void copy16_to_lds(uint32_t m0, uint32_t voff, const int8_t* gbase)
+// [m0_base + IMM + 16 i, +16) with the 16 bytes at gbase + voff (voff per lane).
+// M0 carries the LDS address; one wait state must separate its write from the copy.
+template <int IMM>
+__device__ inline void copy16_to_lds(uint32_t m0_base, uint32_t voff, const int8_t* gbase)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(voff), "s"(gbase)
-                 : "memory");
+    asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(m0_base), "n"(IMM),
+                 "v"(voff), "s"(gbase)
+                 : "memory", "scc");
 }
 
 template <int N>
@@ -70,9 +74,19 @@ __device__ inline void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+template <int I, int N, class F>
+__device__ inline void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 // Soft barrier between the workgroups of one XCD ("team").  They share one L2 and
 // stream the same A / B tiles; the L2 holds only some twenty stages of the team's
-// working set, so operand reuse in L2 lives on the team advancing in lockstep.
+// working set, so operand reuse in L2 lives on the team advancing in lockstep
+// (measured: 6.4 GB instead of 22 GB fetched from HBM per slice pair at 16384^3).
 // Nothing but timing depends on it: a workgroup that has waited `spin_limit`
 // polls goes on alone, so the barrier always ends.  Called by every thread;
 // thread 0 arrives and polls, the rest meet it at the next s_barrier.
@@ -87,6 +101,13 @@ __device__ inline void team_arrive_and_wait(unsigned* ctr, unsigned target, int 
     }
 }
 
+// Copy cursor: tile pointer of the next stage to copy for one operand.  The inner tiles of a slice are
+// consecutive 16 KiB blocks; `groups_left` counts the groups of NS stages left in the current slice.
+struct Cursor {
+    const int8_t* ptr;
+    int groups_left;
+};
+
 // Persistent kernel: gridDim.x workgroups (one per CU), workgroup b belongs to
 // XCD b % 8 (hardware dispatch order) and is member b / 8 of that XCD's team.
 // The tiles of the output are split into 8 contiguous ranges, one per XCD, in
@@ -94,6 +115,13 @@ __device__ inline void team_arrive_and_wait(unsigned* ctr, unsigned target, int 
 // works on tiles q*team .. q*team+team-1 of its range, i.e. an 8 x 4 patch
 // whose A and B tiles are shared through the XCD's L2.  For its tile a
 // workgroup runs every chunk of the schedule in the order of Algorithm 6.
+//
+// The main loop is unrolled NS times so that every LDS address is a register
+// plus an immediate and every M0 value one scalar add: with one wave per SIMD
+// every instruction that is not an MFMA competes with the MFMAs for the wave's
+// issue slots (one instruction per 4 cycles), so the loop carries as few of them
+// as it can (per stage 32 MFMAs, 16 LDS reads, 8 copies of 3 instructions, two
+// cursor updates, one barrier).
 template <int MODE, int NS>
 __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
 {
@@ -103,26 +131,34 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     const int wm = wave >> 1, wn = wave & 1;
     const int lr = lane & 31, lh = lane >> 5;
 
-    const int KT = a.KT;
+    const int KT = a.KT;  // a multiple of NS (inner padding granule KPAD)
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
-    const uint32_t voff = (uint32_t)t * 16u;
     const uint32_t m0_wave = lds_base + (uint32_t)wave * 1024u;
+    uint32_t voff[NLOAD];  // lane offset of quarter q of a tile copy
+#pragma unroll
+    for (int q = 0; q < NLOAD; ++q) voff[q] = (uint32_t)t * 16u + q * 4096u;
     // moving on to the next slice pair of a chunk: A slice s -> s+1, B slice g-s -> g-s-1, inner tile KT-1 -> 0
-    const int64_t wrapA = a.strideA - (int64_t)(KT - 1) * TILE_BYTES;
-    const int64_t wrapB = -a.strideB - (int64_t)(KT - 1) * TILE_BYTES;
+    // (on top of the usual step of one tile)
+    const int64_t wrapA = a.strideA - (int64_t)KT * TILE_BYTES;
+    const int64_t wrapB = -a.strideB - (int64_t)KT * TILE_BYTES;
 
-    // per-lane fragment offsets inside a stage: row = w*128 + i*32 + lane%32, logical chunk = kk*2 + lane/32;
-    // i*32 rows = i*2048 bytes and does not change the swizzle, so only kk needs its own offset
-    uint32_t fragA[2], fragB[2];
+    // Per-lane fragment addresses: row = w*128 + i*32 + lane%32, logical chunk = kk*2 + lane/32.  i*32 rows
+    // = i*2048 bytes and does not change the swizzle; ring buffer u adds u*32 KiB.  ds_read offsets are 16-bit
+    // immediates, so one base register serves two ring buffers (h = u / 2).
+    constexpr int NH = (NS + 1) / 2;
+    uint32_t fragA[2][NH], fragB[2][NH];
     {
         const int rowA = wm * 128 + lr, rowB = wn * 128 + lr;
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            fragA[kk] = lds_base + rowA * TILE_K + swizzle(rowA, kk * 2 + lh) * CHUNK;
-            fragB[kk] = lds_base + TILE_BYTES + rowB * TILE_K + swizzle(rowB, kk * 2 + lh) * CHUNK;
-        }
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                fragA[kk][h] = lds_base + h * 2 * STAGE_BYTES + rowA * TILE_K + swizzle(rowA, kk * 2 + lh) * CHUNK;
+                fragB[kk][h] = lds_base + h * 2 * STAGE_BYTES + rowB * TILE_K + swizzle(rowB, kk * 2 + lh) * CHUNK;
+            }
     }
     typedef __attribute__((address_space(3))) const v4i* lds_v4i_ptr;
+
     // team geometry
     const int nwg = gridDim.x, bid = blockIdx.x;
     const int xcd = bid % NXCD, member = bid / NXCD;
@@ -133,8 +169,6 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     const int range_cnt = tiles_base + (xcd < tiles_rem ? 1 : 0);
     unsigned* const sync_ctr = a.sync + xcd * 16;
     unsigned sync_target = 0;
-    // sync_every is a power of two (or 0: never inside a chunk)
-    const int sync_mask = a.sync_every > 0 ? a.sync_every - 1 : 0x7fffffff;
 
     for (int local = member; local < range_cnt; local += team) {
         const int round_first = local - member;
@@ -152,28 +186,13 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 const int c1 = (c0 + a.r - 1 < s_hi) ? c0 + a.r - 1 : s_hi;  // chunk: s = c0..c1
                 const int nstage = (c1 - c0 + 1) * KT;
 
-                // Copy cursors: tile pointers of the next stage to copy, one per operand (the B half of a
-                // stage is issued half an iteration after its A half).  They stop at the last stage, so the
-                // copies issued past the end re-read valid memory into buffers nobody reads.
-                struct Cursor {
-                    const int8_t* ptr;
-                    int kt, it;
-                };
-                Cursor ca = {a.SA + (int64_t)(c0 - 1) * a.strideA + (int64_t)tm * rowblock_bytes(KT), 0, 0};
-                Cursor cb = {a.SB + (int64_t)(g - c0 - 1) * a.strideB + (int64_t)tp * rowblock_bytes(KT), 0, 0};
-                auto advance = [&](Cursor& c, int64_t wrap_step) {  // branch-free, all scalar
-                    const bool adv = c.it + 1 < nstage;
-                    const bool wrap = adv && (c.kt + 1 == KT);
-                    c.it += adv ? 1 : 0;
-                    c.kt = wrap ? 0 : c.kt + (adv ? 1 : 0);
-                    c.ptr += wrap ? wrap_step : (adv ? (int64_t)TILE_BYTES : 0);
-                };
-                // one 16-byte-per-lane copy (quarter q of a tile) of the A / B tile under the cursor into ring buffer `buf`
-                auto copy_a = [&](int buf, int q) {
-                    copy16_to_lds(m0_wave + (uint32_t)buf * STAGE_BYTES + q * 4096, voff, ca.ptr + q * 4096);
-                };
-                auto copy_b = [&](int buf, int q) {
-                    copy16_to_lds(m0_wave + (uint32_t)buf * STAGE_BYTES + TILE_BYTES + q * 4096, voff, cb.ptr + q * 4096);
+                Cursor ca = {a.SA + (int64_t)(c0 - 1) * a.strideA + (int64_t)tm * rowblock_bytes(KT), KT / NS};
+                Cursor cb = {a.SB + (int64_t)(g - c0 - 1) * a.strideB + (int64_t)tp * rowblock_bytes(KT), KT / NS};
+                // a cursor that has just copied the last inner tile of a slice jumps to the next slice pair
+                auto wrap_check = [&](Cursor& c, int64_t extra) {
+                    const bool wr = (--c.groups_left == 0);
+                    c.ptr += wr ? extra : (int64_t)0;
+                    c.groups_left = wr ? KT / NS : c.groups_left;
                 };
 
                 v16i acc[4][4];
@@ -183,82 +202,121 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     for (int j = 0; j < 4; ++j) acc[i][j] = (v16i){0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
                 // the 4 MFMAs of A row tile i for one k-step
                 auto math_row = [&](const v4i* fa, const v4i* fb, int i) {
+#if defined(OZ_NOMATH) || defined(OZ_NOMFMA)
+                    return;
+#endif
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
                 };
-                // fragment i of A and of B for k-step kk of ring buffer `buf`
-                auto fetch_one = [&](v4i* fa, v4i* fb, int buf, int kk, int i) {
-                    fa[i] = *(lds_v4i_ptr)(uintptr_t)(fragA[kk] + (uint32_t)buf * STAGE_BYTES + i * 2048);
-                    fb[i] = *(lds_v4i_ptr)(uintptr_t)(fragB[kk] + (uint32_t)buf * STAGE_BYTES + i * 2048);
-                };
-
                 v4i fa0[4], fb0[4], fa1[4], fb1[4];
 
                 // prologue: every wave is past the math of the previous chunk (the LDS ring is free),
                 // stages 0 .. NS-3 and the A half of stage NS-2 go in flight, the team lines up, stage 0
                 // lands, first fragments fetched
                 __builtin_amdgcn_s_barrier();
-#pragma unroll
-                for (int sidx = 0; sidx < NS - 1; ++sidx) {
-#pragma unroll
-                    for (int q = 0; q < NLOAD; ++q) copy_a(sidx, q);
-                    advance(ca, wrapA);
-                    if (sidx < NS - 2) {
-#pragma unroll
-                        for (int q = 0; q < NLOAD; ++q) copy_b(sidx, q);
-                        advance(cb, wrapB);
+                static_for<0, NS - 1>([&](auto S) {
+                    constexpr int sidx = decltype(S)::value;
+                    static_for<0, NLOAD>([&](auto Q) {
+                        constexpr int q = decltype(Q)::value;
+                        copy16_to_lds<sidx * STAGE_BYTES + q * 4096>(m0_wave, voff[q], ca.ptr);
+                    });
+                    ca.ptr += TILE_BYTES;
+                    if constexpr (sidx < NS - 2) {
+                        static_for<0, NLOAD>([&](auto Q) {
+                            constexpr int q = decltype(Q)::value;
+                            copy16_to_lds<sidx * STAGE_BYTES + TILE_BYTES + q * 4096>(m0_wave, voff[q], cb.ptr);
+                        });
+                        cb.ptr += TILE_BYTES;
                     }
-                }
+                });
                 sync_target += participants;
                 team_arrive_and_wait(sync_ctr, sync_target, a.spin_limit);
                 wait_vmcnt<NLOAD*(2 * (NS - 2) - 1)>();
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
 #pragma unroll
-                for (int i = 0; i < 4; ++i) fetch_one(fa0, fb0, 0, 0, i);
+                for (int i = 0; i < 4; ++i) {
+                    fa0[i] = *(lds_v4i_ptr)(uintptr_t)(fragA[0][0] + i * 2048);
+                    fb0[i] = *(lds_v4i_ptr)(uintptr_t)(fragB[0][0] + TILE_BYTES + i * 2048);
+                }
 
-                // Main loop.  Per stage: 32 MFMAs, 16 fragment fetches and 8 copies, interleaved as
-                // (2 fetches, 4 MFMAs, 1 copy) so that no copy or fetch ever waits behind a burst of its
-                // own kind while the matrix pipe runs dry.
-                int buf = 0;  // ring buffer of stage it
-                for (int it = 0; it < nstage; ++it) {
-                    const int buf_next = (buf + 1 == NS) ? 0 : buf + 1;
-                    const int buf_prev = (buf == 0) ? NS - 1 : buf - 1;
-                    const int buf_b = (buf + NS - 2 >= NS) ? buf - 2 : buf + NS - 2;  // buffer of stage it+NS-2
-                    // k-step 0 of stage it; fragments of k-step 1 on their way; B half of stage it+NS-2
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        fetch_one(fa1, fb1, buf, 1, q);
+                // One stage whose ring buffer index U is a compile-time constant.  32 MFMAs, 16 fragment
+                // fetches and 8 copies, interleaved as (2 fetches, 4 MFMAs, 1 copy).  The stage copied in
+                // position u is NS-1 (A half) or NS-2 (B half) ahead, so a cursor reaches the end of a slice
+                // in one fixed position of the unrolled group: A in position 0, B in position 1.  In the last
+                // group of a chunk (TAIL) the copies that would run past the chunk are left out.
+                auto stage = [&](auto U, auto TAIL) {
+                    constexpr int u = decltype(U)::value;          // ring buffer of this stage
+                    constexpr bool tail = decltype(TAIL)::value;
+                    constexpr int un = (u + 1) % NS;               // ... of the next stage
+                    constexpr int up = (u + NS - 1) % NS;          // ... of the previous stage (free: refill with stage it+NS-1)
+                    constexpr int ub = (u + NS - 2) % NS;          // ... of stage it+NS-2 (its B half goes in now)
+                    constexpr bool copy_b = !tail || u < 2;        // stage it+NS-2 still inside the chunk
+                    constexpr bool copy_a = !tail || u < 1;        // stage it+NS-1 still inside the chunk
+                    constexpr bool fetch_next = !tail || u < NS - 1;
+                    // k-step 0 of this stage; fragments of k-step 1 on their way; B half of stage it+NS-2
+                    static_for<0, 4>([&](auto Q) {
+                        constexpr int q = decltype(Q)::value;
+#if !defined(OZ_NOMATH) && !defined(OZ_NOFETCH)
+                        // B fragments first (every MFMA row of the next k-step needs all four), then A
+                        if constexpr (q < 2) {
+                            fb1[2 * q] = *(lds_v4i_ptr)(uintptr_t)(fragB[1][u / 2] + (u % 2) * STAGE_BYTES + TILE_BYTES + (2 * q) * 2048);
+                            fb1[2 * q + 1] = *(lds_v4i_ptr)(uintptr_t)(fragB[1][u / 2] + (u % 2) * STAGE_BYTES + TILE_BYTES + (2 * q + 1) * 2048);
+                        } else {
+                            fa1[2 * q - 4] = *(lds_v4i_ptr)(uintptr_t)(fragA[1][u / 2] + (u % 2) * STAGE_BYTES + (2 * q - 4) * 2048);
+                            fa1[2 * q - 3] = *(lds_v4i_ptr)(uintptr_t)(fragA[1][u / 2] + (u % 2) * STAGE_BYTES + (2 * q - 3) * 2048);
+                        }
+#endif
                         math_row(fa0, fb0, q);
 #ifndef OZ_NOCOPY
-                        copy_b(buf_b, q);
+                        if constexpr (copy_b)
+                            copy16_to_lds<ub * STAGE_BYTES + TILE_BYTES + q * 4096>(m0_wave, voff[q], cb.ptr);
 #endif
-                    }
-                    advance(cb, wrapB);
-                    if (((it + 1) & sync_mask) == 0 && it + 1 < nstage) {  // every sync_every stages
-                        sync_target += participants;
-                        team_arrive_and_wait(sync_ctr, sync_target, a.spin_limit);
+                        __builtin_amdgcn_sched_barrier(0);  // keep the (fetch, math, copy) order as written
+                    });
+                    if constexpr (copy_b) {
+                        cb.ptr += TILE_BYTES;
+                        if constexpr (u == 1 && !tail) wrap_check(cb, wrapB);
                     }
                     // stage it+1 complete in LDS for every wave; every wave done reading stage it-1
-                    wait_vmcnt<2 * NLOAD * (NS - 3)>();
+                    if constexpr (tail && u >= 2)
+                        wait_vmcnt<0>();
+                    else
+                        wait_vmcnt<2 * NLOAD * (NS - 3)>();
 #ifndef OZ_NOBARRIER
                     __builtin_amdgcn_s_barrier();
 #endif
                     asm volatile("" ::: "memory");
-                    // k-step 1 of stage it; first fragments of stage it+1 on their way; A half of stage
-                    // it+NS-1 into the buffer of stage it-1
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        fetch_one(fa0, fb0, buf_next, 0, q);
+                    // k-step 1 of this stage; first fragments of stage it+1 on their way; A half of stage it+NS-1
+                    static_for<0, 4>([&](auto Q) {
+                        constexpr int q = decltype(Q)::value;
+#if !defined(OZ_NOMATH) && !defined(OZ_NOFETCH)
+                        if constexpr (fetch_next) {
+                            if constexpr (q < 2) {
+                                fb0[2 * q] = *(lds_v4i_ptr)(uintptr_t)(fragB[0][un / 2] + (un % 2) * STAGE_BYTES + TILE_BYTES + (2 * q) * 2048);
+                                fb0[2 * q + 1] = *(lds_v4i_ptr)(uintptr_t)(fragB[0][un / 2] + (un % 2) * STAGE_BYTES + TILE_BYTES + (2 * q + 1) * 2048);
+                            } else {
+                                fa0[2 * q - 4] = *(lds_v4i_ptr)(uintptr_t)(fragA[0][un / 2] + (un % 2) * STAGE_BYTES + (2 * q - 4) * 2048);
+                                fa0[2 * q - 3] = *(lds_v4i_ptr)(uintptr_t)(fragA[0][un / 2] + (un % 2) * STAGE_BYTES + (2 * q - 3) * 2048);
+                            }
+                        }
+#endif
                         math_row(fa1, fb1, q);
 #ifndef OZ_NOCOPY
-                        copy_a(buf_prev, q);
+                        if constexpr (copy_a) copy16_to_lds<up * STAGE_BYTES + q * 4096>(m0_wave, voff[q], ca.ptr);
 #endif
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                    if constexpr (copy_a) {
+                        ca.ptr += TILE_BYTES;
+                        if constexpr (u == 0 && !tail) wrap_check(ca, wrapA);
                     }
-                    advance(ca, wrapA);
-                    buf = buf_next;
-                }
+                };
+                static_assert(NS == 4, "the tail logic below is written for a ring of 4 stages");
+                for (int it = 0; it < nstage - NS; it += NS)
+                    static_for<0, NS>([&](auto U) { stage(U, std::false_type{}); });
+                static_for<0, NS>([&](auto U) { stage(U, std::true_type{}); });
                 wait_vmcnt<0>();  // no copy may still be writing LDS when the ring is reused or the workgroup retires
 
                 // Epilogue.  Accumulator register r of tile (i, j) in lane l holds output
@@ -293,9 +351,9 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 }
                             }
                         }
-                        // one 32 x 32 tile at a time keeps the epilogue's loads within the register budget
-                        __builtin_amdgcn_sched_barrier(0);
                     }
+                    // one column of 32 x 32 tiles at a time keeps the epilogue's loads within the register budget
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 first = 0;
             }

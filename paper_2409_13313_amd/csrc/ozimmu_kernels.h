@@ -36,7 +36,6 @@ struct GemmArgs {
     int beta;              // shift of group g is 2 - beta * g
     int first;             // D is zero before the first chunk: overwrite
     unsigned* sync;        // 8 x 16 zeroed counters (one cache line apart) for the per-XCD soft barrier
-    int sync_every;        // stages between soft barriers inside a chunk (0: only at chunk start)
     int spin_limit;        // polls before a soft barrier gives up
 };
 // Steps (iii) (+ (iv) when fused != 0) for the chunks of the schedule (Algorithm 6).

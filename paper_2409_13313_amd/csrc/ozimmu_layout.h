@@ -22,7 +22,7 @@ namespace ozl {
 
 constexpr int TILE_R = 256;                  // rows per tile
 constexpr int TILE_K = 64;                   // inner bytes per tile
-constexpr int KPAD = 128;                    // inner padding granule
+constexpr int KPAD = 256;                    // inner padding granule (4 tiles: the GEMM unrolls 4 stages)
 constexpr int CHUNK = 16;                    // bytes per MFMA operand fetch
 constexpr int NCHUNK = TILE_K / CHUNK;       // 4
 constexpr int TILE_BYTES = TILE_R * TILE_K;  // 16 KiB

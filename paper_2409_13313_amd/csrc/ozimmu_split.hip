@@ -192,7 +192,7 @@ __global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const dou
 {
     __shared__ uint32_t tile[SBATCH][64 * PITCH];
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-    const int64_t l0 = (int64_t)blockIdx.x * KPAD;  // inner offset of this block (128 inner rows)
+    const int64_t l0 = (int64_t)blockIdx.x * 128;  // inner offset of this block (128 inner rows)
     const int64_t j0 = (int64_t)blockIdx.y * 64;      // first column (= packed row)
     const int64_t j = j0 + lane;
     const int64_t KT = Npad / TILE_K;
@@ -281,7 +281,7 @@ hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, in
     dim3 gmax((unsigned)((n + LCH - 1) / LCH), (unsigned)((p + 63) / 64));
     hipLaunchKernelGGL(k_colmax_B, gmax, dim3(256), 0, st, n, p, B, ldb, reinterpret_cast<uint32_t*>(eB));
     hipLaunchKernelGGL(k_decode_keys, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
-    dim3 grid((unsigned)(Npad / ozl::KPAD), (unsigned)(Rpad / 64));
+    dim3 grid((unsigned)(Npad / 128), (unsigned)(Rpad / 64));
     hipLaunchKernelGGL(k_split_B, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, SB, eB, Npad, stride);
     return hipGetLastError();
 }

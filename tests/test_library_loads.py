@@ -66,6 +66,6 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 8, fake, 16, None) == -4           # workspace too small
     assert lib.ozimmu_dgemm(4, 2 ** 29 + 1, 4, fake, 2 ** 30, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -2
     assert lib.ozimmu_dgemm(0, 4, 4, None, 4, None, 4, None, 4, 8, None, 0, None) == 0             # empty: nothing to do
-    # workspace = exponents + k padded slices of A and of B
-    assert lib.ozimmu_workspace_bytes(256, 128, 256, 8) == 512 + 2 * 1024 + 2 * 8 * 256 * 128
-    assert lib.ozimmu_workspace_bytes(257, 129, 1, 3) == 512 + 1280 + 256 + 3 * 512 * 256 + 3 * 256 * 256
+    # workspace = scratch + exponents + k padded slices of A and of B (rows padded to 256, inner index to 256)
+    assert lib.ozimmu_workspace_bytes(256, 128, 256, 8) == 512 + 2 * 1024 + 2 * 8 * 256 * 256
+    assert lib.ozimmu_workspace_bytes(257, 257, 1, 3) == 512 + 1280 + 256 + 3 * 512 * 512 + 3 * 256 * 512

@@ -40,6 +40,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // A tile + B tile = 32 KiB
 constexpr int NLOAD = TILE_BYTES / (256 * 16);    // 16-byte copies per thread and operand tile = 4
+constexpr int EXP_BYTES = 2 * 256 * 4;            // exponents of the tile's 256 rows and 256 columns, kept in LDS
 
 // Linear tile order: bands of GROUP tile rows, each walked column by column, so
 // that 32 consecutive tiles form an 8 x 4 patch (8 A tiles + 4 B tiles per stage).
@@ -178,6 +179,15 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
         const int64_t row0 = (int64_t)tm * 256 + wm * 128;
         const int64_t col0 = (int64_t)tp * 256 + wn * 128;
         int first = a.first;
+        int* const lds_exp = reinterpret_cast<int*>(lds + NS * STAGE_BYTES);
+        if (MODE == 1) {
+            // exponents of this tile's rows and columns go to LDS once (every wave is past the previous
+            // tile's epilogue; the chunk prologue's barrier publishes them)
+            __builtin_amdgcn_s_barrier();
+            const int64_t gr = (int64_t)tm * 256 + t, gc = (int64_t)tp * 256 + t;
+            lds_exp[t] = gr < a.m ? a.eA[gr] : 0;
+            lds_exp[256 + t] = gc < a.p ? a.eB[gc] : 0;
+        }
 
         for (int g = a.g_lo; g <= a.g_hi; ++g) {
             const int s_lo = a.s0 > 0 ? a.s0 : 1;
@@ -328,32 +338,56 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 asm volatile("" : "+s"(er0), "+s"(ec0));
                 const bool lane_col_ok[4] = {ec0 + lr < a.p, ec0 + 32 + lr < a.p, ec0 + 64 + lr < a.p,
                                              ec0 + 96 + lr < a.p};
+                if (MODE == 0) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    int eb = 0;
-                    if (MODE == 1 && lane_col_ok[j]) eb = a.eB[ec0 + j * 32 + lr] + shift;
+                    for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
+                        for (int i = 0; i < 4; ++i)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int64_t urow = er0 + i * 32 + 8 * (r / 4) + (r % 4);  // uniform part of the row
-                            const bool ok = lane_col_ok[j] && (urow + 4 * lh < a.m);
-                            if (MODE == 0) {
+                            for (int r = 0; r < 16; ++r) {
+                                const int64_t urow = er0 + i * 32 + 8 * (r / 4) + (r % 4);  // uniform part of the row
                                 int32_t* base = a.C + urow * a.ldc + ec0 + j * 32;
                                 const uint32_t off = (uint32_t)(4 * lh) * (uint32_t)a.ldc + (uint32_t)lr;
-                                if (ok) base[off] = acc[i][j][r];
-                            } else {
-                                double* base = a.D + urow * a.ldd + ec0 + j * 32;
-                                const uint32_t off = (uint32_t)(4 * lh) * (uint32_t)a.ldd + (uint32_t)lr;
-                                if (ok) {
-                                    const double term = ldexp((double)acc[i][j][r], a.eA[urow + 4 * lh] + eb);
-                                    base[off] = first ? term : (base[off] + term);
-                                }
+                                if (lane_col_ok[j] && urow + 4 * lh < a.m) base[off] = acc[i][j][r];
                             }
+                } else {
+                    // Exponents come from LDS (the compiler cannot prove that D does not alias eA / eB and
+                    // would order global exponent loads behind every store).  Per column of 32 x 32 tiles and
+                    // per pair of row tiles: 32 loads of D in flight, then the adds and stores.
+                    int eb[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) eb[j] = lds_exp[256 + wn * 128 + j * 32 + lr] + shift;
+                    const uint32_t off = (uint32_t)(4 * lh) * (uint32_t)a.ldd + (uint32_t)lr;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                        for (int ih = 0; ih < 4; ih += 2) {
+                            double old[2][16];
+                            if (!first) {
+#pragma unroll
+                                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                                    for (int r = 0; r < 16; ++r) {
+                                        const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
+                                        const double* base = a.D + urow * a.ldd + ec0 + j * 32;
+                                        old[i][r] = (lane_col_ok[j] && urow + 4 * lh < a.m) ? base[off] : 0.0;
+                                    }
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) {
+                                    const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
+                                    double* base = a.D + urow * a.ldd + ec0 + j * 32;
+                                    const int ea = lds_exp[wm * 128 + (ih + i) * 32 + 8 * (r / 4) + (r % 4) + 4 * lh];
+                                    const double term = ldexp((double)acc[ih + i][j][r], ea + eb[j]);
+                                    if (lane_col_ok[j] && urow + 4 * lh < a.m)
+                                        base[off] = first ? term : (old[i][r] + term);
+                                }
+                            __builtin_amdgcn_sched_barrier(0);
                         }
                     }
-                    // one column of 32 x 32 tiles at a time keeps the epilogue's loads within the register budget
-                    __builtin_amdgcn_sched_barrier(0);
                 }
                 first = 0;
             }
@@ -399,7 +433,7 @@ namespace ozk {
 hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st)
 {
     const int TM = (int)(ozl::rows_padded(a.m) / ozl::TILE_R), TP = (int)(ozl::rows_padded(a.p) / ozl::TILE_R);
-    const size_t smem = (size_t)NSTAGES * STAGE_BYTES;
+    const size_t smem = (size_t)NSTAGES * STAGE_BYTES + EXP_BYTES;
     static bool attr_set[64] = {false};
     static int num_cu[64] = {0};
     int dev = 0;

@@ -21,6 +21,9 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA peak, 5.0 POP/s
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script, scaled by the same counters on a plain copy (see profiles/k_gemm_16384_k8_traffic.md)
+MEASURED_TRAFFIC_BYTES = {}
 
 
 def log(*a):
@@ -39,6 +42,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
     ap.add_argument("--no-native", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of A (known size) so that a rocprofv3 --pmc run "
+                         "can scale FETCH_SIZE / WRITE_SIZE against it")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -96,6 +102,12 @@ def main() -> int:
         gemm_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / steps
         return wall_ms, split_ms, gemm_ms
 
+    if args.calibrate_copy:
+        cal = torch.empty_like(dA)
+        cal.copy_(dA)            # reads and writes 8*m*n bytes
+        torch.cuda.synchronize()
+        del cal
+
     wall_ms, split_ms, gemm_ms = timed(k, args.steps, args.warmup)
     flops = 2.0 * m * n * p
     value = flops / (wall_ms * 1e-3) / 1e12
@@ -125,16 +137,17 @@ def main() -> int:
         "phases_ms": {"split_A_and_B": round(split_ms, 4), "chunk_gemm_with_fused_accumulation": round(gemm_ms, 4)},
         "int8_mfma_utilisation_pct": round(100.0 * gemm_tops / PEAK_INT8_TOPS, 2),
         "roofline": {
-            "kernel": "k_gemm<1> (INT8 MFMA chunk GEMM + fused FP64 accumulation)",
+            "kernel": "k_gemm<1,4> (persistent INT8 MFMA kernel: every chunk GEMM of the schedule with its "
+                      "fused FP64 accumulation, one launch per step)",
             "bound": "mfma",
             "achieved": round(gemm_tops, 2),
             "peak": PEAK_INT8_TOPS,
             "unit": "TOP/s",
             "frac": round(gemm_tops / PEAK_INT8_TOPS, 4),
-            "launches_per_step": w,
-            "avg_launch_ms": round(gemm_ms / w, 4),
-            "ops_per_launch": int_ops / w,
-            "traffic": None,
+            "launches_per_step": 1,
+            "avg_launch_ms": round(gemm_ms, 4),
+            "ops_per_launch": int_ops,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((m, n, p, k)),
         },
         "split_hbm": {"algorithmic_GBps": round(split_bytes / split_ms / 1e6, 1), "peak_GBps": PEAK_HBM_GBS,
                       "frac": round(split_bytes / split_ms / 1e6 / PEAK_HBM_GBS, 4)},

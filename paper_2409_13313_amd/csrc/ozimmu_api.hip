@@ -5,7 +5,6 @@
 #include "../../include/ozimmu.h"
 #include "ozimmu_kernels.h"
 #include "ozimmu_layout.h"
-#include <cstdlib>
 
 namespace {
 
@@ -44,12 +43,6 @@ int check_gemm_args(int64_t m, int64_t n, int64_t p, const void* SA, int kA, con
     return OZIMMU_OK;
 }
 
-int env_int(const char* name, int dflt)
-{
-    const char* v = getenv(name);
-    return v ? atoi(v) : dflt;
-}
-
 // single chunk (s0 > 0): g, s = s0..s1; full schedule (s0 == 0): g = g_lo..g_hi, chunks of r
 ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, int g_lo, int g_hi,
                         int r, int s0, int s1, void* scratch)
@@ -69,8 +62,7 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
     a.p = p;
     a.beta = beta_of(n);
     a.sync = static_cast<unsigned*>(scratch);
-    static const int spin_limit = env_int("OZIMMU_SPIN_LIMIT", 64);
-    a.spin_limit = spin_limit;
+    a.spin_limit = 64;  // polls (about 0.1 us each) before a workgroup stops waiting for its team
     return a;
 }
 

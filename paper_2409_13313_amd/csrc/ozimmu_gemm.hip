@@ -212,9 +212,6 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     for (int j = 0; j < 4; ++j) acc[i][j] = (v16i){0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
                 // the 4 MFMAs of A row tile i for one k-step
                 auto math_row = [&](const v4i* fa, const v4i* fb, int i) {
-#if defined(OZ_NOMATH) || defined(OZ_NOMFMA)
-                    return;
-#endif
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
@@ -268,7 +265,6 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     // k-step 0 of this stage; fragments of k-step 1 on their way; B half of stage it+NS-2
                     static_for<0, 4>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
-#if !defined(OZ_NOMATH) && !defined(OZ_NOFETCH)
                         // B fragments first (every MFMA row of the next k-step needs all four), then A
                         if constexpr (q < 2) {
                             fb1[2 * q] = *(lds_v4i_ptr)(uintptr_t)(fragB[1][u / 2] + (u % 2) * STAGE_BYTES + TILE_BYTES + (2 * q) * 2048);
@@ -277,12 +273,9 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                             fa1[2 * q - 4] = *(lds_v4i_ptr)(uintptr_t)(fragA[1][u / 2] + (u % 2) * STAGE_BYTES + (2 * q - 4) * 2048);
                             fa1[2 * q - 3] = *(lds_v4i_ptr)(uintptr_t)(fragA[1][u / 2] + (u % 2) * STAGE_BYTES + (2 * q - 3) * 2048);
                         }
-#endif
                         math_row(fa0, fb0, q);
-#ifndef OZ_NOCOPY
                         if constexpr (copy_b)
                             copy16_to_lds<ub * STAGE_BYTES + TILE_BYTES + q * 4096>(m0_wave, voff[q], cb.ptr);
-#endif
                         __builtin_amdgcn_sched_barrier(0);  // keep the (fetch, math, copy) order as written
                     });
                     if constexpr (copy_b) {
@@ -294,14 +287,11 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                         wait_vmcnt<0>();
                     else
                         wait_vmcnt<2 * NLOAD * (NS - 3)>();
-#ifndef OZ_NOBARRIER
                     __builtin_amdgcn_s_barrier();
-#endif
                     asm volatile("" ::: "memory");
                     // k-step 1 of this stage; first fragments of stage it+1 on their way; A half of stage it+NS-1
                     static_for<0, 4>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
-#if !defined(OZ_NOMATH) && !defined(OZ_NOFETCH)
                         if constexpr (fetch_next) {
                             if constexpr (q < 2) {
                                 fb0[2 * q] = *(lds_v4i_ptr)(uintptr_t)(fragB[0][un / 2] + (un % 2) * STAGE_BYTES + TILE_BYTES + (2 * q) * 2048);
@@ -311,11 +301,8 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 fa0[2 * q - 3] = *(lds_v4i_ptr)(uintptr_t)(fragA[0][un / 2] + (un % 2) * STAGE_BYTES + (2 * q - 3) * 2048);
                             }
                         }
-#endif
                         math_row(fa1, fb1, q);
-#ifndef OZ_NOCOPY
                         if constexpr (copy_a) copy16_to_lds<up * STAGE_BYTES + q * 4096>(m0_wave, voff[q], ca.ptr);
-#endif
                         __builtin_amdgcn_sched_barrier(0);
                     });
                     if constexpr (copy_a) {
@@ -421,10 +408,7 @@ __global__ __launch_bounds__(256) void k_zero_f64(int64_t m, int64_t p, double* 
 // zero the soft-barrier counters (a kernel rather than a memset so that the call can be captured in a graph)
 __global__ void k_fill_u32_gemm(unsigned* x) { x[threadIdx.x] = 0u; }
 
-#ifndef OZ_NS
-#define OZ_NS 4
-#endif
-constexpr int NSTAGES = OZ_NS;
+constexpr int NSTAGES = 4;  // ring depth: 4 x 32 KiB of the 160 KiB LDS (3 and 5 measured no faster)
 
 }  // namespace
 

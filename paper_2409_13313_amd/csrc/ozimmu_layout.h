@@ -26,10 +26,7 @@ constexpr int KPAD = 256;                    // inner padding granule (4 tiles: 
 constexpr int CHUNK = 16;                    // bytes per MFMA operand fetch
 constexpr int NCHUNK = TILE_K / CHUNK;       // 4
 constexpr int TILE_BYTES = TILE_R * TILE_K;  // 16 KiB
-#ifndef OZ_ROWPAD
-#define OZ_ROWPAD 0
-#endif
-constexpr int ROWPAD = OZ_ROWPAD;            // bytes of padding after the tiles of one row block
+constexpr int ROWPAD = 0;                    // bytes of padding after the tiles of one row block (0: 256 B .. 4 KiB measured no faster)
 
 __host__ __device__ inline int64_t round_up(int64_t x, int64_t q) { return (x + q - 1) / q * q; }
 __host__ __device__ inline int64_t rows_padded(int64_t rows) { return round_up(rows, TILE_R); }

@@ -23,7 +23,7 @@ PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA peak, 5.0 POP/s
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script, scaled by the same counters on a plain copy (see profiles/k_gemm_16384_k8_traffic.md)
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {(16384, 16384, 16384, 8): 247.4e9 + 17.2e9}
 
 
 def log(*a):
@@ -207,8 +207,8 @@ def main() -> int:
         t = time.perf_counter()
         oracle.dgemm_sub(A, B, k, I0, J0)
         t_probe = time.perf_counter() - t
-        # cost ~ S^2 (products) + S (split); aim at about 15 s
-        S = int(min(m, p, max(S0, S0 * (15.0 / max(t_probe, 1e-3)) ** 0.5)))
+        # cost ~ S^2 (products) + S (split); the probe overestimates the rate, aim at 10-30 s
+        S = int(min(m, p, max(S0, S0 * (40.0 / max(t_probe, 1e-3)) ** 0.5)))
         S = max(S0, min(S, 1024))
         I1 = inputs.sample_indices(m, S, seed=5)
         J1 = inputs.sample_indices(p, S, seed=6)

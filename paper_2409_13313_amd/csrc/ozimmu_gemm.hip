@@ -40,6 +40,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // A tile + B tile = 32 KiB
 constexpr int NLOAD = TILE_BYTES / (256 * 16);    // 16-byte copies per thread and operand tile = 4
+constexpr int EPI_ROWS = 2;                       // 32 x 32 tiles per epilogue batch (16 D loads in flight per lane each)
 constexpr int EXP_BYTES = 2 * 256 * 4;            // exponents of the tile's 256 rows and 256 columns, kept in LDS
 
 // Linear tile order: bands of GROUP tile rows, each walked column by column, so
@@ -213,8 +214,10 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 // the 4 MFMAs of A row tile i for one k-step
                 auto math_row = [&](const v4i* fa, const v4i* fb, int i) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const int j = (i & 1) ? 3 - jj : jj;  // boustrophedon: one operand stays put between MFMAs
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    }
                 };
                 v4i fa0[4], fb0[4], fa1[4], fb1[4];
 
@@ -348,11 +351,11 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
 #pragma unroll
-                        for (int ih = 0; ih < 4; ih += 2) {
-                            double old[2][16];
+                        for (int ih = 0; ih < 4; ih += EPI_ROWS) {
+                            double old[EPI_ROWS][16];
                             if (!first) {
 #pragma unroll
-                                for (int i = 0; i < 2; ++i)
+                                for (int i = 0; i < EPI_ROWS; ++i)
 #pragma unroll
                                     for (int r = 0; r < 16; ++r) {
                                         const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
@@ -362,7 +365,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                             }
                             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                            for (int i = 0; i < 2; ++i)
+                            for (int i = 0; i < EPI_ROWS; ++i)
 #pragma unroll
                                 for (int r = 0; r < 16; ++r) {
                                     const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);

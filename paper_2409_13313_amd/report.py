@@ -1,0 +1,127 @@
+"""Secondary measurements on one MI355X (the headline number is bench.py's):
+
+  --accuracy   m=n=p=1024, phi in {0.5, 1, 2}, k = 6..12: error of the emulated product against a
+               compensated (Dot2) product, next to native FP64 (torch.mm)         [Section 4.1 workload]
+  --phases     m=n=p=8192, phi=0.5, k in {6, 8, 10}: time of split A, split B, chunk GEMMs and
+               FP64 accumulation run as separate phases, and of the fused call    [Section 4.2 workload]
+  --long-inner m=p=4096, n=65536, phi=1, k=10 (r = 2: 30 chunks for 55 products)
+
+Prints markdown tables.  The Dot2 reference comes from the CPU oracle package, which is test
+infrastructure; nothing here feeds back into the HIP path.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def _median_ms(fn, reps):
+    import torch
+    times = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1))
+    times.sort()
+    return times[len(times) // 2]
+
+
+def accuracy():
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2409_13313_amd import inputs, ozimmu
+    n = 1024
+    print(f"### accuracy, m=n=p={n}: max |D - R| / (|A||B|) over all entries, R = Dot2 product\n")
+    print("| phi | " + " | ".join(f"k={k}" for k in range(6, 13)) + " | native FP64 |")
+    print("|---|" + "---|" * 8)
+    for phi in (0.5, 1.0, 2.0):
+        A, B = inputs.phi_pair(n, n, n, phi, seed=0)
+        hi, lo = oracle.dot2_gemm(A, B)
+        absab = np.abs(A) @ np.abs(B)
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        row = []
+        for k in range(6, 13):
+            D = ozimmu.dgemm(dA, dB, k).cpu().numpy()
+            row.append(float((np.abs((D - hi) - lo) / absab).max()))
+        nat = torch.mm(dA, dB).cpu().numpy()
+        e_nat = float((np.abs((nat - hi) - lo) / absab).max())
+        print(f"| {phi} | " + " | ".join(f"{e:.2e}" for e in row) + f" | {e_nat:.2e} |")
+    print()
+
+
+def phases(m, n, p, phi, ks, reps=5):
+    import torch
+    from paper_2409_13313_amd import inputs, ozimmu
+    A, B = inputs.phi_pair(m, n, p, phi, seed=0)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    beta, r = ozimmu.params(n)
+    print(f"### phases, m={m} n={n} p={p}, phi={phi} (beta={beta}, r={r}); median of {reps}, ms\n")
+    print("| k | products | chunks | split A | split B | chunk GEMMs (INT32 out) | FP64 accumulation (separate) | "
+          "fused GEMM+accumulation | ozimmu_dgemm | effective TFLOP/s | INT8 TOP/s of fused phase |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    D = torch.empty((m, p), dtype=torch.float64, device="cuda")
+    C = torch.empty((m, p), dtype=torch.int32, device="cuda")
+    scratch = ozimmu.alloc_scratch()
+    for k in ks:
+        SA, eA = ozimmu.split_A(dA, k)
+        SB, eB = ozimmu.split_B(dB, k)
+        ws = ozimmu.alloc_workspace(m, n, p, k)
+        sched = [(g, s0, min(s0 + r - 1, g - 1)) for g in range(2, k + 2) for s0 in range(1, g, r)]
+
+        def gemms():
+            for (g, s0, s1) in sched:
+                ozimmu.gemm_group(m, n, p, SA, k, SB, k, g, s0, s1, C=C, scratch=scratch)
+
+        def accs():
+            for i, (g, s0, s1) in enumerate(sched):
+                ozimmu.accumulate(C, eA, eB, beta, g, i == 0, D)
+
+        def fused():
+            for i, (g, s0, s1) in enumerate(sched):
+                ozimmu.gemm_group_accumulate(m, n, p, SA, k, SB, k, g, s0, s1, eA, eB, i == 0, D, scratch=scratch)
+
+        ozimmu.dgemm(dA, dB, k, D=D, workspace=ws)
+        torch.cuda.synchronize()
+        t_sa = _median_ms(lambda: ozimmu.split_A(dA, k), reps)
+        t_sb = _median_ms(lambda: ozimmu.split_B(dB, k), reps)
+        t_g = _median_ms(gemms, reps)
+        t_a = _median_ms(accs, reps)
+        t_f = _median_ms(fused, reps)
+        t_all = _median_ms(lambda: ozimmu.dgemm(dA, dB, k, D=D, workspace=ws), reps)
+        pairs = k * (k + 1) // 2
+        print(f"| {k} | {pairs} | {len(sched)} | {t_sa:.3f} | {t_sb:.3f} | {t_g:.3f} | {t_a:.3f} | {t_f:.3f} | "
+              f"{t_all:.3f} | {2.0 * m * n * p / t_all / 1e9:.1f} | {2.0 * m * n * p * pairs / t_f / 1e9:.0f} |")
+        del SA, SB, ws
+    print()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--accuracy", action="store_true")
+    ap.add_argument("--phases", action="store_true")
+    ap.add_argument("--long-inner", action="store_true")
+    args = ap.parse_args()
+    import torch
+    if not torch.cuda.is_available():
+        print("report.py needs a GPU", file=sys.stderr)
+        return 3
+    if args.accuracy:
+        accuracy()
+    if args.phases:
+        phases(8192, 8192, 8192, 0.5, [6, 8, 10])
+    if args.long_inner:
+        phases(4096, 65536, 4096, 1.0, [10], reps=3)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

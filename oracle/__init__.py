@@ -66,6 +66,8 @@ def _load():
         lib.oz_dgemm.restype = _i64
         lib.oz_dot2_gemm.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp, _vp]
         lib.oz_dot2_gemm.restype = None
+        lib.oz_axpby.argtypes = [_i64, _i64, ctypes.c_double, _vp, ctypes.c_double, _vp]
+        lib.oz_axpby.restype = None
         lib.oz_num_threads.argtypes = []
         lib.oz_num_threads.restype = _int
         _lib = lib
@@ -200,6 +202,19 @@ def dgemm_sub(A: np.ndarray, B: np.ndarray, k: int, I: Sequence[int], J: Sequenc
     of B, because scales are per row of A / per column of B and the inner
     dimension (hence beta and r) is unchanged."""
     return dgemm(np.ascontiguousarray(A[np.asarray(I)]), np.ascontiguousarray(B[:, np.asarray(J)]), k)
+
+
+def gemm_ex(transA: bool, transB: bool, alpha: float, A: np.ndarray, B: np.ndarray, beta: float,
+            C: np.ndarray, k: int) -> np.ndarray:
+    """C <- alpha * op(A) op(B) + beta * C with the product emulated by k slices
+    [steps (i)-(v) of Section 1]; op(X) = X or X^T.  Returns the new C."""
+    opA = np.ascontiguousarray(A.T if transA else A, dtype=np.float64)
+    opB = np.ascontiguousarray(B.T if transB else B, dtype=np.float64)
+    D = dgemm(opA, opB, k)
+    out = np.array(C, dtype=np.float64, order="C", copy=True)
+    assert out.shape == D.shape
+    _load().oz_axpby(D.shape[0], D.shape[1], float(alpha), _p(D), float(beta), _p(out))
+    return out
 
 
 def dot2_gemm(A: np.ndarray, B: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:

@@ -364,3 +364,26 @@ int oz_num_threads(void)
     return 1;
 #endif
 }
+
+/* ------------------------------------------------------------------ */
+/* Step (v): C <- alpha D + beta C                                     */
+/* ------------------------------------------------------------------ */
+
+/* The fifth step of the scheme when a GEMM routine is emulated (Section 1):
+ * C <- alpha * D + beta * C with D the emulated product.  The paper gives no
+ * rounding order; the reading taken is the plain one, three rounded FP64
+ * operations per element, t1 = fl(alpha d), t2 = fl(beta c), c = fl(t1 + t2),
+ * no fused multiply-add, and the BLAS convention that beta == 0 means C is not
+ * read (c = fl(alpha d), so that NaN or Inf in the old C does not propagate). */
+void oz_axpby(int64_t m, int64_t p, double alpha, const double *D, double beta, double *C)
+{
+    for (int64_t x = 0; x < m * p; ++x) {
+        volatile double t1 = alpha * D[x];
+        if (beta == 0.0) {
+            C[x] = t1;
+        } else {
+            volatile double t2 = beta * C[x];
+            C[x] = t1 + t2;
+        }
+    }
+}

@@ -92,6 +92,25 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p,
                           int k, void *workspace, size_t workspace_bytes, void *stream,
                           void *const *events);
 
+/* Steps (i)-(v): C <- alpha * op(A) op(B) + beta * C, the GEMM-routine form of the scheme (Section 1,
+ * step (v)), with op(X) = X (trans == 0) or X^T (trans != 0).
+ *   op(A) is m x n: A is stored row-major m x n (lda >= n) or, transposed, n x m (lda >= m).
+ *   op(B) is n x p: B is stored row-major n x p (ldb >= p) or, transposed, p x n (ldb >= n).
+ *   C       device, m x p row-major, ldc >= p; read unless beta == 0, then overwritten.
+ *   workspace  device, >= ozimmu_workspace_bytes_ex(m,n,p,k) bytes, 256-byte aligned.
+ * The product D is formed exactly as by ozimmu_dgemm; then, per element, t1 = fl(alpha d),
+ * t2 = fl(beta c), c = fl(t1 + t2) (three rounded FP64 operations, no fused multiply-add); with
+ * beta == 0 the old C is not read and c = fl(alpha d).  Transposition costs nothing: a transposed
+ * operand is split by the kernel that otherwise handles the other operand.
+ * m == 0 or p == 0: nothing to do; n == 0: C <- beta C (or +0 when beta == 0). */
+int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p,
+                   double alpha, const double *A, int64_t lda, const double *B, int64_t ldb,
+                   double beta, double *C, int64_t ldc,
+                   int k, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of device workspace ozimmu_gemm_ex needs (ozimmu_dgemm's plus an m x p FP64 buffer); host. */
+size_t ozimmu_workspace_bytes_ex(int64_t m, int64_t n, int64_t p, int k);
+
 /* ---- phase-level entry points (the same kernels ozimmu_dgemm runs) ---- */
 
 /* Steps (i): eA[i] = ceil(log2 max_j |a_ij|) (0 for an all-zero row) and the k

@@ -188,6 +188,71 @@ int ozimmu_export_slices(int64_t rows, int64_t n, int k, const int8_t* packed, i
     return hip_status(ozk::launch_export(rows, n, k, packed, out, (hipStream_t)stream));
 }
 
+size_t ozimmu_workspace_bytes_ex(int64_t m, int64_t n, int64_t p, int k)
+{
+    if (m < 0 || n < 0 || p < 0 || k < 0) return 0;
+    return ozimmu_workspace_bytes(m, n, p, k) + (size_t)align256(8 * m * p);
+}
+
+int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, double alpha, const double* A,
+                   int64_t lda, const double* B, int64_t ldb, double beta, double* C, int64_t ldc, int k,
+                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
+    if (lda < (transA ? m : n) || ldb < (transB ? n : p) || ldc < p) return OZIMMU_ERR_DIM;
+    if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
+    if (m == 0 || p == 0) return OZIMMU_OK;
+    if (!C) return OZIMMU_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    if (n == 0) {  // empty product: C <- beta C
+        if (beta == 0.0) return hip_status(ozk::launch_fill_zero_f64(m, p, C, ldc, st));
+        return hip_status(ozk::launch_axpby(m, p, 0.0, nullptr, 0, beta, C, ldc, st));
+    }
+    if (!A || !B || !workspace) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < ozimmu_workspace_bytes_ex(m, n, p, k))
+        return OZIMMU_ERR_WORKSPACE;
+
+    const int bt = beta_of(n);
+    const int64_t r = r_of(n, bt);
+    char* ws = static_cast<char*>(workspace);
+    void* scratch = ws;
+    ws += align256(OZIMMU_SCRATCH_BYTES);
+    int32_t* eA = reinterpret_cast<int32_t*>(ws);
+    ws += align256(4 * m);
+    int32_t* eB = reinterpret_cast<int32_t*>(ws);
+    ws += align256(4 * p);
+    int8_t* SA = reinterpret_cast<int8_t*>(ws);
+    ws += ozimmu_slices_bytes(m, n, k);
+    int8_t* SB = reinterpret_cast<int8_t*>(ws);
+    ws += ozimmu_slices_bytes(p, n, k);
+    double* Dw = reinterpret_cast<double*>(ws);
+
+    // op(A): one scale per row of op(A).  Stored transposed (n x m), those rows are the columns of the
+    // stored matrix, which is what the column-wise split kernel handles; likewise for op(B).
+    hipError_t e = transA ? ozk::launch_split_B(n, m, A, lda, k, bt, SA, eA, st)
+                          : ozk::launch_split_A(m, n, A, lda, k, bt, SA, eA, st);
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+    e = transB ? ozk::launch_split_A(p, n, B, ldb, k, bt, SB, eB, st)
+               : ozk::launch_split_B(n, p, B, ldb, k, bt, SB, eB, st);
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+
+    const bool direct = (alpha == 1.0 && beta == 0.0);  // D is C
+    const int r_eff = (int)(r < k ? r : k);
+    ozk::GemmArgs a = make_args(m, n, p, SA, SB, 2, k + 1, r_eff, 0, 0, scratch);
+    a.D = direct ? C : Dw;
+    a.ldd = direct ? ldc : p;
+    a.eA = eA;
+    a.eB = eB;
+    a.first = 1;
+    e = ozk::launch_gemm(a, 1, st);
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+    if (!direct) {
+        e = ozk::launch_axpby(m, p, alpha, Dw, p, beta, C, ldc, st);
+        if (e != hipSuccess) return OZIMMU_ERR_HIP;
+    }
+    return OZIMMU_OK;
+}
+
 int ozimmu_dgemm(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
                  double* D, int64_t ldd, int k, void* workspace, size_t workspace_bytes, void* stream)
 {

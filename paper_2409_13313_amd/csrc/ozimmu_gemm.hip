@@ -408,6 +408,26 @@ __global__ __launch_bounds__(256) void k_zero_f64(int64_t m, int64_t p, double* 
     if (j < p && i < m) D[i * ldd + j] = 0.0;
 }
 
+// Step (v) of the scheme: c <- fl(fl(alpha d) + fl(beta c)); beta == 0 leaves the old c unread.
+// HBM-bound: 8 bytes read (16 with beta != 0) and 8 written per element.
+__global__ __launch_bounds__(256) void k_axpby(int64_t m, int64_t p, double alpha, const double* __restrict__ D,
+                                               int64_t ldd, double beta, double* __restrict__ C, int64_t ldc)  // D == nullptr: D = 0
+{
+    const int64_t j = (int64_t)blockIdx.y * 256 + threadIdx.x;
+    const int64_t i0 = (int64_t)blockIdx.x * 8;
+    if (j >= p) return;
+    for (int64_t i = i0; i < i0 + 8 && i < m; ++i) {
+        const double t1 = D ? alpha * D[i * ldd + j] : 0.0;
+        double* c = C + i * ldc + j;
+        if (beta == 0.0) {
+            *c = t1;
+        } else {
+            const double t2 = beta * *c;
+            *c = t1 + t2;
+        }
+    }
+}
+
 // zero the soft-barrier counters (a kernel rather than a memset so that the call can be captured in a graph)
 __global__ void k_fill_u32_gemm(unsigned* x) { x[threadIdx.x] = 0u; }
 
@@ -454,6 +474,14 @@ hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc
 {
     dim3 grid((unsigned)((m + 7) / 8), (unsigned)((p + 255) / 256));
     hipLaunchKernelGGL(k_accumulate, grid, dim3(256), 0, st, m, p, C, ldc, eA, eB, shift, first, D, ldd);
+    return hipGetLastError();
+}
+
+hipError_t launch_axpby(int64_t m, int64_t p, double alpha, const double* D, int64_t ldd, double beta, double* C,
+                        int64_t ldc, hipStream_t st)
+{
+    dim3 grid((unsigned)((m + 7) / 8), (unsigned)((p + 255) / 256));
+    hipLaunchKernelGGL(k_axpby, grid, dim3(256), 0, st, m, p, alpha, D, ldd, beta, C, ldc);
     return hipGetLastError();
 }
 

@@ -39,6 +39,11 @@ _lib.ozimmu_dgemm.restype = _int
 _lib.ozimmu_dgemm_profiled.argtypes = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _vp, _sz, _vp,
                                        ctypes.POINTER(_vp)]
 _lib.ozimmu_dgemm_profiled.restype = _int
+_lib.ozimmu_gemm_ex.argtypes = [_int, _int, _i64, _i64, _i64, ctypes.c_double, _vp, _i64, _vp, _i64, ctypes.c_double,
+                                _vp, _i64, _int, _vp, _sz, _vp]
+_lib.ozimmu_gemm_ex.restype = _int
+_lib.ozimmu_workspace_bytes_ex.argtypes = [_i64, _i64, _i64, _int]
+_lib.ozimmu_workspace_bytes_ex.restype = _sz
 _lib.ozimmu_split_A.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_split_A.restype = _int
 _lib.ozimmu_split_B.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp]
@@ -54,7 +59,7 @@ _lib.ozimmu_export_slices.argtypes = [_i64, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_export_slices.restype = _int
 
 EXPORTS = ["ozimmu_status_string", "ozimmu_params", "ozimmu_num_chunks", "ozimmu_slices_bytes",
-           "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_dgemm_profiled", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
+           "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_dgemm_profiled", "ozimmu_gemm_ex", "ozimmu_workspace_bytes_ex", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
            "ozimmu_accumulate", "ozimmu_gemm_group_accumulate", "ozimmu_export_slices"]
 
 
@@ -144,6 +149,23 @@ def dgemm_profiled(A: torch.Tensor, B: torch.Tensor, k: int, D: torch.Tensor, wo
     _check(_lib.ozimmu_dgemm_profiled(m, n, p, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), D.data_ptr(), _ld(D), k,
                                       workspace.data_ptr(), workspace.numel(), _stream(), handles))
     return D
+
+
+def gemm_ex(transA: bool, transB: bool, alpha: float, A: torch.Tensor, B: torch.Tensor, beta: float,
+            C: torch.Tensor, k: int, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """C <- alpha * op(A) op(B) + beta * C in place (product emulated with k slices)."""
+    _dev(A, torch.float64), _dev(B, torch.float64), _dev(C, torch.float64)
+    m, n = (A.shape[1], A.shape[0]) if transA else A.shape
+    n2, p = (B.shape[1], B.shape[0]) if transB else B.shape
+    if n != n2 or tuple(C.shape) != (m, p):
+        raise ValueError("shapes do not match")
+    if workspace is None:
+        workspace = torch.empty(max(int(_lib.ozimmu_workspace_bytes_ex(m, n, p, k)), 256), dtype=torch.uint8,
+                                device=A.device)
+    _check(_lib.ozimmu_gemm_ex(1 if transA else 0, 1 if transB else 0, m, n, p, alpha, A.data_ptr(), _ld(A),
+                               B.data_ptr(), _ld(B), beta, C.data_ptr(), _ld(C), k, workspace.data_ptr(),
+                               workspace.numel(), _stream()))
+    return C
 
 
 def split_A(A: torch.Tensor, k: int) -> Tuple[torch.Tensor, torch.Tensor]:

@@ -1,0 +1,59 @@
+"""GPU parity for the GEMM-routine form C <- alpha op(A) op(B) + beta C against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2409_13313_amd import inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def oz():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: the HIP path has no CPU fallback")
+    from paper_2409_13313_amd import ozimmu
+    return ozimmu
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+@pytest.mark.parametrize("transA", [False, True])
+@pytest.mark.parametrize("transB", [False, True])
+@pytest.mark.parametrize("alpha,beta", [(1.0, 0.0), (1.0 / 3.0, -0.7), (0.0, 2.0), (-2.0, 1.0)])
+def test_gemm_ex_matches_oracle_bit_for_bit(oz, transA, transB, alpha, beta):
+    m, n, p, k = 300, 520, 270, 7
+    A, B = inputs.phi_pair(m, n, p, 1.0, seed=51)
+    C0 = np.random.Generator(np.random.PCG64(52)).standard_normal((m, p))
+    if beta == 0.0:
+        C0[0, 0] = np.nan          # must not propagate: the old C is not read
+    As = np.ascontiguousarray(A.T) if transA else A
+    Bs = np.ascontiguousarray(B.T) if transB else B
+    want = oracle.gemm_ex(transA, transB, alpha, As, Bs, beta, C0, k)
+    # leading dimensions larger than the extents, and a poisoned frame around C
+    Ab = torch.zeros((As.shape[0], As.shape[1] + 3), dtype=torch.float64, device="cuda")
+    Bb = torch.zeros((Bs.shape[0], Bs.shape[1] + 5), dtype=torch.float64, device="cuda")
+    Cb = torch.full((m + 1, p + 2), -3.0, dtype=torch.float64, device="cuda")
+    Ab[:, :As.shape[1]] = dev(As)
+    Bb[:, :Bs.shape[1]] = dev(Bs)
+    Cb[:m, :p] = dev(C0)
+    oz.gemm_ex(transA, transB, alpha, Ab[:, :As.shape[1]], Bb[:, :Bs.shape[1]], beta, Cb[:m, :p], k)
+    got = Cb.cpu().numpy()
+    assert np.isfinite(got[:m, :p]).all()
+    assert np.abs(got[:m, :p] - want).max() <= 2 * np.spacing(np.abs(want)).max()
+    assert np.array_equal(got[:m, :p], want)
+    assert (got[m:, :] == -3.0).all() and (got[:, p:] == -3.0).all()
+
+
+def test_gemm_ex_empty_inner_dimension_scales_c(oz):
+    C0 = np.random.Generator(np.random.PCG64(53)).standard_normal((5, 7))
+    C = dev(C0)
+    oz.gemm_ex(False, False, 1.5, torch.empty((5, 0), dtype=torch.float64, device="cuda"),
+               torch.empty((0, 7), dtype=torch.float64, device="cuda"), 0.25, C, 8)
+    assert np.array_equal(C.cpu().numpy(), 0.25 * C0)
+    oz.gemm_ex(False, False, 1.5, torch.empty((5, 0), dtype=torch.float64, device="cuda"),
+               torch.empty((0, 7), dtype=torch.float64, device="cuda"), 0.0, C, 8)
+    assert (C == 0).all()

@@ -66,6 +66,12 @@ def _load():
         lib.oz_dgemm.restype = _i64
         lib.oz_dot2_gemm.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp, _vp]
         lib.oz_dot2_gemm.restype = None
+        lib.oz_dgemm_variant.argtypes = [_i64, _i64, _i64, _vp, _vp, _int, _int, _int, _vp, _vp]
+        lib.oz_dgemm_variant.restype = _i64
+        lib.oz_exponents_floor.argtypes = [_i64, _i64, _vp, _int, _vp]
+        lib.oz_exponents_floor.restype = None
+        lib.oz_r_wide.argtypes = [_i64, _int]
+        lib.oz_r_wide.restype = _i64
         lib.oz_axpby.argtypes = [_i64, _i64, ctypes.c_double, _vp, ctypes.c_double, _vp]
         lib.oz_axpby.restype = None
         lib.oz_num_threads.argtypes = []
@@ -111,6 +117,23 @@ def col_exponents(B: np.ndarray) -> np.ndarray:
     return e
 
 
+_FORMS = {"int": 0, "sigma": 1, "bitmask": 2}
+
+
+def exponents_floor(X: np.ndarray, by_col: bool) -> np.ndarray:
+    """floor(log2 max |x|) per row (or per column) of X  [Algorithm 3, line 2]; 0 for a zero vector."""
+    X = _c(X, np.float64)
+    rows, cols = X.shape
+    e = np.empty(cols if by_col else rows, dtype=np.int32)
+    _load().oz_exponents_floor(rows, cols, _p(X), 1 if by_col else 0, _p(e))
+    return e
+
+
+def r_wide(n: int, beta: int) -> int:
+    """Products of round-to-nearest slices that fit one INT32 accumulator (option beyond the paper)."""
+    return int(_load().oz_r_wide(int(n), int(beta)))
+
+
 def split_rows(A: np.ndarray, k: int, beta: int, form: str = "int",
                eA: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
     """INT8 slices SA[k][m][n] of A and its row exponents  [Algorithm 8].
@@ -119,9 +142,11 @@ def split_rows(A: np.ndarray, k: int, beta: int, form: str = "int",
     floating-point recipe of Algorithm 8 ((a + sigma) - sigma)."""
     A = _c(A, np.float64)
     m, n = A.shape
-    eA = row_exponents(A) if eA is None else _c(eA, np.int32)
+    if eA is None:
+        eA = exponents_floor(A, by_col=False) if form == "bitmask" else row_exponents(A)
+    eA = _c(eA, np.int32)
     S = np.empty((k, m, n), dtype=np.int8)
-    _load().oz_split_rows(m, n, _p(A), _p(eA), int(beta), int(k), 0 if form == "int" else 1, _p(S))
+    _load().oz_split_rows(m, n, _p(A), _p(eA), int(beta), int(k), _FORMS[form], _p(S))
     return S, eA
 
 
@@ -130,9 +155,11 @@ def split_cols(B: np.ndarray, k: int, beta: int, form: str = "int",
     """INT8 slices SB[k][n][p] of B and its column exponents  [Algorithm 8 on B^T]."""
     B = _c(B, np.float64)
     n, p = B.shape
-    eB = col_exponents(B) if eB is None else _c(eB, np.int32)
+    if eB is None:
+        eB = exponents_floor(B, by_col=True) if form == "bitmask" else col_exponents(B)
+    eB = _c(eB, np.int32)
     S = np.empty((k, n, p), dtype=np.int8)
-    _load().oz_split_cols(n, p, _p(B), _p(eB), int(beta), int(k), 0 if form == "int" else 1, _p(S))
+    _load().oz_split_cols(n, p, _p(B), _p(eB), int(beta), int(k), _FORMS[form], _p(S))
     return S, eB
 
 
@@ -190,6 +217,28 @@ def dgemm(A: np.ndarray, B: np.ndarray, k: int, return_addends: bool = False):
     D = np.empty((m, p), dtype=np.float64)
     w = _i64(0)
     rc = _load().oz_dgemm(m, n, p, _p(A), _p(B), int(k), _p(D), ctypes.byref(w))
+    if rc < 0:
+        raise ValueError("arguments outside the method's domain")
+    if rc > 0:
+        raise OverflowError(f"{rc} INT32 overflows")
+    return (D, int(w.value)) if return_addends else D
+
+
+def dgemm_variant(A: np.ndarray, B: np.ndarray, k: int, split: str = "rn", accumulate: str = "grouped",
+                  return_addends: bool = False):
+    """The variants compared in Section 4: split "rn" (Algorithm 8) or "bitmask" (Algorithm 3);
+    accumulate "grouped" (Algorithm 6, r of eq. (def_r)), "per_pair" (Algorithm 4) or "wide"
+    (chunks of r_wide products, round-to-nearest slices only; beyond the paper).
+    ("rn","grouped") = ozIMMU_H, ("bitmask","grouped") = ozIMMU_EF, ("bitmask","per_pair") = ozIMMU."""
+    A = _c(A, np.float64)
+    B = _c(B, np.float64)
+    m, n = A.shape
+    n2, p = B.shape
+    assert n == n2
+    D = np.empty((m, p), dtype=np.float64)
+    w = _i64(0)
+    rc = _load().oz_dgemm_variant(m, n, p, _p(A), _p(B), int(k), {"rn": 0, "bitmask": 1}[split],
+                                  {"grouped": 0, "per_pair": 1, "wide": 2}[accumulate], _p(D), ctypes.byref(w))
     if rc < 0:
         raise ValueError("arguments outside the method's domain")
     if rc > 0:

@@ -102,6 +102,24 @@ void oz_row_exponents(int64_t m, int64_t n, const double *A, int32_t *eA)
     }
 }
 
+/* Scale exponents of the bit-mask split of the earlier ozIMMU method: floor instead of ceil,
+ * mu''_i = 2^floor(log2 max_j |a_ij|)                                  [Algorithm 3, line 2]
+ * (x = f * 2^t with f in [0.5, 1) has floor(log2 x) = t - 1).  cols != 0: per column of an n x p matrix. */
+void oz_exponents_floor(int64_t rows, int64_t cols_, const double *X, int by_col, int32_t *e)
+{
+    int64_t nvec = by_col ? cols_ : rows, len = by_col ? rows : cols_;
+    for (int64_t v = 0; v < nvec; ++v) {
+        double mx = 0.0;
+        for (int64_t l = 0; l < len; ++l) {
+            double x = fabs(by_col ? X[l * cols_ + v] : X[v * cols_ + l]);
+            if (x > mx) mx = x;
+        }
+        int t = 0;
+        if (mx > 0.0) { (void)frexp(mx, &t); t -= 1; }
+        e[v] = t;
+    }
+}
+
 /* eB[j] = ceil(log2 max_i |b_ij|): B is split as the transpose of the split
  * of B^T (Section 2, remark after eq. (splitB')), i.e. one scale per column. */
 void oz_col_exponents(int64_t n, int64_t p, const double *B, int32_t *eB)
@@ -178,16 +196,51 @@ static void split_one_sigma(double a, int e, int beta, int k, int8_t *q, int64_t
     }
 }
 
+/* Bit-mask slices of ONE number a with scale exponent e = floor(log2 max) (|a| < 2^(e+1)):
+ * slice s holds the s-th group of beta bits of |a| below 2^(e+1), with the sign of a, i.e. the
+ * remainder divided by the grid 2^(e+1-s*beta) and truncated toward zero; |q_s| <= 2^beta - 1.
+ *                                           [Algorithm 3, line 4; eq. (splitA'')]
+ * The paper describes the earlier method only this far ("extract the s-th beta bits of the mantissa
+ * via bit masking"); truncation toward zero of a sign-magnitude number is that operation. */
+static void split_one_trunc(double a, int e, int beta, int k, int8_t *q, int64_t stride)
+{
+    int t;
+    double f = frexp(a, &t);
+    int64_t N = (int64_t)ldexp(f, 53);
+    int X = t - 53;
+    for (int s = 1; s <= k; ++s) {
+        int gexp = e + 1 - s * beta;
+        int d = gexp - X;
+        int64_t qs;
+        if (N == 0) {
+            qs = 0;
+        } else if (d <= 0) {
+            qs = N * ((int64_t)1 << (-d));
+            N = 0;
+        } else if (d >= 62) {
+            qs = 0;
+        } else {
+            int64_t mag = N < 0 ? -N : N;
+            int64_t qm = mag >> d;                 /* floor of the magnitude */
+            qs = N < 0 ? -qm : qm;
+            N -= qs * ((int64_t)1 << d);
+        }
+        q[(int64_t)(s - 1) * stride] = (int8_t)qs;
+    }
+}
+
 /* Slices of all of A: SA[s-1][i][j], s = 1..k, with row exponents eA given.
- * form = 0: integer form, form = 1: Algorithm 8's floating-point form. */
+ * form = 0: integer form, form = 1: Algorithm 8's floating-point form, form = 2: bit-mask slices
+ * of Algorithm 3 (eA must then hold floor exponents). */
 void oz_split_rows(int64_t m, int64_t n, const double *A, const int32_t *eA,
                    int beta, int k, int form, int8_t *SA)
 {
     int64_t stride = m * n;
     for (int64_t i = 0; i < m; ++i)
         for (int64_t j = 0; j < n; ++j) {
-            if (form == 0) split_one_int(A[i * n + j], eA[i], beta, k, SA + i * n + j, stride);
-            else           split_one_sigma(A[i * n + j], eA[i], beta, k, SA + i * n + j, stride);
+            if (form == 0)      split_one_int(A[i * n + j], eA[i], beta, k, SA + i * n + j, stride);
+            else if (form == 1) split_one_sigma(A[i * n + j], eA[i], beta, k, SA + i * n + j, stride);
+            else                split_one_trunc(A[i * n + j], eA[i], beta, k, SA + i * n + j, stride);
         }
 }
 
@@ -198,8 +251,9 @@ void oz_split_cols(int64_t n, int64_t p, const double *B, const int32_t *eB,
     int64_t stride = n * p;
     for (int64_t i = 0; i < n; ++i)
         for (int64_t j = 0; j < p; ++j) {
-            if (form == 0) split_one_int(B[i * p + j], eB[j], beta, k, SB + i * p + j, stride);
-            else           split_one_sigma(B[i * p + j], eB[j], beta, k, SB + i * p + j, stride);
+            if (form == 0)      split_one_int(B[i * p + j], eB[j], beta, k, SB + i * p + j, stride);
+            else if (form == 1) split_one_sigma(B[i * p + j], eB[j], beta, k, SB + i * p + j, stride);
+            else                split_one_trunc(B[i * p + j], eB[j], beta, k, SB + i * p + j, stride);
         }
 }
 
@@ -264,21 +318,39 @@ void oz_accumulate(int64_t m, int64_t p, const int32_t *C,
 /* Whole path                                                          */
 /* ------------------------------------------------------------------ */
 
-/* D = A B emulated with k slices.            [Algorithm 8 + Algorithm 6]
+/* Largest power of two r_w with r_w * n * (2^(beta-1))^2 <= 2^31 - 1: the number of products of
+ * round-to-nearest slices (|q| <= 2^(beta-1), tighter than the 2^beta - 1 behind eq. (def_r)) that
+ * can share an INT32 accumulator.  An option beyond the paper; never below the paper's r. */
+int64_t oz_r_wide(int64_t n, int beta)
+{
+    int64_t r = 1;
+    const int64_t lim = ((int64_t)1 << 31) - 1;
+    while (2 * r * n * ((int64_t)1 << (2 * beta - 2)) <= lim) r *= 2;
+    return r;
+}
+
+/* D = A B emulated with k slices, in the variants the paper compares (Section 4):
+ *   split_mode 0: round-to-nearest slices, one scale per row/column     [Algorithm 8]
+ *   split_mode 1: bit-mask slices                                        [Algorithm 3]
+ *   r_mode 0: chunks of r products, eq. (def_r)                         [Algorithm 6]
+ *   r_mode 1: one FP64 addition per slice pair                           [Algorithm 4]
+ *   r_mode 2: chunks of oz_r_wide products (split_mode 0 only; beyond the paper)
+ * (0,0) = ozIMMU_H, (1,0) = ozIMMU_EF, (1,1) = ozIMMU.
  * A is m x n, B is n x p, both dense row-major; D (m x p) is overwritten.
  * Returns 0, or -1 for arguments outside the method's domain, or the number
  * of INT32 overflows (never expected).  *n_addends (optional) receives the
  * number of FP64 additions per element of D. */
-int64_t oz_dgemm(int64_t m, int64_t n, int64_t p, const double *A, const double *B,
-                 int k, double *D, int64_t *n_addends)
+int64_t oz_dgemm_variant(int64_t m, int64_t n, int64_t p, const double *A, const double *B,
+                         int k, int split_mode, int r_mode, double *D, int64_t *n_addends)
 {
     if (m < 0 || n < 0 || p < 0 || k < 1) return -1;
+    if (split_mode < 0 || split_mode > 1 || r_mode < 0 || r_mode > 2 || (r_mode == 2 && split_mode != 0)) return -1;
     for (int64_t x = 0; x < m * p; ++x) D[x] = 0.0;
     if (n_addends) *n_addends = 0;
     if (m == 0 || p == 0 || n == 0) return 0;
     int beta = oz_beta(n);
     if (beta < 1) return -1;
-    int64_t r = oz_r(n, beta);
+    int64_t r = r_mode == 0 ? oz_r(n, beta) : (r_mode == 1 ? 1 : oz_r_wide(n, beta));
 
     int32_t *eA = (int32_t *)malloc((size_t)m * sizeof(int32_t));
     int32_t *eB = (int32_t *)malloc((size_t)p * sizeof(int32_t));
@@ -286,10 +358,17 @@ int64_t oz_dgemm(int64_t m, int64_t n, int64_t p, const double *A, const double 
     int8_t *SB = (int8_t *)malloc((size_t)k * n * p);
     int32_t *C = (int32_t *)malloc((size_t)m * p * sizeof(int32_t));
 
-    oz_row_exponents(m, n, A, eA);
-    oz_col_exponents(n, p, B, eB);
-    oz_split_rows(m, n, A, eA, beta, k, 0, SA);
-    oz_split_cols(n, p, B, eB, beta, k, 0, SB);
+    if (split_mode == 0) {
+        oz_row_exponents(m, n, A, eA);
+        oz_col_exponents(n, p, B, eB);
+        oz_split_rows(m, n, A, eA, beta, k, 0, SA);
+        oz_split_cols(n, p, B, eB, beta, k, 0, SB);
+    } else {
+        oz_exponents_floor(m, n, A, 0, eA);
+        oz_exponents_floor(n, p, B, 1, eB);
+        oz_split_rows(m, n, A, eA, beta, k, 2, SA);
+        oz_split_cols(n, p, B, eB, beta, k, 2, SB);
+    }
 
     int64_t bad = 0, w = 0;
     int first = 1;
@@ -311,6 +390,13 @@ int64_t oz_dgemm(int64_t m, int64_t n, int64_t p, const double *A, const double 
     if (n_addends) *n_addends = w;
     free(eA); free(eB); free(SA); free(SB); free(C);
     return bad;
+}
+
+/* D = A B emulated with k slices.            [Algorithm 8 + Algorithm 6] */
+int64_t oz_dgemm(int64_t m, int64_t n, int64_t p, const double *A, const double *B,
+                 int k, double *D, int64_t *n_addends)
+{
+    return oz_dgemm_variant(m, n, p, A, B, k, 0, 0, D, n_addends);
 }
 
 /* ------------------------------------------------------------------ */

@@ -92,6 +92,26 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p,
                           int k, void *workspace, size_t workspace_bytes, void *stream,
                           void *const *events);
 
+/* The variants the paper compares (Section 4), through the same kernels:
+ *   split_mode       OZIMMU_SPLIT_NEAREST  round-to-nearest slices, ceil exponent     [Algorithm 8]
+ *                    OZIMMU_SPLIT_BITMASK  bit-mask digits (truncation), floor exponent [Algorithm 3]
+ *   accumulate_mode  OZIMMU_ACCUM_GROUPED  chunks of r products, eq. (def_r)          [Algorithm 6]
+ *                    OZIMMU_ACCUM_PER_PAIR one FP64 addition per slice pair            [Algorithm 4]
+ *                    OZIMMU_ACCUM_WIDE     chunks of ozimmu_r_wide(n) products; needs OZIMMU_SPLIT_NEAREST.
+ *                                          Not in the paper: its r is derived for |A''| <= 2^beta - 1, while
+ *                                          round-to-nearest slices obey |A''| <= 2^(beta-1).
+ * (NEAREST, GROUPED) is ozimmu_dgemm (ozIMMU_H); (BITMASK, GROUPED) is ozIMMU_EF; (BITMASK, PER_PAIR) is the
+ * earlier ozIMMU.  Other arguments as for ozimmu_dgemm; an invalid mode returns OZIMMU_ERR_SLICES. */
+enum { OZIMMU_SPLIT_NEAREST = 0, OZIMMU_SPLIT_BITMASK = 1 };
+enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 2 };
+int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p,
+                         const double *A, int64_t lda, const double *B, int64_t ldb,
+                         double *D, int64_t ldd, int k, int split_mode, int accumulate_mode,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Largest power of two r_w with r_w * n * (2^(beta-1))^2 <= 2^31 - 1 (0 for n outside 1..2^29); host. */
+int64_t ozimmu_r_wide(int64_t n);
+
 /* Steps (i)-(v): C <- alpha * op(A) op(B) + beta * C, the GEMM-routine form of the scheme (Section 1,
  * step (v)), with op(X) = X (trans == 0) or X^T (trans != 0).
  *   op(A) is m x n: A is stored row-major m x n (lda >= n) or, transposed, n x m (lda >= m).
@@ -131,6 +151,12 @@ int ozimmu_split_A(int64_t m, int64_t n, const double *A, int64_t lda, int k,
  *   eB      device, int32[p]. */
 int ozimmu_split_B(int64_t n, int64_t p, const double *B, int64_t ldb, int k,
                    int8_t *SB, int32_t *eB, void *stream);
+
+/* ozimmu_split_A / ozimmu_split_B with the split mode of ozimmu_dgemm_variant. */
+int ozimmu_split_A_variant(int64_t m, int64_t n, const double *A, int64_t lda, int k, int split_mode,
+                           int8_t *SA, int32_t *eA, void *stream);
+int ozimmu_split_B_variant(int64_t n, int64_t p, const double *B, int64_t ldb, int k, int split_mode,
+                           int8_t *SB, int32_t *eB, void *stream);
 
 /* Step (iii) for one chunk: C'' <- sum_{s = s0..s1} A''_s B''_{g-s} in INT32
  *                                              [Algorithm 6, lines 7-9].

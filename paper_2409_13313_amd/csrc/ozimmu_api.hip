@@ -29,6 +29,19 @@ int64_t r_of(int64_t n, int beta)
     return ex > 0 ? ((int64_t)1 << ex) : 1;
 }
 
+// largest power of two r_w with r_w * n * (2^(beta-1))^2 <= 2^31 - 1 (round-to-nearest slices obey |q| <= 2^(beta-1))
+int64_t r_wide_of(int64_t n, int beta)
+{
+    int64_t r = 1;
+    const int64_t lim = ((int64_t)1 << 31) - 1;
+    while (2 * r * n * ((int64_t)1 << (2 * beta - 2)) <= lim) r *= 2;
+    return r;
+}
+
+int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
+               double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
+               size_t workspace_bytes, void* stream, void* const* events);
+
 inline int hip_status(hipError_t e) { return e == hipSuccess ? OZIMMU_OK : OZIMMU_ERR_HIP; }
 
 int check_gemm_args(int64_t m, int64_t n, int64_t p, const void* SA, int kA, const void* SB, int kB, int g, int s0,
@@ -121,7 +134,7 @@ int ozimmu_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, in
     if (m == 0 || n == 0) return OZIMMU_OK;
     if (!A || !SA || !eA) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(SA) % 256) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), SA, eA, (hipStream_t)stream));
+    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), 0, SA, eA, (hipStream_t)stream));
 }
 
 int ozimmu_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int8_t* SB, int32_t* eB, void* stream)
@@ -131,7 +144,7 @@ int ozimmu_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, in
     if (p == 0 || n == 0) return OZIMMU_OK;
     if (!B || !SB || !eB) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(SB) % 256) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), SB, eB, (hipStream_t)stream));
+    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), 0, SB, eB, (hipStream_t)stream));
 }
 
 int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA, const int8_t* SB, int kB, int g,
@@ -229,11 +242,11 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
 
     // op(A): one scale per row of op(A).  Stored transposed (n x m), those rows are the columns of the
     // stored matrix, which is what the column-wise split kernel handles; likewise for op(B).
-    hipError_t e = transA ? ozk::launch_split_B(n, m, A, lda, k, bt, SA, eA, st)
-                          : ozk::launch_split_A(m, n, A, lda, k, bt, SA, eA, st);
+    hipError_t e = transA ? ozk::launch_split_B(n, m, A, lda, k, bt, 0, SA, eA, st)
+                          : ozk::launch_split_A(m, n, A, lda, k, bt, 0, SA, eA, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
-    e = transB ? ozk::launch_split_A(p, n, B, ldb, k, bt, SB, eB, st)
-               : ozk::launch_split_B(n, p, B, ldb, k, bt, SB, eB, st);
+    e = transB ? ozk::launch_split_A(p, n, B, ldb, k, bt, 0, SB, eB, st)
+               : ozk::launch_split_B(n, p, B, ldb, k, bt, 0, SB, eB, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
     const bool direct = (alpha == 1.0 && beta == 0.0);  // D is C
@@ -263,6 +276,57 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p, const double* A, int6
                           int64_t ldb, double* D, int64_t ldd, int k, void* workspace, size_t workspace_bytes,
                           void* stream, void* const* events)
 {
+    return dgemm_impl(m, n, p, A, lda, B, ldb, D, ldd, k, OZIMMU_SPLIT_NEAREST, OZIMMU_ACCUM_GROUPED, workspace,
+                      workspace_bytes, stream, events);
+}
+
+int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
+                         double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
+                         size_t workspace_bytes, void* stream)
+{
+    if (split_mode != OZIMMU_SPLIT_NEAREST && split_mode != OZIMMU_SPLIT_BITMASK) return OZIMMU_ERR_SLICES;
+    if (accumulate_mode < OZIMMU_ACCUM_GROUPED || accumulate_mode > OZIMMU_ACCUM_WIDE) return OZIMMU_ERR_SLICES;
+    if (accumulate_mode == OZIMMU_ACCUM_WIDE && split_mode != OZIMMU_SPLIT_NEAREST) return OZIMMU_ERR_SLICES;
+    return dgemm_impl(m, n, p, A, lda, B, ldb, D, ldd, k, split_mode, accumulate_mode, workspace, workspace_bytes,
+                      stream, nullptr);
+}
+
+int ozimmu_split_A_variant(int64_t m, int64_t n, const double* A, int64_t lda, int k, int split_mode, int8_t* SA,
+                           int32_t* eA, void* stream)
+{
+    if (m < 0 || n < 0 || m > MAX_OUTER || n > MAX_INNER || lda < n) return OZIMMU_ERR_DIM;
+    if (k < 1 || k > OZIMMU_MAX_SLICES || (split_mode != 0 && split_mode != 1)) return OZIMMU_ERR_SLICES;
+    if (m == 0 || n == 0) return OZIMMU_OK;
+    if (!A || !SA || !eA) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(SA) % 256) return OZIMMU_ERR_WORKSPACE;
+    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), split_mode, SA, eA, (hipStream_t)stream));
+}
+
+int ozimmu_split_B_variant(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int split_mode, int8_t* SB,
+                           int32_t* eB, void* stream)
+{
+    if (p < 0 || n < 0 || p > MAX_OUTER || n > MAX_INNER || ldb < p) return OZIMMU_ERR_DIM;
+    if (k < 1 || k > OZIMMU_MAX_SLICES || (split_mode != 0 && split_mode != 1)) return OZIMMU_ERR_SLICES;
+    if (p == 0 || n == 0) return OZIMMU_OK;
+    if (!B || !SB || !eB) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(SB) % 256) return OZIMMU_ERR_WORKSPACE;
+    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), split_mode, SB, eB, (hipStream_t)stream));
+}
+
+int64_t ozimmu_r_wide(int64_t n)
+{
+    if (n < 1 || n > MAX_INNER) return 0;
+    return r_wide_of(n, beta_of(n));
+}
+
+}  // extern "C"
+
+namespace {
+
+int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
+               double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
+               size_t workspace_bytes, void* stream, void* const* events)
+{
     if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
     if (lda < n || ldb < p || ldd < p) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
@@ -275,7 +339,9 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p, const double* A, int6
         return OZIMMU_ERR_WORKSPACE;
 
     const int beta = beta_of(n);
-    const int64_t r = r_of(n, beta);
+    const int64_t r = accumulate_mode == OZIMMU_ACCUM_PER_PAIR
+                          ? 1
+                          : (accumulate_mode == OZIMMU_ACCUM_WIDE ? r_wide_of(n, beta) : r_of(n, beta));
     char* ws = static_cast<char*>(workspace);
     void* scratch = ws;
     ws += align256(OZIMMU_SCRATCH_BYTES);
@@ -292,9 +358,9 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p, const double* A, int6
     };
     hipError_t e = mark(0);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
-    e = ozk::launch_split_A(m, n, A, lda, k, beta, SA, eA, st);
+    e = ozk::launch_split_A(m, n, A, lda, k, beta, split_mode, SA, eA, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
-    e = ozk::launch_split_B(n, p, B, ldb, k, beta, SB, eB, st);
+    e = ozk::launch_split_B(n, p, B, ldb, k, beta, split_mode, SB, eB, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     e = mark(1);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
@@ -313,4 +379,4 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p, const double* A, int6
     return hip_status(mark(2));
 }
 
-}  // extern "C"
+}  // namespace

@@ -7,11 +7,12 @@
 
 namespace ozk {
 
-// Step (i): row exponents + slices of A (Algorithm 8).
-hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta,
+// Step (i): row exponents + slices of A.  split_mode 0: round to nearest, ceil exponent (Algorithm 8);
+// 1: bit-mask digits, floor exponent (Algorithm 3).
+hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int split_mode,
                           int8_t* SA, int32_t* eA, hipStream_t st);
-// Step (ii): column exponents + slices of B (Algorithm 8 applied to B^T).
-hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta,
+// Step (ii): column exponents + slices of B (the same applied to B^T).
+hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int split_mode,
                           int8_t* SB, int32_t* eB, hipStream_t st);
 hipError_t launch_export(int64_t rows, int64_t n, int k, const int8_t* packed, int8_t* out, hipStream_t st);
 

@@ -30,11 +30,20 @@ __device__ inline uint32_t exp_key(uint64_t absbits)
     double f = frexp(x, &t);
     return (uint32_t)(2 * (t + 1100) + (f != 0.5 ? 1 : 0));
 }
+// MASK = false: ceil(log2 x) (round-to-nearest split); MASK = true: floor(log2 x) = t - 1 (bit-mask split)
+template <bool MASK>
 __device__ inline int key_to_exp(uint32_t key)
 {
     if (key == 0u) return 0;
     int t = (int)(key >> 1) - 1100;
+    if (MASK) return t - 1;
     return (key & 1u) ? t : t - 1;
+}
+// digit of one slice: nearest integer, ties to even (Algorithm 8) or truncation toward zero (Algorithm 3)
+template <bool MASK>
+__device__ inline double digit(double y)
+{
+    return MASK ? __builtin_trunc(y) : __builtin_rint(y);
 }
 
 __device__ inline uint64_t abs_bits(double x)
@@ -54,11 +63,12 @@ __device__ inline uint64_t wave_max_u64(uint64_t v)
 
 // k slices of 4 consecutive inner elements, packed one dword per slice.
 // y[] enters as x * 2^(beta-1-e).  out advances by slice_stride bytes per slice.
+template <bool MASK>
 __device__ inline void emit_slices4(double y0, double y1, double y2, double y3, int k, double two_beta,
                                     int8_t* out, int64_t slice_stride)
 {
     for (int s = 0; s < k; ++s) {
-        double q0 = __builtin_rint(y0), q1 = __builtin_rint(y1), q2 = __builtin_rint(y2), q3 = __builtin_rint(y3);
+        double q0 = digit<MASK>(y0), q1 = digit<MASK>(y1), q2 = digit<MASK>(y2), q3 = digit<MASK>(y3);
         uint32_t w = ((uint32_t)(int)q0 & 0xffu) | (((uint32_t)(int)q1 & 0xffu) << 8) |
                      (((uint32_t)(int)q2 & 0xffu) << 16) | (((uint32_t)(int)q3 & 0xffu) << 24);
         *reinterpret_cast<uint32_t*>(out) = w;
@@ -78,7 +88,7 @@ __device__ inline void emit_slices4(double y0, double y1, double y2, double y3, 
 // and writes the k slices.  A lane handles 4 consecutive inner elements per
 // 256-element sweep: the wave reads 2 KiB contiguous per sweep.
 // ---------------------------------------------------------------------------
-template <bool VEC>
+template <bool VEC, bool MASK>
 __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const double* __restrict__ A, int64_t lda,
                                                  int k, int beta, int8_t* __restrict__ SA, int32_t* __restrict__ eA,
                                                  int64_t Npad, int64_t slice_stride)
@@ -117,7 +127,7 @@ __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const dou
         }
     }
     mx = wave_max_u64(mx);
-    const int e = key_to_exp(exp_key(mx));
+    const int e = key_to_exp<MASK>(exp_key(mx));
     if (lane == 0) eA[R] = e;
     const int sc = beta - 1 - e;
     const double two_beta = (double)(1 << beta);
@@ -125,7 +135,7 @@ __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const dou
     for (int64_t l = 4 * lane; l < Npad; l += 256) {
         double v[4];
         load4(l, v);
-        emit_slices4(ldexp(v[0], sc), ldexp(v[1], sc), ldexp(v[2], sc), ldexp(v[3], sc), k, two_beta,
+        emit_slices4<MASK>(ldexp(v[0], sc), ldexp(v[1], sc), ldexp(v[2], sc), ldexp(v[3], sc), k, two_beta,
                      SA + packed_offset(R, l, KT), slice_stride);
     }
 }
@@ -168,10 +178,11 @@ __global__ void k_fill_u32(int64_t count, uint32_t* x, uint32_t v)
     if (i < count) x[i] = v;
 }
 
+template <bool MASK>
 __global__ void k_decode_keys(int64_t count, int32_t* e)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) e[i] = key_to_exp((uint32_t)e[i]);
+    if (i < count) e[i] = key_to_exp<MASK>((uint32_t)e[i]);
 }
 
 // ---------------------------------------------------------------------------
@@ -186,6 +197,7 @@ __global__ void k_decode_keys(int64_t count, int32_t* e)
 constexpr int SBATCH = 4;
 constexpr int PITCH = 33;  // dwords per column row in LDS (32 data + 1 pad)
 
+template <bool MASK>
 __global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const double* __restrict__ B, int64_t ldb,
                                                  int k, int beta, int8_t* __restrict__ SB,
                                                  const int32_t* __restrict__ eB, int64_t Npad, int64_t slice_stride)
@@ -220,7 +232,7 @@ __global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const dou
                 uint32_t wv = 0;
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
-                    double q = __builtin_rint(y[4 * ii + b]);
+                    double q = digit<MASK>(y[4 * ii + b]);
                     wv |= ((uint32_t)(int)q & 0xffu) << (8 * b);
                     y[4 * ii + b] = (y[4 * ii + b] - q) * two_beta;
                 }
@@ -257,22 +269,27 @@ __global__ __launch_bounds__(256) void k_export(int64_t rows, int64_t n, int k, 
 
 namespace ozk {
 
-hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int8_t* SA,
-                          int32_t* eA, hipStream_t st)
+hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int split_mode,
+                          int8_t* SA, int32_t* eA, hipStream_t st)
 {
     const int64_t Rpad = ozl::rows_padded(m), Npad = ozl::inner_padded(n);
     const int64_t stride = ozl::slice_bytes(m, n);
     const bool vec = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 2 == 0);
     dim3 grid((unsigned)(Rpad / 4)), block(256);
-    if (vec)
-        hipLaunchKernelGGL(k_split_A<true>, grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
+    const bool mask = split_mode != 0;
+    if (vec && !mask)
+        hipLaunchKernelGGL((k_split_A<true, false>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
+    else if (!vec && !mask)
+        hipLaunchKernelGGL((k_split_A<false, false>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
+    else if (vec)
+        hipLaunchKernelGGL((k_split_A<true, true>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
     else
-        hipLaunchKernelGGL(k_split_A<false>, grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
+        hipLaunchKernelGGL((k_split_A<false, true>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
     return hipGetLastError();
 }
 
-hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int8_t* SB,
-                          int32_t* eB, hipStream_t st)
+hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int split_mode,
+                          int8_t* SB, int32_t* eB, hipStream_t st)
 {
     const int64_t Rpad = ozl::rows_padded(p), Npad = ozl::inner_padded(n);
     const int64_t stride = ozl::slice_bytes(p, n);
@@ -280,9 +297,14 @@ hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, in
                        reinterpret_cast<uint32_t*>(eB), 0u);
     dim3 gmax((unsigned)((n + LCH - 1) / LCH), (unsigned)((p + 63) / 64));
     hipLaunchKernelGGL(k_colmax_B, gmax, dim3(256), 0, st, n, p, B, ldb, reinterpret_cast<uint32_t*>(eB));
-    hipLaunchKernelGGL(k_decode_keys, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
     dim3 grid((unsigned)(Npad / 128), (unsigned)(Rpad / 64));
-    hipLaunchKernelGGL(k_split_B, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, SB, eB, Npad, stride);
+    if (split_mode == 0) {
+        hipLaunchKernelGGL(k_decode_keys<false>, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
+        hipLaunchKernelGGL(k_split_B<false>, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, SB, eB, Npad, stride);
+    } else {
+        hipLaunchKernelGGL(k_decode_keys<true>, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
+        hipLaunchKernelGGL(k_split_B<true>, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, SB, eB, Npad, stride);
+    }
     return hipGetLastError();
 }
 

@@ -44,6 +44,14 @@ _lib.ozimmu_gemm_ex.argtypes = [_int, _int, _i64, _i64, _i64, ctypes.c_double, _
 _lib.ozimmu_gemm_ex.restype = _int
 _lib.ozimmu_workspace_bytes_ex.argtypes = [_i64, _i64, _i64, _int]
 _lib.ozimmu_workspace_bytes_ex.restype = _sz
+_lib.ozimmu_dgemm_variant.argtypes = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _int, _int, _vp, _sz, _vp]
+_lib.ozimmu_dgemm_variant.restype = _int
+_lib.ozimmu_r_wide.argtypes = [_i64]
+_lib.ozimmu_r_wide.restype = _i64
+_lib.ozimmu_split_A_variant.argtypes = [_i64, _i64, _vp, _i64, _int, _int, _vp, _vp, _vp]
+_lib.ozimmu_split_A_variant.restype = _int
+_lib.ozimmu_split_B_variant.argtypes = [_i64, _i64, _vp, _i64, _int, _int, _vp, _vp, _vp]
+_lib.ozimmu_split_B_variant.restype = _int
 _lib.ozimmu_split_A.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_split_A.restype = _int
 _lib.ozimmu_split_B.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp]
@@ -59,7 +67,8 @@ _lib.ozimmu_export_slices.argtypes = [_i64, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_export_slices.restype = _int
 
 EXPORTS = ["ozimmu_status_string", "ozimmu_params", "ozimmu_num_chunks", "ozimmu_slices_bytes",
-           "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_dgemm_profiled", "ozimmu_gemm_ex", "ozimmu_workspace_bytes_ex", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
+           "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_dgemm_profiled", "ozimmu_gemm_ex", "ozimmu_workspace_bytes_ex", "ozimmu_dgemm_variant",
+           "ozimmu_r_wide", "ozimmu_split_A_variant", "ozimmu_split_B_variant", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
            "ozimmu_accumulate", "ozimmu_gemm_group_accumulate", "ozimmu_export_slices"]
 
 
@@ -151,6 +160,32 @@ def dgemm_profiled(A: torch.Tensor, B: torch.Tensor, k: int, D: torch.Tensor, wo
     return D
 
 
+SPLIT_MODES = {"rn": 0, "bitmask": 1}
+ACCUMULATE_MODES = {"grouped": 0, "per_pair": 1, "wide": 2}
+
+
+def r_wide(n: int) -> int:
+    return int(_lib.ozimmu_r_wide(n))
+
+
+def dgemm_variant(A: torch.Tensor, B: torch.Tensor, k: int, split: str = "rn", accumulate: str = "grouped",
+                  D: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """D = A B in one of the variants of Section 4 (see ozimmu_dgemm_variant in the header)."""
+    _dev(A, torch.float64), _dev(B, torch.float64)
+    m, n = A.shape
+    n2, p = B.shape
+    if n != n2:
+        raise ValueError("inner dimensions differ")
+    if D is None:
+        D = torch.empty((m, p), dtype=torch.float64, device=A.device)
+    if workspace is None:
+        workspace = alloc_workspace(m, n, p, k, A.device)
+    _check(_lib.ozimmu_dgemm_variant(m, n, p, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), D.data_ptr(), _ld(D), k,
+                                     SPLIT_MODES[split], ACCUMULATE_MODES[accumulate], workspace.data_ptr(),
+                                     workspace.numel(), _stream()))
+    return D
+
+
 def gemm_ex(transA: bool, transB: bool, alpha: float, A: torch.Tensor, B: torch.Tensor, beta: float,
             C: torch.Tensor, k: int, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     """C <- alpha * op(A) op(B) + beta * C in place (product emulated with k slices)."""
@@ -168,23 +203,31 @@ def gemm_ex(transA: bool, transB: bool, alpha: float, A: torch.Tensor, B: torch.
     return C
 
 
-def split_A(A: torch.Tensor, k: int) -> Tuple[torch.Tensor, torch.Tensor]:
+def split_A(A: torch.Tensor, k: int, split: str = "rn") -> Tuple[torch.Tensor, torch.Tensor]:
     """(packed slice stack, int32 row exponents) of A."""
     _dev(A, torch.float64)
     m, n = A.shape
     SA = torch.empty(max(slices_bytes(m, n, k), 256), dtype=torch.int8, device=A.device)
     eA = torch.empty(m, dtype=torch.int32, device=A.device)
-    _check(_lib.ozimmu_split_A(m, n, A.data_ptr(), _ld(A), k, SA.data_ptr(), eA.data_ptr(), _stream()))
+    if split == "rn":
+        _check(_lib.ozimmu_split_A(m, n, A.data_ptr(), _ld(A), k, SA.data_ptr(), eA.data_ptr(), _stream()))
+    else:
+        _check(_lib.ozimmu_split_A_variant(m, n, A.data_ptr(), _ld(A), k, SPLIT_MODES[split], SA.data_ptr(),
+                                           eA.data_ptr(), _stream()))
     return SA, eA
 
 
-def split_B(B: torch.Tensor, k: int) -> Tuple[torch.Tensor, torch.Tensor]:
+def split_B(B: torch.Tensor, k: int, split: str = "rn") -> Tuple[torch.Tensor, torch.Tensor]:
     """(packed slice stack, int32 column exponents) of B."""
     _dev(B, torch.float64)
     n, p = B.shape
     SB = torch.empty(max(slices_bytes(p, n, k), 256), dtype=torch.int8, device=B.device)
     eB = torch.empty(p, dtype=torch.int32, device=B.device)
-    _check(_lib.ozimmu_split_B(n, p, B.data_ptr(), _ld(B), k, SB.data_ptr(), eB.data_ptr(), _stream()))
+    if split == "rn":
+        _check(_lib.ozimmu_split_B(n, p, B.data_ptr(), _ld(B), k, SB.data_ptr(), eB.data_ptr(), _stream()))
+    else:
+        _check(_lib.ozimmu_split_B_variant(n, p, B.data_ptr(), _ld(B), k, SPLIT_MODES[split], SB.data_ptr(),
+                                           eB.data_ptr(), _stream()))
     return SB, eB
 
 

@@ -5,6 +5,8 @@
   --phases     m=n=p=8192, phi=0.5, k in {6, 8, 10}: time of split A, split B, chunk GEMMs and
                FP64 accumulation run as separate phases, and of the fused call    [Section 4.2 workload]
   --long-inner m=p=4096, n=65536, phi=1, k=10 (r = 2: 30 chunks for 55 products)
+  --variants   accuracy (1024^3, phi=2) and time (16384^3; 4096x65536x4096) of the variants of Section 4:
+               ozIMMU_H, ozIMMU_EF, ozIMMU, and the wide-chunk option
 
 Prints markdown tables.  The Dot2 reference comes from the CPU oracle package, which is test
 infrastructure; nothing here feeds back into the HIP path.
@@ -104,11 +106,59 @@ def phases(m, n, p, phi, ks, reps=5):
     print()
 
 
+def variants():
+    """Accuracy and time of the variants compared in Section 4, on the same inputs."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2409_13313_amd import inputs, ozimmu
+    combos = [("rn", "grouped", "ozIMMU_H"), ("rn", "wide", "H, wide chunks"), ("bitmask", "grouped", "ozIMMU_EF"),
+              ("bitmask", "per_pair", "ozIMMU"), ("rn", "per_pair", "RN split, per pair")]
+    n = 1024
+    A, B = inputs.phi_pair(n, n, n, 2.0, seed=0)
+    hi, lo = oracle.dot2_gemm(A, B)
+    absab = np.abs(A) @ np.abs(B)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    print(f"### variants, accuracy at m=n=p={n}, phi=2: max |D - R| / (|A||B|), R = Dot2 product\n")
+    print("| variant | " + " | ".join(f"k={k}" for k in range(7, 12)) + " |")
+    print("|---|" + "---|" * 5)
+    for split, acc, name in combos:
+        row = []
+        for k in range(7, 12):
+            D = ozimmu.dgemm_variant(dA, dB, k, split, acc).cpu().numpy()
+            row.append(float((np.abs((D - hi) - lo) / absab).max()))
+        print(f"| {name} | " + " | ".join(f"{e:.2e}" for e in row) + " |")
+    nat = torch.mm(dA, dB).cpu().numpy()
+    print(f"| native FP64 | {float((np.abs((nat - hi) - lo) / absab).max()):.2e} | | | | |\n")
+    del dA, dB
+    for (m, nn, p, ks) in [(16384, 16384, 16384, [8, 12, 14]), (4096, 65536, 4096, [10])]:
+        A, B = inputs.phi_pair(m, nn, p, 0.5, seed=0)
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        D = torch.empty((m, p), dtype=torch.float64, device="cuda")
+        beta, r = ozimmu.params(nn)
+        print(f"### variants, time at m={m} n={nn} p={p} (r={r}, wide r={ozimmu.r_wide(nn)}); median of 3, ms "
+              f"(effective TFLOP/s)\n")
+        print("| k | " + " | ".join(name for _, _, name in combos) + " |")
+        print("|---|" + "---|" * len(combos))
+        for k in ks:
+            ws = ozimmu.alloc_workspace(m, nn, p, k)
+            cells = []
+            for split, acc, name in combos:
+                ozimmu.dgemm_variant(dA, dB, k, split, acc, D=D, workspace=ws)
+                t = _median_ms(lambda: ozimmu.dgemm_variant(dA, dB, k, split, acc, D=D, workspace=ws), 3)
+                cells.append(f"{t:.2f} ({2.0 * m * nn * p / t / 1e9:.1f})")
+            print(f"| {k} | " + " | ".join(cells) + " |")
+            del ws
+        print()
+        del dA, dB, D
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--accuracy", action="store_true")
     ap.add_argument("--phases", action="store_true")
     ap.add_argument("--long-inner", action="store_true")
+    ap.add_argument("--variants", action="store_true")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
@@ -120,6 +170,8 @@ def main():
         phases(8192, 8192, 8192, 0.5, [6, 8, 10])
     if args.long_inner:
         phases(4096, 65536, 4096, 1.0, [10], reps=3)
+    if args.variants:
+        variants()
     return 0
 
 

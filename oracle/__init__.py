@@ -74,6 +74,10 @@ def _load():
         lib.oz_r_wide.restype = _i64
         lib.oz_axpby.argtypes = [_i64, _i64, ctypes.c_double, _vp, ctypes.c_double, _vp]
         lib.oz_axpby.restype = None
+        lib.oz_split_per_slice.argtypes = [_i64, _i64, _vp, _int, _int, _int, _int, _vp, _vp]
+        lib.oz_split_per_slice.restype = None
+        lib.oz_dgemm_per_slice.argtypes = [_i64, _i64, _i64, _vp, _vp, _int, _vp, _vp]
+        lib.oz_dgemm_per_slice.restype = _i64
         lib.oz_num_threads.argtypes = []
         lib.oz_num_threads.restype = _int
         _lib = lib
@@ -239,6 +243,35 @@ def dgemm_variant(A: np.ndarray, B: np.ndarray, k: int, split: str = "rn", accum
     w = _i64(0)
     rc = _load().oz_dgemm_variant(m, n, p, _p(A), _p(B), int(k), {"rn": 0, "bitmask": 1}[split],
                                   {"grouped": 0, "per_pair": 1, "wide": 2}[accumulate], _p(D), ctypes.byref(w))
+    if rc < 0:
+        raise ValueError("arguments outside the method's domain")
+    if rc > 0:
+        raise OverflowError(f"{rc} INT32 overflows")
+    return (D, int(w.value)) if return_addends else D
+
+
+def split_per_slice(X: np.ndarray, k: int, beta: int, by_col: bool, form: str = "int"):
+    """Algorithm 5: slices S[s-1] (shape of X) and per-slice scale exponents E[s-1][v], one vector per
+    row of X (by_col False) or per column (by_col True).  Slice s has scale 2^(E[s-1][v] + 1 - beta)."""
+    X = _c(X, np.float64)
+    rows, cols = X.shape
+    S = np.empty((k, rows, cols), dtype=np.int8)
+    E = np.empty((k, cols if by_col else rows), dtype=np.int32)
+    _load().oz_split_per_slice(rows, cols, _p(X), int(bool(by_col)), int(beta), int(k),
+                               {"int": 0, "sigma": 1}[form], _p(S), _p(E))
+    return S, E
+
+
+def dgemm_per_slice(A: np.ndarray, B: np.ndarray, k: int, return_addends: bool = False):
+    """ozIMMU_RN: Algorithm 5 slices, one FP64 addition per slice pair (Algorithm 4's order)."""
+    A = _c(A, np.float64)
+    B = _c(B, np.float64)
+    m, n = A.shape
+    n2, p = B.shape
+    assert n == n2
+    D = np.empty((m, p), dtype=np.float64)
+    w = _i64(0)
+    rc = _load().oz_dgemm_per_slice(m, n, p, _p(A), _p(B), int(k), _p(D), ctypes.byref(w))
     if rc < 0:
         raise ValueError("arguments outside the method's domain")
     if rc > 0:

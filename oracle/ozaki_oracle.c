@@ -257,6 +257,51 @@ void oz_split_cols(int64_t n, int64_t p, const double *B, const int32_t *eB,
         }
 }
 
+/* Round-to-nearest slices with ONE SCALE PER SLICE (the first of the paper's two round-to-nearest
+ * splits; it is the split of ozIMMU_RN).                              [Algorithm 5]
+ * For s = 1..k: the scale exponent of slice s is taken from what is LEFT of the vector,
+ *   e_s = ceil(log2 max |remainder|)   (0 when the remainder is all zero),
+ *   mu'(s) = 2^(e_s + 1 - beta),  q_s = RNE(remainder / mu'(s)),  remainder <- remainder - q_s mu'(s).
+ * |q_s| <= 2^(beta-1), and |remainder| <= mu'(s)/2 afterwards, so e_(s+1) <= e_s - beta.
+ * X is rows x cols row-major; by_col == 0: one vector per row, by_col != 0: one vector per column
+ * (B is split as the transpose of the split of B^T).  S[s-1] has the shape of X; E[s-1][v] = e_s of
+ * vector v.  form 0: q by scaling with a power of two and rint (both exact but for the rounding that
+ * the algorithm asks for); form 1: the (a + sigma) - sigma recipe as printed, sigma = 0.75 2^53 mu'(s). */
+void oz_split_per_slice(int64_t rows, int64_t cols_, const double *X, int by_col, int beta, int k, int form,
+                        int8_t *S, int32_t *E)
+{
+    int64_t nvec = by_col ? cols_ : rows, len = by_col ? rows : cols_;
+    int64_t stride = rows * cols_;
+    double *rem = (double *)malloc((size_t)(len > 0 ? len : 1) * sizeof(double));
+    for (int64_t v = 0; v < nvec; ++v) {
+        for (int64_t l = 0; l < len; ++l) rem[l] = by_col ? X[l * cols_ + v] : X[v * cols_ + l];
+        for (int s = 1; s <= k; ++s) {
+            double mx = 0.0;
+            for (int64_t l = 0; l < len; ++l) {
+                double a = fabs(rem[l]);
+                if (a > mx) mx = a;
+            }
+            int e = (mx > 0.0) ? ceil_log2_double(mx) : 0;
+            E[(int64_t)(s - 1) * nvec + v] = e;
+            double mu = ldexp(1.0, e + 1 - beta);
+            for (int64_t l = 0; l < len; ++l) {
+                double As;
+                if (form == 0) {
+                    As = ldexp(rint(ldexp(rem[l], beta - 1 - e)), e + 1 - beta);
+                } else {
+                    volatile double sigma = 0.75 * ldexp(mu, 53);
+                    volatile double t = rem[l] + sigma;
+                    As = t - sigma;
+                }
+                int64_t at = by_col ? l * cols_ + v : v * cols_ + l;
+                S[(int64_t)(s - 1) * stride + at] = (int8_t)(As / mu);
+                rem[l] -= As;
+            }
+        }
+    }
+    free(rem);
+}
+
 /* ------------------------------------------------------------------ */
 /* Step (iii): integer products                                        */
 /* ------------------------------------------------------------------ */
@@ -387,6 +432,41 @@ int64_t oz_dgemm_variant(int64_t m, int64_t n, int64_t p, const double *A, const
             }
         }
     }
+    if (n_addends) *n_addends = w;
+    free(eA); free(eB); free(SA); free(SB); free(C);
+    return bad;
+}
+
+/* D = A B by ozIMMU_RN: slices with one scale per slice (Algorithm 5), and one FP64 addition per
+ * slice pair with s + t <= k + 1 in the order g = s + t ascending, s ascending:
+ *   D <- D + diag(mu'(s)) FP64(A'_s B'_t) diag(nu'(t)),  mu'(s)_i nu'(t)_j = 2^(eA_s[i] + eB_t[j] + 2 - 2 beta)
+ *                                      [Algorithm 5; accumulation in the form of Algorithms 2 and 4]
+ * Same return values as oz_dgemm_variant. */
+int64_t oz_dgemm_per_slice(int64_t m, int64_t n, int64_t p, const double *A, const double *B,
+                           int k, double *D, int64_t *n_addends)
+{
+    if (m < 0 || n < 0 || p < 0 || k < 1) return -1;
+    for (int64_t x = 0; x < m * p; ++x) D[x] = 0.0;
+    if (n_addends) *n_addends = 0;
+    if (m == 0 || p == 0 || n == 0) return 0;
+    int beta = oz_beta(n);
+    if (beta < 1) return -1;
+    int32_t *eA = (int32_t *)malloc((size_t)k * m * sizeof(int32_t));
+    int32_t *eB = (int32_t *)malloc((size_t)k * p * sizeof(int32_t));
+    int8_t *SA = (int8_t *)malloc((size_t)k * m * n);
+    int8_t *SB = (int8_t *)malloc((size_t)k * n * p);
+    int32_t *C = (int32_t *)malloc((size_t)m * p * sizeof(int32_t));
+    oz_split_per_slice(m, n, A, 0, beta, k, 0, SA, eA);
+    oz_split_per_slice(n, p, B, 1, beta, k, 0, SB, eB);
+    int64_t bad = 0, w = 0;
+    for (int g = 2; g <= k + 1; ++g)
+        for (int s = 1; s <= g - 1; ++s) {
+            int t = g - s;
+            bad += oz_group_chunk(m, n, p, SA, SB, g, s, s, C);
+            /* oz_accumulate with g = 2 applies 2^(e + f + 2 - 2 beta) */
+            oz_accumulate(m, p, C, eA + (int64_t)(s - 1) * m, eB + (int64_t)(t - 1) * p, beta, 2, w == 0, D);
+            ++w;
+        }
     if (n_addends) *n_addends = w;
     free(eA); free(eB); free(SA); free(SB); free(C);
     return bad;

@@ -100,14 +100,24 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p,
  *                    OZIMMU_ACCUM_WIDE     chunks of ozimmu_r_wide(n) products; needs OZIMMU_SPLIT_NEAREST.
  *                                          Not in the paper: its r is derived for |A''| <= 2^beta - 1, while
  *                                          round-to-nearest slices obey |A''| <= 2^(beta-1).
+ *   split_mode       OZIMMU_SPLIT_NEAREST_PER_SLICE  round-to-nearest slices, each slice with a scale of
+ *                    its own taken from what the earlier slices left; needs OZIMMU_ACCUM_PER_PAIR (slices
+ *                    of one group no longer share a shift)                              [Algorithm 5]
  * (NEAREST, GROUPED) is ozimmu_dgemm (ozIMMU_H); (BITMASK, GROUPED) is ozIMMU_EF; (BITMASK, PER_PAIR) is the
- * earlier ozIMMU.  Other arguments as for ozimmu_dgemm; an invalid mode returns OZIMMU_ERR_SLICES. */
-enum { OZIMMU_SPLIT_NEAREST = 0, OZIMMU_SPLIT_BITMASK = 1 };
+ * earlier ozIMMU; (NEAREST_PER_SLICE, PER_PAIR) is ozIMMU_RN.  Other arguments as for ozimmu_dgemm, except
+ * that the workspace holds ozimmu_workspace_bytes_variant(m,n,p,k,split_mode) bytes; an invalid mode or
+ * combination returns OZIMMU_ERR_SLICES. */
+enum { OZIMMU_SPLIT_NEAREST = 0, OZIMMU_SPLIT_BITMASK = 1, OZIMMU_SPLIT_NEAREST_PER_SLICE = 2 };
 enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 2 };
 int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p,
                          const double *A, int64_t lda, const double *B, int64_t ldb,
                          double *D, int64_t ldd, int k, int split_mode, int accumulate_mode,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Workspace of ozimmu_dgemm_variant: ozimmu_workspace_bytes for the shared-scale splits; for
+ * OZIMMU_SPLIT_NEAREST_PER_SLICE also k exponents per row / column and the FP64 remainders of A and B
+ * (8 (m inner_padded + n p) bytes more).  0 for an invalid mode.  Host. */
+size_t ozimmu_workspace_bytes_variant(int64_t m, int64_t n, int64_t p, int k, int split_mode);
 
 /* Largest power of two r_w with r_w * n * (2^(beta-1))^2 <= 2^31 - 1 (0 for n outside 1..2^29); host. */
 int64_t ozimmu_r_wide(int64_t n);
@@ -157,6 +167,22 @@ int ozimmu_split_A_variant(int64_t m, int64_t n, const double *A, int64_t lda, i
                            int8_t *SA, int32_t *eA, void *stream);
 int ozimmu_split_B_variant(int64_t n, int64_t p, const double *B, int64_t ldb, int k, int split_mode,
                            int8_t *SB, int32_t *eB, void *stream);
+
+/* Steps (i) / (ii) with one scale per slice                                    [Algorithm 5]
+ * For s = 1..k: e_s = ceil(log2 max |remainder|) over the row of A (column of B), 0 when nothing is
+ * left; slice s = RNE(remainder / 2^(e_s + 1 - beta)); remainder reduced accordingly.
+ *   eA / eB  device, k arrays of m / p exponents, slice-major: e_s of row i at eA[(s-1) m + i].
+ *   rem      device scratch for the remainders, ozimmu_remainder_bytes(m, n, 0) bytes for A
+ *            (m rows of the padded inner length) and ozimmu_remainder_bytes(p, n, 1) for B (n x p),
+ *            16-byte aligned; contents undefined afterwards.
+ * Other arguments as for ozimmu_split_A / ozimmu_split_B.  The pair product of slices s and t enters
+ * D with the factor 2^(eA_s[i] + eB_t[j] + 2 - 2 beta), which ozimmu_accumulate applies when given
+ * those two exponent arrays and g = 2. */
+size_t ozimmu_remainder_bytes(int64_t rows, int64_t n, int by_col);
+int ozimmu_split_A_per_slice(int64_t m, int64_t n, const double *A, int64_t lda, int k,
+                             int8_t *SA, int32_t *eA, double *rem, void *stream);
+int ozimmu_split_B_per_slice(int64_t n, int64_t p, const double *B, int64_t ldb, int k,
+                             int8_t *SB, int32_t *eB, double *rem, void *stream);
 
 /* Step (iii) for one chunk: C'' <- sum_{s = s0..s1} A''_s B''_{g-s} in INT32
  *                                              [Algorithm 6, lines 7-9].

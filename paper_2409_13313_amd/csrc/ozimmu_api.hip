@@ -280,13 +280,55 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p, const double* A, int6
                       workspace_bytes, stream, events);
 }
 
+size_t ozimmu_remainder_bytes(int64_t rows, int64_t n, int by_col)
+{
+    if (rows < 0 || n < 0) return 0;
+    return (size_t)8 * (size_t)rows * (size_t)(by_col ? n : ozl::inner_padded(n));
+}
+
+size_t ozimmu_workspace_bytes_variant(int64_t m, int64_t n, int64_t p, int k, int split_mode)
+{
+    if (m < 0 || n < 0 || p < 0 || k < 0) return 0;
+    if (split_mode == OZIMMU_SPLIT_NEAREST || split_mode == OZIMMU_SPLIT_BITMASK)
+        return ozimmu_workspace_bytes(m, n, p, k);
+    if (split_mode != OZIMMU_SPLIT_NEAREST_PER_SLICE) return 0;
+    return (size_t)(align256(OZIMMU_SCRATCH_BYTES) + align256(4 * (int64_t)k * m) + align256(4 * (int64_t)k * p)) +
+           ozimmu_slices_bytes(m, n, k) + ozimmu_slices_bytes(p, n, k) +
+           (size_t)align256((int64_t)ozimmu_remainder_bytes(m, n, 0)) +
+           (size_t)align256((int64_t)ozimmu_remainder_bytes(p, n, 1));
+}
+
+int ozimmu_split_A_per_slice(int64_t m, int64_t n, const double* A, int64_t lda, int k, int8_t* SA, int32_t* eA,
+                             double* rem, void* stream)
+{
+    if (m < 0 || n < 0 || m > MAX_OUTER || n > MAX_INNER || lda < n) return OZIMMU_ERR_DIM;
+    if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
+    if (m == 0 || n == 0) return OZIMMU_OK;
+    if (!A || !SA || !eA || !rem) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(SA) % 256 || reinterpret_cast<uintptr_t>(rem) % 16) return OZIMMU_ERR_WORKSPACE;
+    return hip_status(ozk::launch_split_A_per_slice(m, n, A, lda, k, beta_of(n), SA, eA, rem, (hipStream_t)stream));
+}
+
+int ozimmu_split_B_per_slice(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int8_t* SB, int32_t* eB,
+                             double* rem, void* stream)
+{
+    if (p < 0 || n < 0 || p > MAX_OUTER || n > MAX_INNER || ldb < p) return OZIMMU_ERR_DIM;
+    if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
+    if (p == 0 || n == 0) return OZIMMU_OK;
+    if (!B || !SB || !eB || !rem) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(SB) % 256 || reinterpret_cast<uintptr_t>(rem) % 16) return OZIMMU_ERR_WORKSPACE;
+    return hip_status(ozk::launch_split_B_per_slice(n, p, B, ldb, k, beta_of(n), SB, eB, rem, (hipStream_t)stream));
+}
+
 int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
                          double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
                          size_t workspace_bytes, void* stream)
 {
-    if (split_mode != OZIMMU_SPLIT_NEAREST && split_mode != OZIMMU_SPLIT_BITMASK) return OZIMMU_ERR_SLICES;
+    if (split_mode < OZIMMU_SPLIT_NEAREST || split_mode > OZIMMU_SPLIT_NEAREST_PER_SLICE) return OZIMMU_ERR_SLICES;
     if (accumulate_mode < OZIMMU_ACCUM_GROUPED || accumulate_mode > OZIMMU_ACCUM_WIDE) return OZIMMU_ERR_SLICES;
     if (accumulate_mode == OZIMMU_ACCUM_WIDE && split_mode != OZIMMU_SPLIT_NEAREST) return OZIMMU_ERR_SLICES;
+    if (split_mode == OZIMMU_SPLIT_NEAREST_PER_SLICE && accumulate_mode != OZIMMU_ACCUM_PER_PAIR)
+        return OZIMMU_ERR_SLICES;
     return dgemm_impl(m, n, p, A, lda, B, ldb, D, ldd, k, split_mode, accumulate_mode, workspace, workspace_bytes,
                       stream, nullptr);
 }
@@ -335,10 +377,13 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     hipStream_t st = (hipStream_t)stream;
     if (n == 0) return hip_status(ozk::launch_fill_zero_f64(m, p, D, ldd, st));
     if (!A || !B || !workspace) return OZIMMU_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < ozimmu_workspace_bytes(m, n, p, k))
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 ||
+        workspace_bytes < ozimmu_workspace_bytes_variant(m, n, p, k, split_mode))
         return OZIMMU_ERR_WORKSPACE;
 
     const int beta = beta_of(n);
+    const bool per_slice = split_mode == OZIMMU_SPLIT_NEAREST_PER_SLICE;
+    const int64_t ne = per_slice ? k : 1;  // exponent arrays per operand
     const int64_t r = accumulate_mode == OZIMMU_ACCUM_PER_PAIR
                           ? 1
                           : (accumulate_mode == OZIMMU_ACCUM_WIDE ? r_wide_of(n, beta) : r_of(n, beta));
@@ -346,21 +391,26 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     void* scratch = ws;
     ws += align256(OZIMMU_SCRATCH_BYTES);
     int32_t* eA = reinterpret_cast<int32_t*>(ws);
-    ws += align256(4 * m);
+    ws += align256(4 * ne * m);
     int32_t* eB = reinterpret_cast<int32_t*>(ws);
-    ws += align256(4 * p);
+    ws += align256(4 * ne * p);
     int8_t* SA = reinterpret_cast<int8_t*>(ws);
     ws += ozimmu_slices_bytes(m, n, k);
     int8_t* SB = reinterpret_cast<int8_t*>(ws);
+    ws += ozimmu_slices_bytes(p, n, k);
+    double* remA = reinterpret_cast<double*>(ws);  // per-slice split only
+    double* remB = reinterpret_cast<double*>(ws + align256((int64_t)ozimmu_remainder_bytes(m, n, 0)));
 
     auto mark = [&](int i) -> hipError_t {
         return (events && events[i]) ? hipEventRecord((hipEvent_t)events[i], st) : hipSuccess;
     };
     hipError_t e = mark(0);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
-    e = ozk::launch_split_A(m, n, A, lda, k, beta, split_mode, SA, eA, st);
+    e = per_slice ? ozk::launch_split_A_per_slice(m, n, A, lda, k, beta, SA, eA, remA, st)
+                  : ozk::launch_split_A(m, n, A, lda, k, beta, split_mode, SA, eA, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
-    e = ozk::launch_split_B(n, p, B, ldb, k, beta, split_mode, SB, eB, st);
+    e = per_slice ? ozk::launch_split_B_per_slice(n, p, B, ldb, k, beta, SB, eB, remB, st)
+                  : ozk::launch_split_B(n, p, B, ldb, k, beta, split_mode, SB, eB, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     e = mark(1);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
@@ -373,8 +423,10 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     a.ldd = ldd;
     a.eA = eA;
     a.eB = eB;
+    a.estrideA = m;
+    a.estrideB = p;
     a.first = 1;
-    e = ozk::launch_gemm(a, 1, st);
+    e = ozk::launch_gemm(a, per_slice ? 2 : 1, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     return hip_status(mark(2));
 }

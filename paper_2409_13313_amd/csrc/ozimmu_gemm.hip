@@ -7,6 +7,8 @@
 //     D <- D + 2^(2 - beta g) diag(2^eA) FP64(C'') diag(2^eB)     (MODE 1)
 // from registers.  The conversion and the power-of-two scaling are exact, so the
 // single FP64 addition per chunk is the only rounding on the whole path.
+// MODE 2 is MODE 1 for slices that carry one scale each (Algorithm 5): every chunk
+// is one pair (s, t) and the factor is 2^(2 - 2 beta) diag(2^eA_s) . diag(2^eB_t).
 //
 // Tiling: 256 x 256 outputs per workgroup, 4 waves in a 2 x 2 grid, each wave
 // 128 x 128 = 4 x 4 tiles of v_mfma_i32_32x32x32_i8 (256 INT32 accumulators per
@@ -225,6 +227,13 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 // stages 0 .. NS-3 and the A half of stage NS-2 go in flight, the team lines up, stage 0
                 // lands, first fragments fetched
                 __builtin_amdgcn_s_barrier();
+                if (MODE == 2) {
+                    // one scale per slice: this chunk is the single pair (c0, g - c0); every wave is past the
+                    // previous epilogue, and the barriers of the main loop publish the new exponents
+                    const int64_t gr = (int64_t)tm * 256 + t, gc = (int64_t)tp * 256 + t;
+                    lds_exp[t] = gr < a.m ? a.eA[(int64_t)(c0 - 1) * a.estrideA + gr] : 0;
+                    lds_exp[256 + t] = gc < a.p ? a.eB[(int64_t)(g - c0 - 1) * a.estrideB + gc] : 0;
+                }
                 static_for<0, NS - 1>([&](auto S) {
                     constexpr int sidx = decltype(S)::value;
                     static_for<0, NLOAD>([&](auto Q) {
@@ -323,7 +332,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 // row 8*(r/4) + 4*(l/32) + r%4 and column l%32 of that 32 x 32 tile.  Addresses are a
                 // wave-uniform base plus a 32-bit lane offset, rebuilt for every chunk (the empty asm
                 // keeps the compiler from hoisting 64 element addresses per lane out of the chunk loops).
-                const int shift = 2 - a.beta * g;
+                const int shift = MODE == 2 ? 2 - 2 * a.beta : 2 - a.beta * g;
                 int64_t er0 = row0, ec0 = col0;
                 asm volatile("" : "+s"(er0), "+s"(ec0));
                 const bool lane_col_ok[4] = {ec0 + lr < a.p, ec0 + 32 + lr < a.p, ec0 + 64 + lr < a.p,
@@ -452,6 +461,9 @@ hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<1, NSTAGES>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2, NSTAGES>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
         e = hipDeviceGetAttribute(&num_cu[dev], hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
         attr_set[dev] = true;
@@ -462,7 +474,9 @@ hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st)
     if (tiles < nwg) nwg = (int)tiles;
     hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(NXCD * 16), 0, st, a.sync);
     dim3 grid((unsigned)nwg), block(256);
-    if (fused)
+    if (fused == 2)
+        hipLaunchKernelGGL((k_gemm<2, NSTAGES>), grid, block, smem, st, a, TM, TP);
+    else if (fused)
         hipLaunchKernelGGL((k_gemm<1, NSTAGES>), grid, block, smem, st, a, TM, TP);
     else
         hipLaunchKernelGGL((k_gemm<0, NSTAGES>), grid, block, smem, st, a, TM, TP);

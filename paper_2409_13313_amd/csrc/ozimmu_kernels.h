@@ -14,6 +14,12 @@ hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, in
 // Step (ii): column exponents + slices of B (the same applied to B^T).
 hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int split_mode,
                           int8_t* SB, int32_t* eB, hipStream_t st);
+// Algorithm 5: round-to-nearest slices with one scale per slice.  e holds k arrays of exponents (slice-major);
+// rem is scratch for the remainders: m x inner_padded(n) doubles for A, n x p doubles for B.
+hipError_t launch_split_A_per_slice(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int8_t* SA,
+                                    int32_t* eA, double* rem, hipStream_t st);
+hipError_t launch_split_B_per_slice(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int8_t* SB,
+                                    int32_t* eB, double* rem, hipStream_t st);
 hipError_t launch_export(int64_t rows, int64_t n, int k, const int8_t* packed, int8_t* out, hipStream_t st);
 
 struct GemmArgs {
@@ -34,12 +40,14 @@ struct GemmArgs {
     int64_t ldd;
     const int32_t* eA;
     const int32_t* eB;
+    int64_t estrideA, estrideB;  // fused == 2 only: elements from the exponents of slice s to those of slice s+1
     int beta;              // shift of group g is 2 - beta * g
     int first;             // D is zero before the first chunk: overwrite
     unsigned* sync;        // 8 x 16 zeroed counters (one cache line apart) for the per-XCD soft barrier
     int spin_limit;        // polls before a soft barrier gives up
 };
-// Steps (iii) (+ (iv) when fused != 0) for the chunks of the schedule (Algorithm 6).
+// Steps (iii) (+ (iv) when fused != 0) for the chunks of the schedule (Algorithm 6).  fused == 2: one scale
+// per slice (Algorithm 5), r must be 1.
 hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st);
 // Step (iv) alone.
 hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA,

@@ -254,6 +254,157 @@ __global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const dou
     }
 }
 
+// ---------------------------------------------------------------------------
+// Algorithm 5 (one scale per slice), A: one wave per padded row as in k_split_A.
+// The scale of slice s+1 comes from the largest remainder after slice s, so the
+// row is walked k times; what is left of it lives in `rem` (row pitch Npad) and
+// every lane re-reads only the elements it wrote itself.  With
+//   y = remainder * 2^(beta-1-e_s)  (exact),  q_s = rint(y),
+//   remainder <- (y - q_s) * 2^(e_s+1-beta)  (both exact).
+// HBM-bound: about 16 k bytes per element (remainder read and written per slice).
+// ---------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(256) void k_split_A_ps(int64_t m, int64_t n, const double* __restrict__ A, int64_t lda,
+                                                    int k, int beta, int8_t* __restrict__ SA,
+                                                    int32_t* __restrict__ eA, double* __restrict__ rem, int64_t Npad,
+                                                    int64_t slice_stride)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t R = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t KT = Npad / TILE_K;
+
+    if (R >= m) {  // padding row: zeros in every slice
+        for (int64_t l = 4 * lane; l < Npad; l += 256)
+            for (int s = 0; s < k; ++s)
+                *reinterpret_cast<uint32_t*>(SA + s * slice_stride + packed_offset(R, l, KT)) = 0u;
+        return;
+    }
+    const double* row = A + R * lda;
+    double* rrow = rem + R * Npad;
+
+    auto load4 = [&](int64_t l, double* v) {
+        if (VEC && l + 3 < n) {
+            double2 a = *reinterpret_cast<const double2*>(row + l);
+            double2 b = *reinterpret_cast<const double2*>(row + l + 2);
+            v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (l + j < n) ? row[l + j] : 0.0;
+        }
+    };
+
+    uint64_t mx = 0;
+    for (int64_t l = 4 * lane; l < n; l += 256) {
+        double v[4];
+        load4(l, v);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint64_t b = abs_bits(v[j]);
+            mx = b > mx ? b : mx;
+        }
+    }
+    int e = key_to_exp<false>(exp_key(wave_max_u64(mx)));
+
+    for (int s = 0; s < k; ++s) {
+        if (lane == 0) eA[(int64_t)s * m + R] = e;
+        const int sc = beta - 1 - e;
+        const bool keep = s + 1 < k;
+        mx = 0;
+        for (int64_t l = 4 * lane; l < Npad; l += 256) {
+            double v[4];
+            if (s == 0) {
+                load4(l, v);
+            } else {
+                double2 a = *reinterpret_cast<const double2*>(rrow + l);
+                double2 b = *reinterpret_cast<const double2*>(rrow + l + 2);
+                v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y;
+            }
+            uint32_t w = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double y = ldexp(v[j], sc);
+                const double q = __builtin_rint(y);
+                w |= ((uint32_t)(int)q & 0xffu) << (8 * j);
+                v[j] = ldexp(y - q, -sc);
+                const uint64_t b = abs_bits(v[j]);
+                mx = b > mx ? b : mx;
+            }
+            *reinterpret_cast<uint32_t*>(SA + s * slice_stride + packed_offset(R, l, KT)) = w;
+            if (keep) {
+                *reinterpret_cast<double2*>(rrow + l) = make_double2(v[0], v[1]);
+                *reinterpret_cast<double2*>(rrow + l + 2) = make_double2(v[2], v[3]);
+            }
+        }
+        e = key_to_exp<false>(exp_key(wave_max_u64(mx)));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Algorithm 5, B: one launch per slice (the column maxima of the remainder need
+// a grid-wide reduction between slices).  Tiling and write-out as in k_split_B;
+// src is B for the first slice and the remainder buffer (pitch p) afterwards.
+// The maxima of the new remainder are merged into keys_next for the next launch.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_split_B_ps(int64_t n, int64_t p, const double* src, int64_t ld, int beta,
+                                                    int8_t* __restrict__ SBs, const uint32_t* __restrict__ keys,
+                                                    uint32_t* __restrict__ keys_next, double* rem, int64_t Npad)
+{
+    __shared__ uint32_t tile[64 * PITCH];
+    __shared__ uint64_t part[4][64];
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int64_t l0 = (int64_t)blockIdx.x * 128;
+    const int64_t j0 = (int64_t)blockIdx.y * 64;
+    const int64_t j = j0 + lane;
+    const int64_t KT = Npad / TILE_K;
+    const bool col_ok = j < p;
+    const int sc = beta - 1 - (col_ok ? key_to_exp<false>(keys[j]) : 0);
+
+    double y[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        const int64_t l = l0 + w * 32 + i;
+        y[i] = (col_ok && l < n) ? src[l * ld + j] : 0.0;
+    }
+    uint64_t mx = 0;
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) {
+        uint32_t wv = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int i = 4 * ii + b;
+            const double ys = ldexp(y[i], sc);
+            const double q = __builtin_rint(ys);
+            wv |= ((uint32_t)(int)q & 0xffu) << (8 * b);
+            y[i] = ldexp(ys - q, -sc);
+            const uint64_t ab = abs_bits(y[i]);
+            mx = ab > mx ? ab : mx;
+        }
+        tile[lane * PITCH + w * 8 + ii] = wv;
+    }
+    if (keys_next) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            const int64_t l = l0 + w * 32 + i;
+            if (col_ok && l < n) rem[l * p + j] = y[i];
+        }
+    }
+    part[w][lane] = mx;
+    __syncthreads();
+    const int oc = t & 7, orow = t >> 3;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int jr = orow + 32 * pass;
+        const uint32_t* sp = &tile[jr * PITCH + oc * 4];
+        uint4 v = make_uint4(sp[0], sp[1], sp[2], sp[3]);
+        *reinterpret_cast<uint4*>(SBs + packed_offset(j0 + jr, l0 + oc * CHUNK, KT)) = v;
+    }
+    if (keys_next && w == 0 && col_ok) {
+        for (int q = 1; q < 4; ++q) mx = part[q][lane] > mx ? part[q][lane] : mx;
+        const uint32_t key = exp_key(mx);
+        if (key) atomicMax(keys_next + j, key);
+    }
+}
+
 // Unpack: one thread per output byte, out[s][row][l].
 __global__ __launch_bounds__(256) void k_export(int64_t rows, int64_t n, int k, const int8_t* __restrict__ packed,
                                                 int8_t* __restrict__ out, int64_t KT, int64_t slice_stride)
@@ -305,6 +456,39 @@ hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, in
         hipLaunchKernelGGL(k_decode_keys<true>, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
         hipLaunchKernelGGL(k_split_B<true>, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, SB, eB, Npad, stride);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_split_A_per_slice(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int8_t* SA,
+                                    int32_t* eA, double* rem, hipStream_t st)
+{
+    const int64_t Rpad = ozl::rows_padded(m), Npad = ozl::inner_padded(n);
+    const int64_t stride = ozl::slice_bytes(m, n);
+    const bool vec = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 2 == 0);
+    dim3 grid((unsigned)(Rpad / 4)), block(256);
+    if (vec)
+        hipLaunchKernelGGL((k_split_A_ps<true>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, rem, Npad, stride);
+    else
+        hipLaunchKernelGGL((k_split_A_ps<false>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, rem, Npad, stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_split_B_per_slice(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int8_t* SB,
+                                    int32_t* eB, double* rem, hipStream_t st)
+{
+    const int64_t Rpad = ozl::rows_padded(p), Npad = ozl::inner_padded(n);
+    const int64_t stride = ozl::slice_bytes(p, n);
+    uint32_t* keys = reinterpret_cast<uint32_t*>(eB);  // k arrays of p keys, decoded in place at the end
+    const int64_t nk = (int64_t)k * p;
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, st, nk, keys, 0u);
+    dim3 gmax((unsigned)((n + LCH - 1) / LCH), (unsigned)((p + 63) / 64));
+    hipLaunchKernelGGL(k_colmax_B, gmax, dim3(256), 0, st, n, p, B, ldb, keys);
+    dim3 grid((unsigned)(Npad / 128), (unsigned)(Rpad / 64));
+    for (int s = 0; s < k; ++s)
+        hipLaunchKernelGGL(k_split_B_ps, grid, dim3(256), 0, st, n, p, s == 0 ? B : rem, s == 0 ? ldb : p, beta,
+                           SB + (int64_t)s * stride, keys + (int64_t)s * p,
+                           s + 1 < k ? keys + (int64_t)(s + 1) * p : nullptr, rem, Npad);
+    hipLaunchKernelGGL(k_decode_keys<false>, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, st, nk, eB);
     return hipGetLastError();
 }
 

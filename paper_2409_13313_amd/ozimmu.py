@@ -63,13 +63,27 @@ _lib.ozimmu_accumulate.restype = _int
 _lib.ozimmu_gemm_group_accumulate.argtypes = [_i64, _i64, _i64, _vp, _int, _vp, _int, _int, _int, _int,
                                               _vp, _vp, _int, _vp, _i64, _vp, _vp]
 _lib.ozimmu_gemm_group_accumulate.restype = _int
+_lib.ozimmu_workspace_bytes_variant.argtypes = [_i64, _i64, _i64, _int, _int]
+_lib.ozimmu_workspace_bytes_variant.restype = _sz
+_lib.ozimmu_remainder_bytes.argtypes = [_i64, _i64, _int]
+_lib.ozimmu_remainder_bytes.restype = _sz
+_lib.ozimmu_split_A_per_slice.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
+_lib.ozimmu_split_A_per_slice.restype = _int
+_lib.ozimmu_split_B_per_slice.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
+_lib.ozimmu_split_B_per_slice.restype = _int
 _lib.ozimmu_export_slices.argtypes = [_i64, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_export_slices.restype = _int
 
 EXPORTS = ["ozimmu_status_string", "ozimmu_params", "ozimmu_num_chunks", "ozimmu_slices_bytes",
            "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_dgemm_profiled", "ozimmu_gemm_ex", "ozimmu_workspace_bytes_ex", "ozimmu_dgemm_variant",
            "ozimmu_r_wide", "ozimmu_split_A_variant", "ozimmu_split_B_variant", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
-           "ozimmu_accumulate", "ozimmu_gemm_group_accumulate", "ozimmu_export_slices"]
+           "ozimmu_accumulate", "ozimmu_gemm_group_accumulate", "ozimmu_export_slices",
+           "ozimmu_workspace_bytes_variant", "ozimmu_remainder_bytes", "ozimmu_split_A_per_slice",
+           "ozimmu_split_B_per_slice"]
+
+
+SPLIT_MODES = {"rn": 0, "bitmask": 1, "per_slice": 2}
+ACCUMULATE_MODES = {"grouped": 0, "per_pair": 1, "wide": 2}
 
 
 class OzimmuError(RuntimeError):
@@ -124,8 +138,9 @@ def workspace_bytes(m: int, n: int, p: int, k: int) -> int:
     return int(_lib.ozimmu_workspace_bytes(m, n, p, k))
 
 
-def alloc_workspace(m: int, n: int, p: int, k: int, device="cuda") -> torch.Tensor:
-    return torch.empty(max(workspace_bytes(m, n, p, k), 256), dtype=torch.uint8, device=device)
+def alloc_workspace(m: int, n: int, p: int, k: int, device="cuda", split: str = "rn") -> torch.Tensor:
+    nbytes = int(_lib.ozimmu_workspace_bytes_variant(m, n, p, k, SPLIT_MODES[split]))
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 
 def dgemm(A: torch.Tensor, B: torch.Tensor, k: int, D: Optional[torch.Tensor] = None,
@@ -160,10 +175,6 @@ def dgemm_profiled(A: torch.Tensor, B: torch.Tensor, k: int, D: torch.Tensor, wo
     return D
 
 
-SPLIT_MODES = {"rn": 0, "bitmask": 1}
-ACCUMULATE_MODES = {"grouped": 0, "per_pair": 1, "wide": 2}
-
-
 def r_wide(n: int) -> int:
     return int(_lib.ozimmu_r_wide(n))
 
@@ -179,7 +190,7 @@ def dgemm_variant(A: torch.Tensor, B: torch.Tensor, k: int, split: str = "rn", a
     if D is None:
         D = torch.empty((m, p), dtype=torch.float64, device=A.device)
     if workspace is None:
-        workspace = alloc_workspace(m, n, p, k, A.device)
+        workspace = alloc_workspace(m, n, p, k, A.device, split)
     _check(_lib.ozimmu_dgemm_variant(m, n, p, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), D.data_ptr(), _ld(D), k,
                                      SPLIT_MODES[split], ACCUMULATE_MODES[accumulate], workspace.data_ptr(),
                                      workspace.numel(), _stream()))
@@ -204,10 +215,16 @@ def gemm_ex(transA: bool, transB: bool, alpha: float, A: torch.Tensor, B: torch.
 
 
 def split_A(A: torch.Tensor, k: int, split: str = "rn") -> Tuple[torch.Tensor, torch.Tensor]:
-    """(packed slice stack, int32 row exponents) of A."""
+    """(packed slice stack, int32 row exponents) of A; split "per_slice": exponents [k][m] (Algorithm 5)."""
     _dev(A, torch.float64)
     m, n = A.shape
     SA = torch.empty(max(slices_bytes(m, n, k), 256), dtype=torch.int8, device=A.device)
+    if split == "per_slice":
+        eA = torch.empty((k, m), dtype=torch.int32, device=A.device)
+        rem = torch.empty(max(int(_lib.ozimmu_remainder_bytes(m, n, 0)), 256), dtype=torch.uint8, device=A.device)
+        _check(_lib.ozimmu_split_A_per_slice(m, n, A.data_ptr(), _ld(A), k, SA.data_ptr(), eA.data_ptr(),
+                                             rem.data_ptr(), _stream()))
+        return SA, eA
     eA = torch.empty(m, dtype=torch.int32, device=A.device)
     if split == "rn":
         _check(_lib.ozimmu_split_A(m, n, A.data_ptr(), _ld(A), k, SA.data_ptr(), eA.data_ptr(), _stream()))
@@ -218,10 +235,16 @@ def split_A(A: torch.Tensor, k: int, split: str = "rn") -> Tuple[torch.Tensor, t
 
 
 def split_B(B: torch.Tensor, k: int, split: str = "rn") -> Tuple[torch.Tensor, torch.Tensor]:
-    """(packed slice stack, int32 column exponents) of B."""
+    """(packed slice stack, int32 column exponents) of B; split "per_slice": exponents [k][p] (Algorithm 5)."""
     _dev(B, torch.float64)
     n, p = B.shape
     SB = torch.empty(max(slices_bytes(p, n, k), 256), dtype=torch.int8, device=B.device)
+    if split == "per_slice":
+        eB = torch.empty((k, p), dtype=torch.int32, device=B.device)
+        rem = torch.empty(max(int(_lib.ozimmu_remainder_bytes(p, n, 1)), 256), dtype=torch.uint8, device=B.device)
+        _check(_lib.ozimmu_split_B_per_slice(n, p, B.data_ptr(), _ld(B), k, SB.data_ptr(), eB.data_ptr(),
+                                             rem.data_ptr(), _stream()))
+        return SB, eB
     eB = torch.empty(p, dtype=torch.int32, device=B.device)
     if split == "rn":
         _check(_lib.ozimmu_split_B(n, p, B.data_ptr(), _ld(B), k, SB.data_ptr(), eB.data_ptr(), _stream()))

@@ -6,7 +6,7 @@
                FP64 accumulation run as separate phases, and of the fused call    [Section 4.2 workload]
   --long-inner m=p=4096, n=65536, phi=1, k=10 (r = 2: 30 chunks for 55 products)
   --variants   accuracy (1024^3, phi=2) and time (16384^3; 4096x65536x4096) of the variants of Section 4:
-               ozIMMU_H, ozIMMU_EF, ozIMMU, and the wide-chunk option
+               ozIMMU_H, ozIMMU_EF, ozIMMU, ozIMMU_RN, and the wide-chunk option
 
 Prints markdown tables.  The Dot2 reference comes from the CPU oracle package, which is test
 infrastructure; nothing here feeds back into the HIP path.
@@ -113,7 +113,8 @@ def variants():
     import oracle
     from paper_2409_13313_amd import inputs, ozimmu
     combos = [("rn", "grouped", "ozIMMU_H"), ("rn", "wide", "H, wide chunks"), ("bitmask", "grouped", "ozIMMU_EF"),
-              ("bitmask", "per_pair", "ozIMMU"), ("rn", "per_pair", "RN split, per pair")]
+              ("bitmask", "per_pair", "ozIMMU"), ("per_slice", "per_pair", "ozIMMU_RN"),
+              ("rn", "per_pair", "RN split, per pair")]
     n = 1024
     A, B = inputs.phi_pair(n, n, n, 2.0, seed=0)
     hi, lo = oracle.dot2_gemm(A, B)
@@ -141,7 +142,7 @@ def variants():
         print("| k | " + " | ".join(name for _, _, name in combos) + " |")
         print("|---|" + "---|" * len(combos))
         for k in ks:
-            ws = ozimmu.alloc_workspace(m, nn, p, k)
+            ws = ozimmu.alloc_workspace(m, nn, p, k, split="per_slice")      # the largest of the variants
             cells = []
             for split, acc, name in combos:
                 ozimmu.dgemm_variant(dA, dB, k, split, acc, D=D, workspace=ws)

@@ -8,6 +8,11 @@
   --variants   accuracy (1024^3, phi=2) and time (16384^3; 4096x65536x4096) of the variants of Section 4:
                ozIMMU_H, ozIMMU_EF, ozIMMU, ozIMMU_RN, and the wide-chunk option
 
+  --perf-vs-accuracy  m=n=p=4096, phi=0, k = 3..12: throughput against accuracy for the four methods of
+               Section 4 and native FP64                                          [Section 4.3 workload]
+  --small-beta m=p=2048, n=2^18 (beta = 6, r = 2) next to n=2^17 (beta = 7, r = 1): the loss of accuracy
+               per slice beyond n = 2^17                                          [Section 4.1 remark]
+
 Prints markdown tables.  The Dot2 reference comes from the CPU oracle package, which is test
 infrastructure; nothing here feeds back into the HIP path.
 """
@@ -154,12 +159,94 @@ def variants():
         del dA, dB, D
 
 
+def _sampled_errors(D, A, B, I, J, hi, lo, absab):
+    """(max |D-R|/|R|, max |D-R|/(|A||B|)) over the sampled entries D[I][:, J]; R = hi + lo (Dot2)."""
+    import numpy as np
+    got = D[I][:, J].cpu().numpy()
+    diff = np.abs((got - hi) - lo)
+    return float((diff / np.abs(hi)).max()), float((diff / absab).max())
+
+
+def perf_vs_accuracy(n=4096, phi=0.0, sample=256, reps=5):
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2409_13313_amd import inputs, ozimmu
+    methods = [("rn", "grouped", "ozIMMU_H"), ("bitmask", "grouped", "ozIMMU_EF"), ("bitmask", "per_pair", "ozIMMU"),
+               ("per_slice", "per_pair", "ozIMMU_RN")]
+    A, B = inputs.phi_pair(n, n, n, phi, seed=0)
+    I = inputs.sample_indices(n, sample, seed=1)
+    J = inputs.sample_indices(n, sample, seed=2)
+    Asub, Bsub = np.ascontiguousarray(A[I]), np.ascontiguousarray(B[:, J])
+    hi, lo = oracle.dot2_gemm(Asub, Bsub)
+    absab = np.abs(Asub) @ np.abs(Bsub)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    tI, tJ = torch.from_numpy(I).cuda(), torch.from_numpy(J).cuda()
+    D = torch.empty((n, n), dtype=torch.float64, device="cuda")
+    flops = 2.0 * n ** 3
+    print(f"### throughput against accuracy, m=n=p={n}, phi={phi}; median of {reps}; errors over a {sample}x{sample} "
+          f"sample of D against a Dot2 product R: e1 = max |D-R|/|R|, e2 = max |D-R|/(|A||B|)\n")
+    torch.mm(dA, dB, out=D)
+    t = _median_ms(lambda: torch.mm(dA, dB, out=D), reps)
+    e1, e2 = _sampled_errors(D, A, B, tI, tJ, hi, lo, absab)
+    print(f"native FP64 (torch.mm): {flops / t / 1e9:.1f} TFLOP/s, e1 = {e1:.2e}, e2 = {e2:.2e}\n")
+    print("| k | " + " | ".join(f"{name}: TFLOP/s, e1, e2" for _, _, name in methods) + " |")
+    print("|---|" + "---|" * len(methods))
+    ws = ozimmu.alloc_workspace(n, n, n, 12, split="per_slice")
+    for k in range(3, 13):
+        cells = []
+        for split, acc, name in methods:
+            ozimmu.dgemm_variant(dA, dB, k, split, acc, D=D, workspace=ws)
+            e1, e2 = _sampled_errors(D, A, B, tI, tJ, hi, lo, absab)
+            t = _median_ms(lambda: ozimmu.dgemm_variant(dA, dB, k, split, acc, D=D, workspace=ws), reps)
+            cells.append(f"{flops / t / 1e9:.1f}, {e1:.1e}, {e2:.1e}")
+        print(f"| {k} | " + " | ".join(cells) + " |")
+    print()
+
+
+def small_beta(m=2048, p=2048, phi=0.5, sample=64, reps=3):
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2409_13313_amd import inputs, ozimmu
+    print(f"### beyond n = 2^17 (beta < 7): m=p={m}, phi={phi}; e2 = max |D-R|/(|A||B|) over a {sample}x{sample} sample, "
+          f"time = median of {reps}\n")
+    print("| n | beta | r | " + " | ".join(f"k={k}: e2, ms" for k in (8, 9, 10, 11, 12)) + " | native FP64: e2, ms |")
+    print("|---|---|---|" + "---|" * 6)
+    for n in (2 ** 17, 2 ** 18):
+        A, B = inputs.phi_pair(m, n, p, phi, seed=0)
+        I = inputs.sample_indices(m, sample, seed=1)
+        J = inputs.sample_indices(p, sample, seed=2)
+        Asub, Bsub = np.ascontiguousarray(A[I]), np.ascontiguousarray(B[:, J])
+        hi, lo = oracle.dot2_gemm(Asub, Bsub)
+        absab = np.abs(Asub) @ np.abs(Bsub)
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        tI, tJ = torch.from_numpy(I).cuda(), torch.from_numpy(J).cuda()
+        D = torch.empty((m, p), dtype=torch.float64, device="cuda")
+        beta, r = ozimmu.params(n)
+        ws = ozimmu.alloc_workspace(m, n, p, 12)
+        cells = []
+        for k in (8, 9, 10, 11, 12):
+            ozimmu.dgemm(dA, dB, k, D=D, workspace=ws)
+            _, e2 = _sampled_errors(D, A, B, tI, tJ, hi, lo, absab)
+            t = _median_ms(lambda: ozimmu.dgemm(dA, dB, k, D=D, workspace=ws), reps)
+            cells.append(f"{e2:.1e}, {t:.2f}")
+        torch.mm(dA, dB, out=D)
+        _, e2 = _sampled_errors(D, A, B, tI, tJ, hi, lo, absab)
+        t = _median_ms(lambda: torch.mm(dA, dB, out=D), reps)
+        print(f"| {n} | {beta} | {r} | " + " | ".join(cells) + f" | {e2:.1e}, {t:.2f} |")
+        del dA, dB, D, ws
+    print()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--accuracy", action="store_true")
     ap.add_argument("--phases", action="store_true")
     ap.add_argument("--long-inner", action="store_true")
     ap.add_argument("--variants", action="store_true")
+    ap.add_argument("--perf-vs-accuracy", action="store_true")
+    ap.add_argument("--small-beta", action="store_true")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
@@ -173,6 +260,10 @@ def main():
         phases(4096, 65536, 4096, 1.0, [10], reps=3)
     if args.variants:
         variants()
+    if args.perf_vs_accuracy:
+        perf_vs_accuracy()
+    if args.small_beta:
+        small_beta()
     return 0
 
 

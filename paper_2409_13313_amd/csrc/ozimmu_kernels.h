@@ -43,7 +43,7 @@ struct GemmArgs {
     int64_t estrideA, estrideB;  // fused == 2 only: elements from the exponents of slice s to those of slice s+1
     int beta;              // shift of group g is 2 - beta * g
     int first;             // D is zero before the first chunk: overwrite
-    unsigned* sync;        // 8 x 16 zeroed counters (one cache line apart) for the per-XCD soft barrier
+    unsigned* sync;        // 8 x 16 counters, zeroed by launch_gemm: [16 x] per-XCD soft barrier, [1] whole grid
     int spin_limit;        // polls before a soft barrier gives up
 };
 // Steps (iii) (+ (iv) when fused != 0) for the chunks of the schedule (Algorithm 6).  fused == 2: one scale

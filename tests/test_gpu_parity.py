@@ -265,3 +265,33 @@ def test_argument_errors_are_reported(oz):
         oz.dgemm(A, A, 21)
     with pytest.raises(oz.OzimmuError):
         oz.dgemm(A, A, 8, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+
+
+def test_dgemm_captured_in_a_hip_graph_replays_bit_identically(oz):
+    # the call enqueues kernels only (counters are cleared by a fill kernel, not a memset), so it can be
+    # captured; every replay must reproduce the eager result, also after eager work in between
+    m, n, p, k = 300, 520, 270, 8
+    A, B = inputs.phi_pair(m, n, p, 0.5, seed=41)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    ws = oz.alloc_workspace(m, n, p, k)
+    eager = oz.dgemm(dA, dB, k, workspace=ws).clone()     # also the warm-up that sets the kernel attributes
+    D = torch.zeros((m, p), dtype=torch.float64, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        oz.dgemm(dA, dB, k, D=D, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        oz.dgemm(dA, dB, k, D=D, workspace=ws)
+    for rep in range(4):
+        D.fill_(float(rep))                                # eager work between the replays
+        other = oz.dgemm(dB.T.contiguous(), dA.T.contiguous(), k) if rep == 2 else None   # its own workspace
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(D, eager), f"replay {rep}"
+        del other
+    want = oracle.dgemm(A, B, k)
+    assert (np.abs(eager.cpu().numpy() - want) <= 2 * np.spacing(np.abs(want))).all()

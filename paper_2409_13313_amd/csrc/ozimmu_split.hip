@@ -141,6 +141,76 @@ __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const dou
 }
 
 // ---------------------------------------------------------------------------
+// A, single pass (rows of at most 1024 * GROUPS padded elements): one workgroup
+// per padded row keeps the whole row in registers (4 * GROUPS doubles per
+// thread), reduces max |a_ij| through LDS and writes the k slices, so A is read
+// from HBM exactly once.  Thread t holds elements 4t + 1024 g .. + 3.
+// Workgroup b serves XCD b % 8 (hardware dispatch order); the row mapping below
+// gives the four rows of a 4-row group (whose 64-byte segments share 256
+// contiguous bytes of a packed tile) to four workgroups of the same XCD, so the
+// partial lines meet in one L2.
+// ---------------------------------------------------------------------------
+template <int GROUPS, bool VEC, bool MASK>
+__global__ __launch_bounds__(256) void k_split_A_row(int64_t m, int64_t n, const double* __restrict__ A, int64_t lda,
+                                                     int k, int beta, int8_t* __restrict__ SA,
+                                                     int32_t* __restrict__ eA, int64_t Npad, int64_t slice_stride,
+                                                     int64_t Rpad)
+{
+    __shared__ uint64_t part[4];
+    const int t = threadIdx.x;
+    // Rpad is a multiple of 256, so b / 8 and b % 8 cover whole groups of 32 rows
+    const int64_t b = blockIdx.x, x = b % 8, j = b / 8;
+    const int64_t R = ((j / 4) * 8 + x) * 4 + (j % 4);
+    const int64_t KT = Npad / TILE_K;
+    (void)Rpad;
+
+    if (R >= m) {  // padding row: zeros in every slice
+        for (int64_t l = 4 * t; l < Npad; l += 1024)
+            for (int s = 0; s < k; ++s)
+                *reinterpret_cast<uint32_t*>(SA + s * slice_stride + packed_offset(R, l, KT)) = 0u;
+        return;
+    }
+    const double* row = A + R * lda;
+    double v[GROUPS][4];
+    uint64_t mx = 0;
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) {
+        const int64_t l = 4 * t + 1024 * g;
+        if (VEC && l + 3 < n) {
+            double2 a = *reinterpret_cast<const double2*>(row + l);
+            double2 c = *reinterpret_cast<const double2*>(row + l + 2);
+            v[g][0] = a.x; v[g][1] = a.y; v[g][2] = c.x; v[g][3] = c.y;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[g][q] = (l + q < n) ? row[l + q] : 0.0;
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint64_t ab = abs_bits(v[g][q]);
+            mx = ab > mx ? ab : mx;
+        }
+    mx = wave_max_u64(mx);
+    if ((t & 63) == 0) part[t >> 6] = mx;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 4; ++w) mx = part[w] > mx ? part[w] : mx;
+    const int e = key_to_exp<MASK>(exp_key(mx));
+    if (t == 0) eA[R] = e;
+    const int sc = beta - 1 - e;
+    const double two_beta = (double)(1 << beta);
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) {
+        const int64_t l = 4 * t + 1024 * g;
+        if (l < Npad)
+            emit_slices4<MASK>(ldexp(v[g][0], sc), ldexp(v[g][1], sc), ldexp(v[g][2], sc), ldexp(v[g][3], sc), k,
+                               two_beta, SA + packed_offset(R, l, KT), slice_stride);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // B, pass 1: column maxima.  A workgroup covers 64 columns x LCH inner rows;
 // lane = column, so each wave reads 512 contiguous bytes per inner row.  The
 // per-column maximum is merged into keys[] with a 32-bit atomic max (order
@@ -426,8 +496,28 @@ hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, in
     const int64_t Rpad = ozl::rows_padded(m), Npad = ozl::inner_padded(n);
     const int64_t stride = ozl::slice_bytes(m, n);
     const bool vec = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 2 == 0);
-    dim3 grid((unsigned)(Rpad / 4)), block(256);
     const bool mask = split_mode != 0;
+    if (Npad <= 16384) {  // the row fits the registers of one workgroup: single pass over A
+        dim3 grid((unsigned)Rpad), block(256);
+#define OZ_LAUNCH_ROW(G, V, M)                                                                                  \
+    hipLaunchKernelGGL((k_split_A_row<G, V, M>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride, \
+                       Rpad)
+#define OZ_PICK_ROW(G)                         \
+    do {                                       \
+        if (vec && !mask) OZ_LAUNCH_ROW(G, true, false);       \
+        else if (!vec && !mask) OZ_LAUNCH_ROW(G, false, false); \
+        else if (vec) OZ_LAUNCH_ROW(G, true, true);             \
+        else OZ_LAUNCH_ROW(G, false, true);                     \
+    } while (0)
+        if (Npad <= 4096)
+            OZ_PICK_ROW(4);
+        else
+            OZ_PICK_ROW(16);
+#undef OZ_PICK_ROW
+#undef OZ_LAUNCH_ROW
+        return hipGetLastError();
+    }
+    dim3 grid((unsigned)(Rpad / 4)), block(256);
     if (vec && !mask)
         hipLaunchKernelGGL((k_split_A<true, false>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
     else if (!vec && !mask)

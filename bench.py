@@ -42,6 +42,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
     ap.add_argument("--no-native", action="store_true")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the register-only MFMA rate measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of A (known size) so that a rocprofv3 --pmc run "
                          "can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -152,6 +153,19 @@ def main() -> int:
         "split_hbm": {"algorithmic_GBps": round(split_bytes / split_ms / 1e6, 1), "peak_GBps": PEAK_HBM_GBS,
                       "frac": round(split_bytes / split_ms / 1e6 / PEAK_HBM_GBS, 4)},
     }
+
+    if not args.no_ceiling:
+        # what this chip sustains on the instruction the GEMM phase is made of, measured now on this machine:
+        # a register-only v_mfma_i32_32x32x32_i8 loop on every CU, operands uniform in [-64, 64] like
+        # round-to-nearest slices (the sustained clock depends on the operand statistics), and on zeros
+        sliceslike = ozimmu.mfma_rate_probe(300000, -64, 64)
+        zeros = ozimmu.mfma_rate_probe(300000, 0, 0)
+        result["roofline"]["sustained_mfma_rate"] = {
+            "unit": "TOP/s", "operands_uniform_in_-64..64": round(sliceslike, 1), "operands_zero": round(zeros, 1),
+            "what": "ozimmu_mfma_rate_probe: register-only MFMA loop, 4 waves on every CU, about 0.1 s per launch",
+            "gemm_phase_frac_of_it": round(gemm_tops / sliceslike, 4)}
+        log(f"register-only MFMA loop on this box: {sliceslike:.0f} TOP/s with slice-like operands, {zeros:.0f} TOP/s "
+            f"with zeros; the GEMM phase runs at {100.0 * gemm_tops / sliceslike:.1f} % of the former")
 
     per_k = {str(k): round(value, 3)}
     for kk in extra_ks:

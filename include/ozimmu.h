@@ -220,6 +220,19 @@ int ozimmu_gemm_group_accumulate(int64_t m, int64_t n, int64_t p,
 int ozimmu_export_slices(int64_t rows, int64_t n, int k, const int8_t *packed,
                          int8_t *out, void *stream);
 
+/* Measurement aid, not part of the method: what this chip sustains on the matrix-core instruction the
+ * GEMM phase is made of.  Launches one workgroup of 4 waves per compute unit; every wave runs `iters`
+ * rounds of 16 independent v_mfma_i32_32x32x32_i8 on register operands (no LDS or memory traffic in the
+ * loop), the operand bytes being pseudo-random and uniform in [value_lo, value_hi] (-64..64 is what
+ * round-to-nearest slices look like; 0..0 gives the data-independent rate).  The sustained clock of the
+ * chip under this load depends on the operand statistics, so the rate measured for [-64, 64] is the
+ * ceiling that the GEMM phase can be priced against next to the data-sheet peak.
+ *   out   device, at least 4 bytes (receives a checksum so that the loop is not optimised away).
+ *   *ops  host, receives the number of integer operations of the launch (2 per multiply-add).
+ * The caller times the launch (events on `stream`).  Errors: OZIMMU_ERR_NULL, OZIMMU_ERR_DIM for
+ * iters < 1 or a range outside -128..127, OZIMMU_ERR_HIP. */
+int ozimmu_mfma_rate_probe(int iters, int value_lo, int value_hi, int32_t *out, double *ops, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -355,6 +355,13 @@ int ozimmu_split_B_variant(int64_t n, int64_t p, const double* B, int64_t ldb, i
     return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), split_mode, SB, eB, (hipStream_t)stream));
 }
 
+int ozimmu_mfma_rate_probe(int iters, int value_lo, int value_hi, int32_t* out, double* ops, void* stream)
+{
+    if (!out || !ops) return OZIMMU_ERR_NULL;
+    if (iters < 1 || value_lo < -128 || value_hi > 127 || value_lo > value_hi) return OZIMMU_ERR_DIM;
+    return hip_status(ozk::launch_mfma_rate_probe(iters, value_lo, value_hi, out, ops, (hipStream_t)stream));
+}
+
 int64_t ozimmu_r_wide(int64_t n)
 {
     if (n < 1 || n > MAX_INNER) return 0;

@@ -455,6 +455,57 @@ __global__ __launch_bounds__(256) void k_axpby(int64_t m, int64_t p, double alph
     }
 }
 
+// Measurement aid: 16 independent accumulator tiles per wave, operands in registers, nothing else in the loop.
+// One operand register set is rotated per round so that consecutive rounds do not repeat the same products.
+__global__ __launch_bounds__(256) void k_mfma_rate_probe(int iters, int lo, int span, int32_t* out)
+{
+    uint32_t x = (uint32_t)(blockIdx.x * 256 + threadIdx.x) * 2654435761u + 12345u;
+    auto next_byte = [&]() -> uint32_t {
+        x = x * 1664525u + 1013904223u;
+        return (uint32_t)(lo + (int)((x >> 16) % (uint32_t)span)) & 0xffu;
+    };
+    auto next_v4i = [&]() -> v4i {
+        v4i v;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t b0 = next_byte(), b1 = next_byte(), b2 = next_byte(), b3 = next_byte();
+            v[d] = (int)(b0 | (b1 << 8) | (b2 << 16) | (b3 << 24));
+        }
+        return v;
+    };
+    v4i fa[4], fb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        fa[i] = next_v4i();
+        fb[i] = next_v4i();
+    }
+    v16i acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = (v16i){0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    for (int it = 0; it < iters; ++it) {
+        const v4i tmp = fa[0];
+        fa[0] = fa[1];
+        fa[1] = fa[2];
+        fa[2] = fa[3];
+        fa[3] = tmp;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
+    if (sum == 0x5a5a5a5a) out[0] = sum;  // practically never: keeps the loop alive without memory traffic
+}
+
 // zero the soft-barrier counters (a kernel rather than a memset so that the call can be captured in a graph)
 __global__ void k_fill_u32_gemm(unsigned* x) { x[threadIdx.x] = 0u; }
 
@@ -498,6 +549,20 @@ hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st)
         hipLaunchKernelGGL((k_gemm<1, NSTAGES>), grid, block, smem, st, a, TM, TP);
     else
         hipLaunchKernelGGL((k_gemm<0, NSTAGES>), grid, block, smem, st, a, TM, TP);
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_rate_probe(int iters, int lo, int hi, int32_t* out, double* ops, hipStream_t st)
+{
+    int dev = 0, ncu = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    if (ncu < 1) ncu = 1;
+    hipLaunchKernelGGL(k_mfma_rate_probe, dim3((unsigned)ncu), dim3(256), 0, st, iters, lo, hi - lo + 1, out);
+    // per wave and round: 16 MFMAs of 32 x 32 x 32 multiply-adds
+    *ops = (double)ncu * 4.0 * (double)iters * 16.0 * 2.0 * 32.0 * 32.0 * 32.0;
     return hipGetLastError();
 }
 

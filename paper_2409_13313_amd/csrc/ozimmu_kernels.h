@@ -55,6 +55,8 @@ hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc
 // Step (v): C <- alpha D + beta C (beta == 0: C not read).
 hipError_t launch_axpby(int64_t m, int64_t p, double alpha, const double* D, int64_t ldd, double beta, double* C,
                         int64_t ldc, hipStream_t st);
+// Register-only MFMA loop on every compute unit (measurement aid); *ops receives the operation count.
+hipError_t launch_mfma_rate_probe(int iters, int lo, int hi, int32_t* out, double* ops, hipStream_t st);
 hipError_t launch_fill_zero_f64(int64_t m, int64_t p, double* D, int64_t ldd, hipStream_t st);
 
 }  // namespace ozk

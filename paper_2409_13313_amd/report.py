@@ -13,6 +13,8 @@
   --small-beta m=p=2048, n=2^18 (beta = 6, r = 2) next to n=2^17 (beta = 7, r = 1): the loss of accuracy
                per slice beyond n = 2^17                                          [Section 4.1 remark]
 
+  --sizes      m=n=p in {1024 .. 16384}, k in {4, 8, 12}: time of ozimmu_dgemm against native FP64   [Section 4.2]
+
 Prints markdown tables.  The Dot2 reference comes from the CPU oracle package, which is test
 infrastructure; nothing here feeds back into the HIP path.
 """
@@ -239,6 +241,30 @@ def small_beta(m=2048, p=2048, phi=0.5, sample=64, reps=3):
     print()
 
 
+def sizes(ns=(1024, 2048, 3072, 4096, 6144, 8192, 12288, 16384), ks=(4, 8, 12), reps=5):
+    import torch
+    from paper_2409_13313_amd import inputs, ozimmu
+    print(f"### ozimmu_dgemm against native FP64 (torch.mm) over the matrix size, phi=0.5; median of {reps}, ms "
+          f"(speed-up over native)\n")
+    print("| m=n=p | native FP64 ms (TFLOP/s) | " + " | ".join(f"k={k}" for k in ks) + " |")
+    print("|---|---|" + "---|" * len(ks))
+    for n in ns:
+        A, B = inputs.phi_pair(n, n, n, 0.5, seed=0)
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        D = torch.empty((n, n), dtype=torch.float64, device="cuda")
+        ws = ozimmu.alloc_workspace(n, n, n, max(ks))
+        torch.mm(dA, dB, out=D)
+        t_nat = _median_ms(lambda: torch.mm(dA, dB, out=D), reps)
+        cells = []
+        for k in ks:
+            ozimmu.dgemm(dA, dB, k, D=D, workspace=ws)
+            t = _median_ms(lambda: ozimmu.dgemm(dA, dB, k, D=D, workspace=ws), reps)
+            cells.append(f"{t:.3f} ({t_nat / t:.2f}x)")
+        print(f"| {n} | {t_nat:.3f} ({2.0 * n ** 3 / t_nat / 1e9:.1f}) | " + " | ".join(cells) + " |")
+        del dA, dB, D, ws
+    print()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--accuracy", action="store_true")
@@ -247,6 +273,7 @@ def main():
     ap.add_argument("--variants", action="store_true")
     ap.add_argument("--perf-vs-accuracy", action="store_true")
     ap.add_argument("--small-beta", action="store_true")
+    ap.add_argument("--sizes", action="store_true")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
@@ -264,6 +291,8 @@ def main():
         perf_vs_accuracy()
     if args.small_beta:
         small_beta()
+    if args.sizes:
+        sizes()
     return 0
 
 

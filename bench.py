@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--k", type=int, default=8)
     ap.add_argument("--phi", type=float, default=0.5)
     ap.add_argument("--extra-k", type=str, default="12,14", help="further slice counts timed with 2 steps each")
+    ap.add_argument("--extra-phi", type=float, default=4.0,
+                    help="also time the same shape with this phi (0 = skip); the headline value stays --phi's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
     ap.add_argument("--no-native", action="store_true")
@@ -212,6 +214,36 @@ def main() -> int:
             acc["native_fp64"] = float((np.abs((got - hi) - lo) / absab).max())
         result["accuracy_max_err_over_absA_absB"] = {"sample": f"{S}x{S} entries vs Dot2", **acc}
         log("accuracy:", acc)
+
+    if args.extra_phi > 0:
+        # the wide-exponent-range inputs of the same configuration: same work, other operand statistics
+        A4, B4 = inputs.phi_pair(m, n, p, args.extra_phi, seed=0)
+        dA.copy_(torch.from_numpy(A4))
+        dB.copy_(torch.from_numpy(B4))
+        per_k4 = {}
+        for kk in [k] + extra_ks:
+            wms, sms, gms = timed(kk, 2, 1)
+            per_k4[str(kk)] = round(flops / (wms * 1e-3) / 1e12, 3)
+            log(f"phi={args.extra_phi} k={kk}: {wms:.2f} ms/step -> {per_k4[str(kk)]:.1f} TFLOP/s")
+        result["tflops_vs_k_phi%g" % args.extra_phi] = per_k4
+        if not args.no_accuracy:
+            S = min(96, m, p)
+            I = inputs.sample_indices(m, S, seed=1)
+            J = inputs.sample_indices(p, S, seed=2)
+            Asub, Bsub = np.ascontiguousarray(A4[I]), np.ascontiguousarray(B4[:, J])
+            hi, lo = oracle.dot2_gemm(Asub, Bsub)
+            absab = np.abs(Asub) @ np.abs(Bsub)
+            tI, tJ = torch.from_numpy(I).cuda(), torch.from_numpy(J).cuda()
+            acc4 = {}
+            for kk in [k] + extra_ks:
+                ozimmu.dgemm(dA, dB, kk, D=D, workspace=ws)
+                acc4[f"ozimmu_k{kk}"] = float((np.abs((D[tI][:, tJ].cpu().numpy() - hi) - lo) / absab).max())
+            if not args.no_native:
+                torch.mm(dA, dB, out=D)
+                acc4["native_fp64"] = float((np.abs((D[tI][:, tJ].cpu().numpy() - hi) - lo) / absab).max())
+            result["accuracy_phi%g" % args.extra_phi] = {"sample": f"{S}x{S} entries vs Dot2", **acc4}
+            log(f"accuracy phi={args.extra_phi}:", acc4)
+        del A4, B4
 
     if not args.no_cpu_baseline:
         # the oracle, untuned, on a bounded sample of the same workload: rows I and columns J of D

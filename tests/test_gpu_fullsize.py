@@ -22,6 +22,7 @@ def oz():
 FULL = [
     (8192, 8192, 8192, 0.5, [8]),                 # config 3
     (16384, 16384, 16384, 0.5, [8, 14]),          # config 4 (headline)
+    (16384, 16384, 16384, 4.0, [12]),             # config 4, wide exponent range
     (4096, 65536, 4096, 1.0, [10]),               # config 5: r = 2, 30 chunks
 ]
 

@@ -53,7 +53,9 @@ def special_matrix():
 
 # --------------------------------------------------------------------------- split
 SPLIT_CASES = [(256, 256, 0.5, 8, 0), (300, 200, 4.0, 14, 1), (1, 5, 1.0, 3, 2), (513, 1000, 2.0, 9, 3),
-               (64, 1029, 0.5, 20, 4), (5, 2 ** 17 + 5, 1.0, 4, 5)]
+               (64, 1029, 0.5, 20, 4), (5, 2 ** 17 + 5, 1.0, 4, 5),
+               # the three row-split kernels of A: row in registers (<= 4096, <= 16384 padded), two passes beyond
+               (20, 4096, 1.0, 5, 6), (40, 4097, 1.0, 6, 7), (33, 16384, 0.5, 8, 8), (9, 16385, 2.0, 5, 9)]
 
 
 @pytest.mark.parametrize("rows,n,phi,k,seed", SPLIT_CASES)

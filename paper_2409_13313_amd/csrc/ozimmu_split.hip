@@ -153,16 +153,14 @@ __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const dou
 template <int GROUPS, bool VEC, bool MASK>
 __global__ __launch_bounds__(256) void k_split_A_row(int64_t m, int64_t n, const double* __restrict__ A, int64_t lda,
                                                      int k, int beta, int8_t* __restrict__ SA,
-                                                     int32_t* __restrict__ eA, int64_t Npad, int64_t slice_stride,
-                                                     int64_t Rpad)
+                                                     int32_t* __restrict__ eA, int64_t Npad, int64_t slice_stride)
 {
     __shared__ uint64_t part[4];
     const int t = threadIdx.x;
-    // Rpad is a multiple of 256, so b / 8 and b % 8 cover whole groups of 32 rows
+    // the grid has rows_padded(m) workgroups, a multiple of 256, so b / 8 and b % 8 cover whole groups of 32 rows
     const int64_t b = blockIdx.x, x = b % 8, j = b / 8;
     const int64_t R = ((j / 4) * 8 + x) * 4 + (j % 4);
     const int64_t KT = Npad / TILE_K;
-    (void)Rpad;
 
     if (R >= m) {  // padding row: zeros in every slice
         for (int64_t l = 4 * t; l < Npad; l += 1024)
@@ -500,8 +498,7 @@ hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, in
     if (Npad <= 16384) {  // the row fits the registers of one workgroup: single pass over A
         dim3 grid((unsigned)Rpad), block(256);
 #define OZ_LAUNCH_ROW(G, V, M)                                                                                  \
-    hipLaunchKernelGGL((k_split_A_row<G, V, M>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride, \
-                       Rpad)
+    hipLaunchKernelGGL((k_split_A_row<G, V, M>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride)
 #define OZ_PICK_ROW(G)                         \
     do {                                       \
         if (vec && !mask) OZ_LAUNCH_ROW(G, true, false);       \

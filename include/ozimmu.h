@@ -64,7 +64,8 @@ int64_t ozimmu_num_chunks(int64_t n, int k);
  * is private to the library (tile-major, see ozimmu_export_slices). */
 size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k);
 
-/* Bytes of device workspace ozimmu_dgemm needs; host. */
+/* Bytes of device workspace ozimmu_dgemm needs (scheduling scratch, exponents, the two slice stacks and,
+ * for outputs of at most 128 tiles of 256 x 256, an INT32 m x p buffer for partial sums); host. */
 size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k);
 
 /* D <- A B with k slices: steps (i)-(iv) of the scheme (Section 1) as
@@ -109,6 +110,15 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p,
  * combination returns OZIMMU_ERR_SLICES. */
 enum { OZIMMU_SPLIT_NEAREST = 0, OZIMMU_SPLIT_BITMASK = 1, OZIMMU_SPLIT_NEAREST_PER_SLICE = 2 };
 enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 2 };
+/* How the schedule is run; OR one of these into accumulate_mode (default: the library chooses).  The result
+ * does not depend on it, bit for bit.
+ *   OZIMMU_SCHEDULE_ONE_LAUNCH   the whole schedule in one persistent kernel with the FP64 accumulation
+ *                                fused into the GEMM epilogue (what large outputs always get);
+ *   OZIMMU_SCHEDULE_SPLIT_INNER  outputs of at most 128 tiles of 256 x 256 only (else ignored): per chunk,
+ *                                the inner dimension is cut into parts that run on different workgroups and
+ *                                add their INT32 partial sums with integer atomics, then one accumulation
+ *                                kernel; chosen by default when few tiles meet a long inner dimension. */
+enum { OZIMMU_SCHEDULE_ONE_LAUNCH = 0x100, OZIMMU_SCHEDULE_SPLIT_INNER = 0x200 };
 int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p,
                          const double *A, int64_t lda, const double *B, int64_t ldb,
                          double *D, int64_t ldd, int k, int split_mode, int accumulate_mode,

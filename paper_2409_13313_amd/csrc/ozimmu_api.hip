@@ -42,6 +42,20 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
                double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
                size_t workspace_bytes, void* stream, void* const* events);
 
+// Outputs of at most this many 256 x 256 tiles leave most compute units without a tile; for them the inner
+// range of every chunk is cut into parts (see run_schedule).  A constant, so that the workspace size does
+// not depend on the device.
+constexpr int64_t SPLIT_INNER_MAX_TILES = 128;
+inline int64_t output_tiles(int64_t m, int64_t p)
+{
+    return (ozl::rows_padded(m) / ozl::TILE_R) * (ozl::rows_padded(p) / ozl::TILE_R);
+}
+// INT32 buffer for the partial sums of such outputs (0 for larger ones)
+inline int64_t partial_sums_bytes(int64_t m, int64_t p)
+{
+    return output_tiles(m, p) <= SPLIT_INNER_MAX_TILES ? align256(4 * m * p) : 0;
+}
+
 inline int hip_status(hipError_t e) { return e == hipSuccess ? OZIMMU_OK : OZIMMU_ERR_HIP; }
 
 int check_gemm_args(int64_t m, int64_t n, int64_t p, const void* SA, int kA, const void* SB, int kB, int g, int s0,
@@ -77,6 +91,67 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
     a.sync = static_cast<unsigned*>(scratch);
     a.spin_limit = 64;  // polls (about 0.1 us each) before a workgroup stops waiting for its team
     return a;
+}
+
+// Steps (iii) + (iv) for the whole schedule of Algorithm 6 (groups g = 2..k+1 ascending, chunks of at most r
+// consecutive s), into D.  Two ways to run it, with bit-identical results:
+//  * one persistent launch with the accumulation fused into the GEMM epilogue (mode 1, or 2 for per-slice
+//    scales) -- the way for outputs with enough tiles to fill the chip;
+//  * for outputs of few tiles (most compute units would idle): per chunk, zero an INT32 buffer, run the
+//    chunk GEMM with its inner range cut into Z parts on Z workgroups per tile that add their partial sums
+//    with integer atomics, then the stand-alone accumulation kernel.  Three launches per chunk, worth it
+//    when the tiles are few and the inner dimension long.
+// schedule: 0 = choose, OZIMMU_SCHEDULE_ONE_LAUNCH, OZIMMU_SCHEDULE_SPLIT_INNER (honoured when possible).
+int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, const int32_t* eA,
+                 const int32_t* eB, int k, int64_t r, bool per_slice, int schedule, double* D, int64_t ldd,
+                 int32_t* partial, void* scratch, hipStream_t st)
+{
+    const int beta = beta_of(n);
+    const int r_eff = (int)(r < k ? r : k);
+    const int KT = (int)(ozl::inner_padded(n) / ozl::TILE_K);
+    const int64_t T = output_tiles(m, p);
+    int Z = 1;
+    if (!per_slice && partial && T <= SPLIT_INNER_MAX_TILES && schedule != OZIMMU_SCHEDULE_ONE_LAUNCH) {
+        const int ncu = ozk::num_compute_units();
+        int64_t z = ncu > 0 ? ncu / T : 1;
+        if (z > KT / 4) z = KT / 4;  // every part gets at least one group of 4 stages of the shortest chunk
+        if (z >= 2) {
+            // stages per tile saved against the price of three launches per chunk instead of one launch in
+            // all (measured: worth it from 512^3 with k = 8 upwards)
+            int64_t w = 0;
+            for (int g = 2; g <= k + 1; ++g) w += ((g - 1) + r_eff - 1) / r_eff;
+            const int64_t stages = (int64_t)k * (k + 1) / 2 * KT;
+            if (schedule == OZIMMU_SCHEDULE_SPLIT_INNER || stages * (z - 1) / z > 8 * w) Z = (int)z;
+        }
+    }
+    if (Z == 1) {
+        ozk::GemmArgs a = make_args(m, n, p, SA, SB, 2, k + 1, r_eff, 0, 0, scratch);
+        a.D = D;
+        a.ldd = ldd;
+        a.eA = eA;
+        a.eB = eB;
+        a.estrideA = m;
+        a.estrideB = p;
+        a.first = 1;
+        return hip_status(ozk::launch_gemm(a, per_slice ? 2 : 1, st));
+    }
+    int first = 1;
+    for (int g = 2; g <= k + 1; ++g)
+        for (int s0 = 1; s0 <= g - 1; s0 += r_eff) {
+            const int s1 = s0 + r_eff - 1 < g - 1 ? s0 + r_eff - 1 : g - 1;
+            hipError_t e = ozk::launch_fill_zero_i32(m * p, partial, st);
+            if (e != hipSuccess) return OZIMMU_ERR_HIP;
+            ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch);
+            a.C = partial;
+            a.ldc = p;
+            a.zsplit = Z;
+            e = ozk::launch_gemm(a, 3, st);
+            if (e != hipSuccess) return OZIMMU_ERR_HIP;
+            e = ozk::launch_accumulate(m, p, partial, p, eA, eB, 2 - beta * g, first, D, ldd, st);
+            if (e != hipSuccess) return OZIMMU_ERR_HIP;
+            first = 0;
+        }
+    return OZIMMU_OK;
 }
 
 }  // namespace
@@ -124,7 +199,7 @@ size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k)
 {
     if (m < 0 || n < 0 || p < 0 || k < 0) return 0;
     return (size_t)(align256(OZIMMU_SCRATCH_BYTES) + align256(4 * m) + align256(4 * p)) +
-           ozimmu_slices_bytes(m, n, k) + ozimmu_slices_bytes(p, n, k);
+           ozimmu_slices_bytes(m, n, k) + ozimmu_slices_bytes(p, n, k) + (size_t)partial_sums_bytes(m, p);
 }
 
 int ozimmu_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int8_t* SA, int32_t* eA, void* stream)
@@ -250,15 +325,10 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
     const bool direct = (alpha == 1.0 && beta == 0.0);  // D is C
-    const int r_eff = (int)(r < k ? r : k);
-    ozk::GemmArgs a = make_args(m, n, p, SA, SB, 2, k + 1, r_eff, 0, 0, scratch);
-    a.D = direct ? C : Dw;
-    a.ldd = direct ? ldc : p;
-    a.eA = eA;
-    a.eB = eB;
-    a.first = 1;
-    e = ozk::launch_gemm(a, 1, st);
-    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+    int32_t* partial = partial_sums_bytes(m, p) ? reinterpret_cast<int32_t*>(Dw + m * p) : nullptr;
+    int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, false, 0, direct ? C : Dw, direct ? ldc : p, partial,
+                          scratch, st);
+    if (rc != OZIMMU_OK) return rc;
     if (!direct) {
         e = ozk::launch_axpby(m, p, alpha, Dw, p, beta, C, ldc, st);
         if (e != hipSuccess) return OZIMMU_ERR_HIP;
@@ -324,11 +394,13 @@ int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p, const double* A, int64
                          double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
                          size_t workspace_bytes, void* stream)
 {
+    const int flags = accumulate_mode & ~0xff, amode = accumulate_mode & 0xff;
     if (split_mode < OZIMMU_SPLIT_NEAREST || split_mode > OZIMMU_SPLIT_NEAREST_PER_SLICE) return OZIMMU_ERR_SLICES;
-    if (accumulate_mode < OZIMMU_ACCUM_GROUPED || accumulate_mode > OZIMMU_ACCUM_WIDE) return OZIMMU_ERR_SLICES;
-    if (accumulate_mode == OZIMMU_ACCUM_WIDE && split_mode != OZIMMU_SPLIT_NEAREST) return OZIMMU_ERR_SLICES;
-    if (split_mode == OZIMMU_SPLIT_NEAREST_PER_SLICE && accumulate_mode != OZIMMU_ACCUM_PER_PAIR)
+    if (amode < OZIMMU_ACCUM_GROUPED || amode > OZIMMU_ACCUM_WIDE) return OZIMMU_ERR_SLICES;
+    if (flags != 0 && flags != OZIMMU_SCHEDULE_ONE_LAUNCH && flags != OZIMMU_SCHEDULE_SPLIT_INNER)
         return OZIMMU_ERR_SLICES;
+    if (amode == OZIMMU_ACCUM_WIDE && split_mode != OZIMMU_SPLIT_NEAREST) return OZIMMU_ERR_SLICES;
+    if (split_mode == OZIMMU_SPLIT_NEAREST_PER_SLICE && amode != OZIMMU_ACCUM_PER_PAIR) return OZIMMU_ERR_SLICES;
     return dgemm_impl(m, n, p, A, lda, B, ldb, D, ldd, k, split_mode, accumulate_mode, workspace, workspace_bytes,
                       stream, nullptr);
 }
@@ -388,6 +460,8 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
         workspace_bytes < ozimmu_workspace_bytes_variant(m, n, p, k, split_mode))
         return OZIMMU_ERR_WORKSPACE;
 
+    const int schedule = accumulate_mode & (OZIMMU_SCHEDULE_ONE_LAUNCH | OZIMMU_SCHEDULE_SPLIT_INNER);
+    accumulate_mode &= 0xff;
     const int beta = beta_of(n);
     const bool per_slice = split_mode == OZIMMU_SPLIT_NEAREST_PER_SLICE;
     const int64_t ne = per_slice ? k : 1;  // exponent arrays per operand
@@ -422,19 +496,11 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     e = mark(1);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
-    // one persistent launch runs the whole schedule of Algorithm 6: groups g = 2..k+1 in ascending
-    // order, each in chunks of at most r consecutive s, one fused FP64 accumulation per chunk
-    const int r_eff = (int)(r < k ? r : k);
-    ozk::GemmArgs a = make_args(m, n, p, SA, SB, 2, k + 1, r_eff, 0, 0, scratch);
-    a.D = D;
-    a.ldd = ldd;
-    a.eA = eA;
-    a.eB = eB;
-    a.estrideA = m;
-    a.estrideB = p;
-    a.first = 1;
-    e = ozk::launch_gemm(a, per_slice ? 2 : 1, st);
-    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+    int32_t* partial = nullptr;  // INT32 partial sums of few-tile outputs, behind the slices
+    if (!per_slice && partial_sums_bytes(m, p))
+        partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(SB) + ozimmu_slices_bytes(p, n, k));
+    const int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, per_slice, schedule, D, ldd, partial, scratch, st);
+    if (rc != OZIMMU_OK) return rc;
     return hip_status(mark(2));
 }
 

@@ -9,6 +9,9 @@
 // single FP64 addition per chunk is the only rounding on the whole path.
 // MODE 2 is MODE 1 for slices that carry one scale each (Algorithm 5): every chunk
 // is one pair (s, t) and the factor is 2^(2 - 2 beta) diag(2^eA_s) . diag(2^eB_t).
+// MODE 3 is MODE 0 for outputs with few tiles: the inner range of the chunk is cut
+// into Z parts that run on different workgroups and add their INT32 partial sums to
+// a zeroed C'' with integer atomics (exact in any order).
 //
 // Tiling: 256 x 256 outputs per workgroup, 4 waves in a 2 x 2 grid, each wave
 // 128 x 128 = 4 x 4 tiles of v_mfma_i32_32x32x32_i8 (256 INT32 accumulators per
@@ -167,7 +170,9 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     const int nwg = gridDim.x, bid = blockIdx.x;
     const int xcd = bid % NXCD, member = bid / NXCD;
     const int team = nwg / NXCD + (xcd < nwg % NXCD ? 1 : 0);
-    const int T = TM * TP;
+    // MODE 3 cuts the inner range of every chunk into Z parts; a work item is (tile, part), parts adjacent
+    const int Z = (MODE == 3) ? a.zsplit : 1;
+    const int T = TM * TP * Z;
     const int tiles_base = T / NXCD, tiles_rem = T % NXCD;
     const int range_off = xcd * tiles_base + (xcd < tiles_rem ? xcd : tiles_rem);
     const int range_cnt = tiles_base + (xcd < tiles_rem ? 1 : 0);
@@ -194,7 +199,9 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
             }
         }
         int tm, tp;
-        tile_of_linear(range_off + local, TM, TP, tm, tp);
+        const int item = range_off + local;
+        const int zpart = (MODE == 3) ? item % Z : 0;
+        tile_of_linear((MODE == 3) ? item / Z : item, TM, TP, tm, tp);
         const int64_t row0 = (int64_t)tm * 256 + wm * 128;
         const int64_t col0 = (int64_t)tp * 256 + wn * 128;
         int first = a.first;
@@ -213,10 +220,22 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
             const int s_hi = a.s0 > 0 ? a.s1 : g - 1;
             for (int c0 = s_lo; c0 <= s_hi; c0 += a.r) {
                 const int c1 = (c0 + a.r - 1 < s_hi) ? c0 + a.r - 1 : s_hi;  // chunk: s = c0..c1
-                const int nstage = (c1 - c0 + 1) * KT;
-
-                Cursor ca = {a.SA + (int64_t)(c0 - 1) * a.strideA + (int64_t)tm * rowblock_bytes(KT), KT / NS};
-                Cursor cb = {a.SB + (int64_t)(g - c0 - 1) * a.strideB + (int64_t)tp * rowblock_bytes(KT), KT / NS};
+                int nstage = (c1 - c0 + 1) * KT;
+                int pair0 = 0, kt0 = 0;  // slice pair and inner tile this workgroup starts at
+                if (MODE == 3) {
+                    // part zpart of the chunk's groups of NS stages (the host keeps Z <= KT / NS: no part is empty)
+                    const int groups = nstage / NS;
+                    const int g0 = (int)((int64_t)zpart * groups / Z), g1 = (int)((int64_t)(zpart + 1) * groups / Z);
+                    pair0 = g0 * NS / KT;
+                    kt0 = g0 * NS % KT;
+                    nstage = (g1 - g0) * NS;
+                }
+                Cursor ca = {a.SA + (int64_t)(c0 - 1 + pair0) * a.strideA + (int64_t)tm * rowblock_bytes(KT) +
+                                 (int64_t)kt0 * TILE_BYTES,
+                             (KT - kt0) / NS};
+                Cursor cb = {a.SB + (int64_t)(g - c0 - 1 - pair0) * a.strideB + (int64_t)tp * rowblock_bytes(KT) +
+                                 (int64_t)kt0 * TILE_BYTES,
+                             (KT - kt0) / NS};
                 // a cursor that has just copied the last inner tile of a slice jumps to the next slice pair
                 auto wrap_check = [&](Cursor& c, int64_t extra) {
                     const bool wr = (--c.groups_left == 0);
@@ -355,7 +374,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 asm volatile("" : "+s"(er0), "+s"(ec0));
                 const bool lane_col_ok[4] = {ec0 + lr < a.p, ec0 + 32 + lr < a.p, ec0 + 64 + lr < a.p,
                                              ec0 + 96 + lr < a.p};
-                if (MODE == 0) {
+                if (MODE == 0 || MODE == 3) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -365,7 +384,13 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 const int64_t urow = er0 + i * 32 + 8 * (r / 4) + (r % 4);  // uniform part of the row
                                 int32_t* base = a.C + urow * a.ldc + ec0 + j * 32;
                                 const uint32_t off = (uint32_t)(4 * lh) * (uint32_t)a.ldc + (uint32_t)lr;
-                                if (lane_col_ok[j] && urow + 4 * lh < a.m) base[off] = acc[i][j][r];
+                                if (lane_col_ok[j] && urow + 4 * lh < a.m) {
+                                    if (MODE == 3)  // partial sum of one part: integer adds commute, C'' starts at zero
+                                        __hip_atomic_fetch_add(&base[off], acc[i][j][r], __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+                                    else
+                                        base[off] = acc[i][j][r];
+                                }
                             }
                 } else {
                     // Exponents come from LDS (the compiler cannot prove that D does not alias eA / eB and
@@ -506,6 +531,14 @@ __global__ __launch_bounds__(256) void k_mfma_rate_probe(int iters, int lo, int 
     if (sum == 0x5a5a5a5a) out[0] = sum;  // practically never: keeps the loop alive without memory traffic
 }
 
+__global__ __launch_bounds__(256) void k_zero_i32(int64_t count, int32_t* __restrict__ x)
+{
+    const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (i0 + q < count) x[i0 + q] = 0;
+}
+
 // zero the soft-barrier counters (a kernel rather than a memset so that the call can be captured in a graph)
 __global__ void k_fill_u32_gemm(unsigned* x) { x[threadIdx.x] = 0u; }
 
@@ -530,6 +563,9 @@ hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<1, NSTAGES>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<3, NSTAGES>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2, NSTAGES>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
@@ -538,12 +574,14 @@ hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st)
         attr_set[dev] = true;
     }
     // one workgroup per CU (the LDS ring allows no second one), never more workgroups than tiles
-    const int64_t tiles = (int64_t)TM * TP;
+    const int64_t tiles = (int64_t)TM * TP * (fused == 3 ? a.zsplit : 1);
     int nwg = num_cu[dev] > 0 ? num_cu[dev] : 1;
     if (tiles < nwg) nwg = (int)tiles;
     hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(NXCD * 16), 0, st, a.sync);
     dim3 grid((unsigned)nwg), block(256);
-    if (fused == 2)
+    if (fused == 3)
+        hipLaunchKernelGGL((k_gemm<3, NSTAGES>), grid, block, smem, st, a, TM, TP);
+    else if (fused == 2)
         hipLaunchKernelGGL((k_gemm<2, NSTAGES>), grid, block, smem, st, a, TM, TP);
     else if (fused)
         hipLaunchKernelGGL((k_gemm<1, NSTAGES>), grid, block, smem, st, a, TM, TP);
@@ -563,6 +601,21 @@ hipError_t launch_mfma_rate_probe(int iters, int lo, int hi, int32_t* out, doubl
     hipLaunchKernelGGL(k_mfma_rate_probe, dim3((unsigned)ncu), dim3(256), 0, st, iters, lo, hi - lo + 1, out);
     // per wave and round: 16 MFMAs of 32 x 32 x 32 multiply-adds
     *ops = (double)ncu * 4.0 * (double)iters * 16.0 * 2.0 * 32.0 * 32.0 * 32.0;
+    return hipGetLastError();
+}
+
+int num_compute_units()
+{
+    int dev = 0, ncu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return ncu;
+}
+
+hipError_t launch_fill_zero_i32(int64_t count, int32_t* x, hipStream_t st)
+{
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)((count + 1023) / 1024)), dim3(256), 0, st, count, x);
     return hipGetLastError();
 }
 

@@ -41,14 +41,19 @@ struct GemmArgs {
     const int32_t* eA;
     const int32_t* eB;
     int64_t estrideA, estrideB;  // fused == 2 only: elements from the exponents of slice s to those of slice s+1
+    int zsplit;            // fused == 3 only: parts the inner range of a chunk is cut into (<= KT / 4)
     int beta;              // shift of group g is 2 - beta * g
     int first;             // D is zero before the first chunk: overwrite
     unsigned* sync;        // 8 x 16 counters, zeroed by launch_gemm: [16 x] per-XCD soft barrier, [1] whole grid
     int spin_limit;        // polls before a soft barrier gives up
 };
-// Steps (iii) (+ (iv) when fused != 0) for the chunks of the schedule (Algorithm 6).  fused == 2: one scale
-// per slice (Algorithm 5), r must be 1.
+// Steps (iii) (+ (iv) when fused is 1 or 2) for the chunks of the schedule (Algorithm 6).  fused == 2: one scale
+// per slice (Algorithm 5), r must be 1.  fused == 3: INT32 partial sums of a.zsplit inner parts added to a
+// zeroed C (single chunk).
 hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st);
+// Compute units of the current device (0 on error).
+int num_compute_units();
+hipError_t launch_fill_zero_i32(int64_t count, int32_t* x, hipStream_t st);
 // Step (iv) alone.
 hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA,
                              const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st);

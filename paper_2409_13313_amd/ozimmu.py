@@ -86,6 +86,7 @@ EXPORTS = ["ozimmu_status_string", "ozimmu_params", "ozimmu_num_chunks", "ozimmu
 
 SPLIT_MODES = {"rn": 0, "bitmask": 1, "per_slice": 2}
 ACCUMULATE_MODES = {"grouped": 0, "per_pair": 1, "wide": 2}
+SCHEDULES = {"auto": 0, "one_launch": 0x100, "split_inner": 0x200}
 
 
 class OzimmuError(RuntimeError):
@@ -182,8 +183,10 @@ def r_wide(n: int) -> int:
 
 
 def dgemm_variant(A: torch.Tensor, B: torch.Tensor, k: int, split: str = "rn", accumulate: str = "grouped",
-                  D: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """D = A B in one of the variants of Section 4 (see ozimmu_dgemm_variant in the header)."""
+                  D: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                  schedule: str = "auto") -> torch.Tensor:
+    """D = A B in one of the variants of Section 4 (see ozimmu_dgemm_variant in the header); schedule
+    "one_launch" / "split_inner" forces how the schedule is run (same bits either way)."""
     _dev(A, torch.float64), _dev(B, torch.float64)
     m, n = A.shape
     n2, p = B.shape
@@ -194,7 +197,8 @@ def dgemm_variant(A: torch.Tensor, B: torch.Tensor, k: int, split: str = "rn", a
     if workspace is None:
         workspace = alloc_workspace(m, n, p, k, A.device, split)
     _check(_lib.ozimmu_dgemm_variant(m, n, p, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), D.data_ptr(), _ld(D), k,
-                                     SPLIT_MODES[split], ACCUMULATE_MODES[accumulate], workspace.data_ptr(),
+                                     SPLIT_MODES[split], ACCUMULATE_MODES[accumulate] | SCHEDULES[schedule],
+                                     workspace.data_ptr(),
                                      workspace.numel(), _stream()))
     return D
 

@@ -15,6 +15,8 @@
 
   --sizes      m=n=p in {1024 .. 16384}, k in {4, 8, 12}: time of ozimmu_dgemm against native FP64   [Section 4.2]
 
+  --schedules  outputs of few tiles: the one-launch schedule against the split-inner one and native FP64
+
 Prints markdown tables.  The Dot2 reference comes from the CPU oracle package, which is test
 infrastructure; nothing here feeds back into the HIP path.
 """
@@ -265,6 +267,34 @@ def sizes(ns=(1024, 2048, 3072, 4096, 6144, 8192, 12288, 16384), ks=(4, 8, 12), 
     print()
 
 
+def schedules(k=8, reps=5):
+    import torch
+    from paper_2409_13313_amd import inputs, ozimmu
+    shapes = [(512, 512, 512), (1024, 1024, 1024), (2048, 2048, 2048), (2560, 2560, 2560), (3072, 3072, 3072),
+              (1024, 16384, 1024), (1024, 65536, 1024), (2048, 131072, 2048), (512, 131072, 512), (256, 262144, 256)]
+    print(f"### outputs of few 256 x 256 tiles, k={k}, phi=0.5; median of {reps}, ms (effective TFLOP/s)\n")
+    print("| m x n x p | tiles | one launch | split inner | what the library picks | native FP64 |")
+    print("|---|---|---|---|---|---|")
+    for (m, n, p) in shapes:
+        A, B = inputs.phi_pair(m, n, p, 0.5, seed=0)
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        D = torch.empty((m, p), dtype=torch.float64, device="cuda")
+        ws = ozimmu.alloc_workspace(m, n, p, k)
+        flops = 2.0 * m * n * p
+        cells = []
+        for sched in ("one_launch", "split_inner", "auto"):
+            run = lambda: ozimmu.dgemm_variant(dA, dB, k, "rn", "grouped", D=D, workspace=ws, schedule=sched)
+            run()
+            t = _median_ms(run, reps)
+            cells.append(f"{t:.3f} ({flops / t / 1e9:.1f})")
+        torch.mm(dA, dB, out=D)
+        t = _median_ms(lambda: torch.mm(dA, dB, out=D), reps)
+        tiles = ((m + 255) // 256) * ((p + 255) // 256)
+        print(f"| {m} x {n} x {p} | {tiles} | " + " | ".join(cells) + f" | {t:.3f} ({flops / t / 1e9:.1f}) |")
+        del dA, dB, D, ws
+    print()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--accuracy", action="store_true")
@@ -274,6 +304,7 @@ def main():
     ap.add_argument("--perf-vs-accuracy", action="store_true")
     ap.add_argument("--small-beta", action="store_true")
     ap.add_argument("--sizes", action="store_true")
+    ap.add_argument("--schedules", action="store_true")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
@@ -293,6 +324,8 @@ def main():
         small_beta()
     if args.sizes:
         sizes()
+    if args.schedules:
+        schedules()
     return 0
 
 

@@ -1,0 +1,79 @@
+"""GPU parity of the two ways the schedule is run: one persistent launch with the fused epilogue, and the
+split-inner way for outputs of few tiles (partial INT32 sums by integer atomics + accumulation kernel).
+Both must give the oracle's D bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2409_13313_amd import inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def oz():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: the HIP path has no CPU fallback")
+    from paper_2409_13313_amd import ozimmu
+    return ozimmu
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+SHAPES = [
+    (300, 520, 270, 8, 0.5),       # 4 tiles, 12 inner tiles: 3 parts
+    (513, 1029, 257, 6, 2.0),      # 6 ragged tiles, 20 inner tiles: 5 parts
+    (130, 65536, 70, 5, 1.0),      # 1 tile, r = 2, 16 parts, parts that start inside a slice pair
+    (1024, 1024, 1024, 12, 0.5),   # 16 tiles, 4 parts, chunks of up to 12 pairs
+    (256, 256, 256, 8, 0.5),       # one group of stages per pair: nothing to cut, falls back to one launch
+    (40, 2 ** 17 + 128, 64, 4, 0.5),   # beta = 6
+]
+
+
+@pytest.mark.parametrize("schedule", ["one_launch", "split_inner", "auto"])
+@pytest.mark.parametrize("m,n,p,k,phi", SHAPES)
+def test_both_schedules_match_the_oracle_bit_for_bit(oz, m, n, p, k, phi, schedule):
+    A, B = inputs.phi_pair(m, n, p, phi, seed=91)
+    want = oracle.dgemm(A, B, k)
+    D = torch.full((m, p), float("nan"), dtype=torch.float64, device="cuda")
+    oz.dgemm_variant(dev(A), dev(B), k, "rn", "grouped", D=D, schedule=schedule)
+    got = D.cpu().numpy()
+    assert np.isfinite(got).all()
+    assert (np.abs(got - want) <= 2 * np.spacing(np.abs(want))).all()
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("split,accumulate", [("bitmask", "grouped"), ("bitmask", "per_pair"), ("rn", "wide")])
+def test_split_inner_schedule_with_the_comparison_variants(oz, split, accumulate):
+    m, n, p, k = 300, 2000, 270, 9
+    A, B = inputs.phi_pair(m, n, p, 2.0, seed=92)
+    want = oracle.dgemm_variant(A, B, k, split, accumulate)
+    got = oz.dgemm_variant(dev(A), dev(B), k, split, accumulate, schedule="split_inner").cpu().numpy()
+    assert np.array_equal(got, want)
+
+
+def test_split_inner_with_strided_output_and_reused_workspace(oz):
+    m, n, p, k = 200, 3000, 150, 7
+    A, B = inputs.phi_pair(m, n, p, 1.0, seed=93)
+    want = oracle.dgemm(A, B, k)
+    Dbig = torch.full((m, p + 3), -1.0, dtype=torch.float64, device="cuda")
+    ws = oz.alloc_workspace(m, n, p, k)
+    ws.fill_(0x5A)                       # stale bytes (also in the partial-sum buffer) must not leak
+    for _ in range(2):
+        oz.dgemm_variant(dev(A), dev(B), k, "rn", "grouped", D=Dbig[:, :p], workspace=ws, schedule="split_inner")
+    got = Dbig.cpu().numpy()
+    assert np.array_equal(got[:, :p], want) and (got[:, p:] == -1.0).all()
+
+
+def test_schedule_flags_are_validated(oz):
+    A = torch.zeros((4, 4), dtype=torch.float64, device="cuda")
+    ws = oz.alloc_workspace(4, 4, 4, 4)
+    st = torch.cuda.current_stream().cuda_stream
+    D = torch.empty((4, 4), dtype=torch.float64, device="cuda")
+    for bad in (0x300, 0x400, 0x103 | 0x200):
+        rc = oz._lib.ozimmu_dgemm_variant(4, 4, 4, A.data_ptr(), 4, A.data_ptr(), 4, D.data_ptr(), 4, 4, 0, bad,
+                                          ws.data_ptr(), ws.numel(), st)
+        assert rc == -3

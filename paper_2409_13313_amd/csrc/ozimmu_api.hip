@@ -97,10 +97,11 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
 // consecutive s), into D.  Two ways to run it, with bit-identical results:
 //  * one persistent launch with the accumulation fused into the GEMM epilogue (mode 1, or 2 for per-slice
 //    scales) -- the way for outputs with enough tiles to fill the chip;
-//  * for outputs of few tiles (most compute units would idle): per chunk, zero an INT32 buffer, run the
-//    chunk GEMM with its inner range cut into Z parts on Z workgroups per tile that add their partial sums
-//    with integer atomics, then the stand-alone accumulation kernel.  Three launches per chunk, worth it
-//    when the tiles are few and the inner dimension long.
+//  * for outputs of few tiles (most compute units would idle): per chunk, run the chunk GEMM with its inner
+//    range cut into Z parts on Z workgroups per tile that add their partial sums to a zeroed INT32 buffer
+//    with integer atomics, then the stand-alone accumulation kernel, which also clears the buffer again.
+//    Two launches (three with the counter reset) per chunk, worth it when the tiles are few and the inner
+//    dimension long.
 // schedule: 0 = choose, OZIMMU_SCHEDULE_ONE_LAUNCH, OZIMMU_SCHEDULE_SPLIT_INNER (honoured when possible).
 int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, const int32_t* eA,
                  const int32_t* eB, int k, int64_t r, bool per_slice, int schedule, double* D, int64_t ldd,
@@ -136,18 +137,18 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         return hip_status(ozk::launch_gemm(a, per_slice ? 2 : 1, st));
     }
     int first = 1;
+    hipError_t e = ozk::launch_fill_zero_i32(m * p, partial, st);  // later chunks find it cleared by the accumulation
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
     for (int g = 2; g <= k + 1; ++g)
         for (int s0 = 1; s0 <= g - 1; s0 += r_eff) {
             const int s1 = s0 + r_eff - 1 < g - 1 ? s0 + r_eff - 1 : g - 1;
-            hipError_t e = ozk::launch_fill_zero_i32(m * p, partial, st);
-            if (e != hipSuccess) return OZIMMU_ERR_HIP;
             ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch);
             a.C = partial;
             a.ldc = p;
             a.zsplit = Z;
             e = ozk::launch_gemm(a, 3, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;
-            e = ozk::launch_accumulate(m, p, partial, p, eA, eB, 2 - beta * g, first, D, ldd, st);
+            e = ozk::launch_accumulate_and_clear(m, p, partial, p, eA, eB, 2 - beta * g, first, D, ldd, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;
             first = 0;
         }

@@ -437,8 +437,10 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     }
 }
 
-// Step (iv) alone: one thread per element, lanes along a row of D.
-__global__ __launch_bounds__(256) void k_accumulate(int64_t m, int64_t p, const int32_t* __restrict__ C, int64_t ldc,
+// Step (iv) alone: one thread per element, lanes along a row of D.  ZERO: C is cleared after use (the
+// split-inner schedule hands the same buffer to the next chunk's integer atomics).
+template <bool ZERO>
+__global__ __launch_bounds__(256) void k_accumulate(int64_t m, int64_t p, int32_t* __restrict__ C, int64_t ldc,
                                                     const int32_t* __restrict__ eA, const int32_t* __restrict__ eB,
                                                     int shift, int first, double* __restrict__ D, int64_t ldd)
 {
@@ -448,6 +450,7 @@ __global__ __launch_bounds__(256) void k_accumulate(int64_t m, int64_t p, const 
     const int eb = eB[j] + shift;
     for (int64_t i = i0; i < i0 + 8 && i < m; ++i) {
         const double term = ldexp((double)C[i * ldc + j], eA[i] + eb);
+        if (ZERO) C[i * ldc + j] = 0;
         double* d = D + i * ldd + j;
         *d = first ? term : (*d + term);
     }
@@ -623,7 +626,16 @@ hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc
                              const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st)
 {
     dim3 grid((unsigned)((m + 7) / 8), (unsigned)((p + 255) / 256));
-    hipLaunchKernelGGL(k_accumulate, grid, dim3(256), 0, st, m, p, C, ldc, eA, eB, shift, first, D, ldd);
+    hipLaunchKernelGGL(k_accumulate<false>, grid, dim3(256), 0, st, m, p, const_cast<int32_t*>(C), ldc, eA, eB, shift,
+                       first, D, ldd);
+    return hipGetLastError();
+}
+
+hipError_t launch_accumulate_and_clear(int64_t m, int64_t p, int32_t* C, int64_t ldc, const int32_t* eA,
+                                       const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st)
+{
+    dim3 grid((unsigned)((m + 7) / 8), (unsigned)((p + 255) / 256));
+    hipLaunchKernelGGL(k_accumulate<true>, grid, dim3(256), 0, st, m, p, C, ldc, eA, eB, shift, first, D, ldd);
     return hipGetLastError();
 }
 

@@ -57,6 +57,10 @@ hipError_t launch_fill_zero_i32(int64_t count, int32_t* x, hipStream_t st);
 // Step (iv) alone.
 hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA,
                              const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st);
+// The same, and C is left zeroed.
+hipError_t launch_accumulate_and_clear(int64_t m, int64_t p, int32_t* C, int64_t ldc, const int32_t* eA,
+                                       const int32_t* eB, int shift, int first, double* D, int64_t ldd,
+                                       hipStream_t st);
 // Step (v): C <- alpha D + beta C (beta == 0: C not read).
 hipError_t launch_axpby(int64_t m, int64_t p, double alpha, const double* D, int64_t ldd, double beta, double* C,
                         int64_t ldc, hipStream_t st);

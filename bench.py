@@ -169,6 +169,32 @@ def main() -> int:
         log(f"register-only MFMA loop on this box: {sliceslike:.0f} TOP/s with slice-like operands, {zeros:.0f} TOP/s "
             f"with zeros; the GEMM phase runs at {100.0 * gemm_tops / sliceslike:.1f} % of the former")
 
+    if not args.no_native and hasattr(torch, "_int_mm"):
+        # context: the INT8 GEMM of the vendor library on one slice-pair-sized product with slice-like
+        # operands (what a design with one library GEMM call per slice pair would run 36 times)
+        try:
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(0)
+            qa = torch.randint(-64, 65, (m, n), dtype=torch.int8, device="cuda", generator=gen)
+            qb = torch.randint(-64, 65, (p, n), dtype=torch.int8, device="cuda", generator=gen).t()  # inner index contiguous
+            torch._int_mm(qa, qb)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                qc = torch._int_mm(qa, qb)
+            e1.record()
+            torch.cuda.synchronize()
+            lib_ms = e0.elapsed_time(e1) / 3
+            result["library_int8_gemm"] = {"ms": round(lib_ms, 3), "tops": round(flops / lib_ms / 1e9, 1),
+                                           "what": "torch._int_mm (vendor INT8 GEMM) on one m x n x p product of int8 "
+                                                   "operands uniform in [-64, 64], both operands inner-contiguous"}
+            log(f"vendor INT8 GEMM (torch._int_mm), one slice-pair-sized product: {lib_ms:.2f} ms -> "
+                f"{flops / lib_ms / 1e9:.0f} TOP/s")
+            del qa, qb, qc
+        except Exception as ex:  # not every build of torch carries it for every shape
+            log(f"torch._int_mm not usable here: {ex!r}")
+
     per_k = {str(k): round(value, 3)}
     for kk in extra_ks:
         wms, sms, gms = timed(kk, 2, 1)

@@ -581,7 +581,7 @@ hipError_t launch_split_B_per_slice(int64_t n, int64_t p, const double* B, int64
 
 hipError_t launch_export(int64_t rows, int64_t n, int k, const int8_t* packed, int8_t* out, hipStream_t st)
 {
-    const int64_t Rpad = ozl::rows_padded(rows), Npad = ozl::inner_padded(n);
+    const int64_t Npad = ozl::inner_padded(n);
     const int64_t total = (int64_t)k * rows * n;
     if (total == 0) return hipSuccess;
     hipLaunchKernelGGL(k_export, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, rows, n, k, packed, out,

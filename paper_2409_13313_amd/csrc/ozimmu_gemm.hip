@@ -120,7 +120,9 @@ struct Cursor {
 // The tiles of the output are split into 8 contiguous ranges, one per XCD, in
 // band order (GROUP tile rows walked column by column); in round q the team
 // works on tiles q*team .. q*team+team-1 of its range, i.e. an 8 x 4 patch
-// whose A and B tiles are shared through the XCD's L2.  For its tile a
+// whose A and B tiles are shared through the XCD's L2.  (Tile grids made of
+// 16 x 16 blocks place the eight patches of a round side by side instead, see
+// below.)  For its tile a
 // workgroup runs every chunk of the schedule in the order of Algorithm 6.
 //
 // The main loop is unrolled NS times so that every LDS address is a register
@@ -201,7 +203,19 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
         int tm, tp;
         const int item = range_off + local;
         const int zpart = (MODE == 3) ? item % Z : 0;
-        tile_of_linear((MODE == 3) ? item / Z : item, TM, TP, tm, tp);
+        if (MODE != 3 && TM % 16 == 0 && TP % 16 == 0 && nwg == 32 * NXCD) {
+            // Tile grid made of 16 x 16 blocks and a full grid of workgroups: in round q the 8 x 4 patches of
+            // the eight XCDs tile block q (2 x 4 patches), so that all XCDs together stream 16 A and 16 B
+            // tile rows (instead of 64 + 4 when every XCD walks a band of its own) and the memory-side cache
+            // serves what another XCD has just fetched.  Blocks in boustrophedon order.  (1.4 % at 16384^3.)
+            const int q = local / 32, mem = local % 32;
+            const int sbr = q / (TP / 16), sbc0 = q % (TP / 16);
+            const int sbc = (sbr & 1) ? (TP / 16 - 1 - sbc0) : sbc0;
+            tm = sbr * 16 + (xcd / 4) * 8 + mem % 8;
+            tp = sbc * 16 + (xcd % 4) * 4 + mem / 8;
+        } else {
+            tile_of_linear((MODE == 3) ? item / Z : item, TM, TP, tm, tp);
+        }
         const int64_t row0 = (int64_t)tm * 256 + wm * 128;
         const int64_t col0 = (int64_t)tp * 256 + wn * 128;
         int first = a.first;

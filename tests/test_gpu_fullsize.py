@@ -35,7 +35,10 @@ def test_full_size_sampled_entries(oz, m, n, p, phi, ks):
     I = inputs.sample_indices(m, 40, seed=1)
     J = inputs.sample_indices(p, 40, seed=2)
     D = torch.empty((m, p), dtype=torch.float64, device="cuda")
+    native = torch.mm(dA, dB)
+    bound = torch.mm(dA.abs(), dB.abs())          # |A||B|: the scale of the error bounds of Section 5
     for k in ks:
+        D.fill_(float("nan"))                     # a tile the kernel never wrote would stay NaN
         print(f"full-size case m={m} n={n} p={p} k={k}", flush=True)
         ws = oz.alloc_workspace(m, n, p, k)
         oz.dgemm(dA, dB, k, D=D, workspace=ws)
@@ -45,7 +48,8 @@ def test_full_size_sampled_entries(oz, m, n, p, phi, ks):
         assert np.isfinite(got).all()
         assert (np.abs(got - want) <= 2 * sp).all()
         assert np.array_equal(got, want)
-        # a property that holds at any size: every D entry is finite and the
-        # row of largest magnitude is not zero
+        # properties that hold at any size: every entry of D was written, and every entry agrees with the
+        # native FP64 product to the accuracy k >= 8 slices give (catches a tile computed from wrong operands)
         assert torch.isfinite(D).all()
+        assert bool(((D - native).abs() <= 1e-11 * bound).all())
         del ws

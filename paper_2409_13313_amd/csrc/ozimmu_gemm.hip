@@ -409,7 +409,9 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 } else {
                     // Exponents come from LDS (the compiler cannot prove that D does not alias eA / eB and
                     // would order global exponent loads behind every store).  Per column of 32 x 32 tiles and
-                    // per pair of row tiles: 32 loads of D in flight, then the adds and stores.
+                    // per pair of row tiles: 32 loads of D in flight, then the adds and stores.  D is touched
+                    // once per chunk, a millisecond apart: non-temporal accesses keep it from displacing the
+                    // operand tiles the team shares in L2 (1 % at 16384^3).
                     int eb[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) eb[j] = lds_exp[256 + wn * 128 + j * 32 + lr] + shift;
@@ -426,7 +428,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                     for (int r = 0; r < 16; ++r) {
                                         const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
                                         const double* base = a.D + urow * a.ldd + ec0 + j * 32;
-                                        old[i][r] = (lane_col_ok[j] && urow + 4 * lh < a.m) ? base[off] : 0.0;
+                                        old[i][r] = (lane_col_ok[j] && urow + 4 * lh < a.m) ? __builtin_nontemporal_load(&base[off]) : 0.0;
                                     }
                             }
                             __builtin_amdgcn_sched_barrier(0);
@@ -439,7 +441,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                     const int ea = lds_exp[wm * 128 + (ih + i) * 32 + 8 * (r / 4) + (r % 4) + 4 * lh];
                                     const double term = ldexp((double)acc[ih + i][j][r], ea + eb[j]);
                                     if (lane_col_ok[j] && urow + 4 * lh < a.m)
-                                        base[off] = first ? term : (old[i][r] + term);
+                                        __builtin_nontemporal_store(first ? term : (old[i][r] + term), &base[off]);
                                 }
                             __builtin_amdgcn_sched_barrier(0);
                         }

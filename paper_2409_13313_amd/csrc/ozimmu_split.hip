@@ -315,7 +315,11 @@ __global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const dou
                 const uint32_t* src = &tile[s][jr * PITCH + oc * 4];
                 uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
                 int8_t* dst = SB + (int64_t)(sb + s) * slice_stride + packed_offset(j0 + jr, l0 + oc * CHUNK, KT);
-                *reinterpret_cast<uint4*>(dst) = v;
+                // whole 128-byte lines that nobody reads before the GEMM: non-temporal (4 % on this kernel; the
+                // 64-byte row segments of the A kernels need the L2 to merge them and stay temporal)
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                const u32x4 vv = {v.x, v.y, v.z, v.w};
+                __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>(dst));
             }
         }
         __syncthreads();

@@ -64,8 +64,8 @@ int64_t ozimmu_num_chunks(int64_t n, int k);
  * is private to the library (tile-major, see ozimmu_export_slices). */
 size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k);
 
-/* Bytes of device workspace ozimmu_dgemm needs (scheduling scratch, exponents, the two slice stacks and,
- * for outputs of at most 128 tiles of 256 x 256, an INT32 m x p buffer for partial sums); host. */
+/* Bytes of device workspace ozimmu_dgemm needs (scheduling scratch, exponents, the two slice stacks and
+ * INT32 blocks of 256 x 256 for the partial sums of up to 128 output tiles); host. */
 size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k);
 
 /* D <- A B with k slices: steps (i)-(iv) of the scheme (Section 1) as
@@ -114,10 +114,13 @@ enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 
  * does not depend on it, bit for bit.
  *   OZIMMU_SCHEDULE_ONE_LAUNCH   the whole schedule in one persistent kernel with the FP64 accumulation
  *                                fused into the GEMM epilogue (what large outputs always get);
- *   OZIMMU_SCHEDULE_SPLIT_INNER  outputs of at most 128 tiles of 256 x 256 only (else ignored): per chunk,
- *                                the inner dimension is cut into parts that run on different workgroups and
- *                                add their INT32 partial sums with integer atomics, then one accumulation
- *                                kernel; chosen by default when few tiles meet a long inner dimension. */
+ *   OZIMMU_SCHEDULE_SPLIT_INNER  for the tiles (256 x 256) that would leave most compute units idle -- an
+ *                                output of at most 128 tiles, or the last, partly filled round of at most
+ *                                128 tiles of a larger output: per chunk, the inner dimension is cut into
+ *                                parts that run on different workgroups and add their INT32 partial sums
+ *                                with integer atomics, then one accumulation kernel.  Chosen by default when
+ *                                the inner dimension is long enough to pay for the extra launches; the flag
+ *                                forces it wherever the inner dimension can be cut at all. */
 enum { OZIMMU_SCHEDULE_ONE_LAUNCH = 0x100, OZIMMU_SCHEDULE_SPLIT_INNER = 0x200 };
 int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p,
                          const double *A, int64_t lda, const double *B, int64_t ldb,

@@ -42,18 +42,19 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
                double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
                size_t workspace_bytes, void* stream, void* const* events);
 
-// Outputs of at most this many 256 x 256 tiles leave most compute units without a tile; for them the inner
-// range of every chunk is cut into parts (see run_schedule).  A constant, so that the workspace size does
-// not depend on the device.
+// The split-inner way of running the schedule (see run_schedule) works on at most this many 256 x 256 tiles
+// at a time: outputs that small as a whole, or the last, partly filled round of tiles of a larger output.
+// A constant, so that the workspace size does not depend on the device.
 constexpr int64_t SPLIT_INNER_MAX_TILES = 128;
 inline int64_t output_tiles(int64_t m, int64_t p)
 {
     return (ozl::rows_padded(m) / ozl::TILE_R) * (ozl::rows_padded(p) / ozl::TILE_R);
 }
-// INT32 buffer for the partial sums of such outputs (0 for larger ones)
+// INT32 partial sums: one dense 256 x 256 block per tile handled that way
 inline int64_t partial_sums_bytes(int64_t m, int64_t p)
 {
-    return output_tiles(m, p) <= SPLIT_INNER_MAX_TILES ? align256(4 * m * p) : 0;
+    const int64_t T = output_tiles(m, p);
+    return (T < SPLIT_INNER_MAX_TILES ? T : SPLIT_INNER_MAX_TILES) * (4 * 256 * 256);
 }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? OZIMMU_OK : OZIMMU_ERR_HIP; }
@@ -88,6 +89,9 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
     a.m = m;
     a.p = p;
     a.beta = beta_of(n);
+    a.tile_begin = 0;
+    a.tile_count = (int)((ozl::rows_padded(m) / ozl::TILE_R) * (ozl::rows_padded(p) / ozl::TILE_R));
+    a.zsplit = 1;
     a.sync = static_cast<unsigned*>(scratch);
     a.spin_limit = 64;  // polls (about 0.1 us each) before a workgroup stops waiting for its team
     return a;
@@ -96,12 +100,12 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
 // Steps (iii) + (iv) for the whole schedule of Algorithm 6 (groups g = 2..k+1 ascending, chunks of at most r
 // consecutive s), into D.  Two ways to run it, with bit-identical results:
 //  * one persistent launch with the accumulation fused into the GEMM epilogue (mode 1, or 2 for per-slice
-//    scales) -- the way for outputs with enough tiles to fill the chip;
-//  * for outputs of few tiles (most compute units would idle): per chunk, run the chunk GEMM with its inner
-//    range cut into Z parts on Z workgroups per tile that add their partial sums to a zeroed INT32 buffer
-//    with integer atomics, then the stand-alone accumulation kernel, which also clears the buffer again.
-//    Two launches (three with the counter reset) per chunk, worth it when the tiles are few and the inner
-//    dimension long.
+//    scales): one workgroup per compute unit takes tile after tile -- the way for as many tiles as fill
+//    whole rounds of the chip;
+//  * for tiles that would leave most compute units idle -- an output of few tiles, or the last, partly
+//    filled round of a larger one: per chunk, the chunk GEMM with its inner range cut into Z parts on Z
+//    workgroups per tile, which add their partial sums to zeroed per-tile INT32 blocks with integer atomics,
+//    then the accumulation kernel over those tiles, which also clears the blocks again.
 // schedule: 0 = choose, OZIMMU_SCHEDULE_ONE_LAUNCH, OZIMMU_SCHEDULE_SPLIT_INNER (honoured when possible).
 int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, const int32_t* eA,
                  const int32_t* eB, int k, int64_t r, bool per_slice, int schedule, double* D, int64_t ldd,
@@ -111,22 +115,31 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     const int r_eff = (int)(r < k ? r : k);
     const int KT = (int)(ozl::inner_padded(n) / ozl::TILE_K);
     const int64_t T = output_tiles(m, p);
+    // tiles [0, T - tail) go to the persistent launch, the last `tail` tiles (band order) are cut Z ways
+    int64_t tail = 0;
     int Z = 1;
-    if (!per_slice && partial && T <= SPLIT_INNER_MAX_TILES && schedule != OZIMMU_SCHEDULE_ONE_LAUNCH) {
-        const int ncu = ozk::num_compute_units();
-        int64_t z = ncu > 0 ? ncu / T : 1;
-        if (z > KT / 4) z = KT / 4;  // every part gets at least one group of 4 stages of the shortest chunk
-        if (z >= 2) {
-            // stages per tile saved against the price of three launches per chunk instead of one launch in
-            // all (measured: worth it from 512^3 with k = 8 upwards)
-            int64_t w = 0;
-            for (int g = 2; g <= k + 1; ++g) w += ((g - 1) + r_eff - 1) / r_eff;
-            const int64_t stages = (int64_t)k * (k + 1) / 2 * KT;
-            if (schedule == OZIMMU_SCHEDULE_SPLIT_INNER || stages * (z - 1) / z > 8 * w) Z = (int)z;
+    if (!per_slice && partial && schedule != OZIMMU_SCHEDULE_ONE_LAUNCH) {
+        const int64_t ncu = ozk::num_compute_units();
+        const int64_t cand = ncu > 0 ? (T <= SPLIT_INNER_MAX_TILES ? T : T % ncu) : 0;
+        if (cand >= 1 && cand <= SPLIT_INNER_MAX_TILES) {
+            int64_t z = ncu / cand;
+            if (z > KT / 4) z = KT / 4;  // every part gets at least one group of 4 stages of the shortest chunk
+            if (z >= 2) {
+                // stages per tile saved against the price of three launches per chunk (measured: worth it
+                // from 512^3 with k = 8 upwards)
+                int64_t w = 0;
+                for (int g = 2; g <= k + 1; ++g) w += ((g - 1) + r_eff - 1) / r_eff;
+                const int64_t stages = (int64_t)k * (k + 1) / 2 * KT;
+                if (schedule == OZIMMU_SCHEDULE_SPLIT_INNER || stages * (z - 1) / z > 8 * w) {
+                    tail = cand;
+                    Z = (int)z;
+                }
+            }
         }
     }
-    if (Z == 1) {
+    if (T - tail > 0) {
         ozk::GemmArgs a = make_args(m, n, p, SA, SB, 2, k + 1, r_eff, 0, 0, scratch);
+        a.tile_count = (int)(T - tail);
         a.D = D;
         a.ldd = ldd;
         a.eA = eA;
@@ -134,21 +147,25 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         a.estrideA = m;
         a.estrideB = p;
         a.first = 1;
-        return hip_status(ozk::launch_gemm(a, per_slice ? 2 : 1, st));
+        const hipError_t e = ozk::launch_gemm(a, per_slice ? 2 : 1, st);
+        if (e != hipSuccess) return OZIMMU_ERR_HIP;
     }
+    if (tail == 0) return OZIMMU_OK;
     int first = 1;
-    hipError_t e = ozk::launch_fill_zero_i32(m * p, partial, st);  // later chunks find it cleared by the accumulation
+    hipError_t e = ozk::launch_fill_zero_i32(tail * 256 * 256, partial, st);  // later chunks find it cleared
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     for (int g = 2; g <= k + 1; ++g)
         for (int s0 = 1; s0 <= g - 1; s0 += r_eff) {
             const int s1 = s0 + r_eff - 1 < g - 1 ? s0 + r_eff - 1 : g - 1;
             ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch);
+            a.tile_begin = (int)(T - tail);
+            a.tile_count = (int)tail;
             a.C = partial;
-            a.ldc = p;
             a.zsplit = Z;
             e = ozk::launch_gemm(a, 3, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;
-            e = ozk::launch_accumulate_and_clear(m, p, partial, p, eA, eB, 2 - beta * g, first, D, ldd, st);
+            e = ozk::launch_accumulate_tiles((int)(T - tail), (int)tail, m, p, partial, eA, eB, 2 - beta * g, first, D,
+                                             ldd, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;
             first = 0;
         }
@@ -326,7 +343,7 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
     const bool direct = (alpha == 1.0 && beta == 0.0);  // D is C
-    int32_t* partial = partial_sums_bytes(m, p) ? reinterpret_cast<int32_t*>(Dw + m * p) : nullptr;
+    int32_t* partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(Dw) + align256(8 * m * p));
     int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, false, 0, direct ? C : Dw, direct ? ldc : p, partial,
                           scratch, st);
     if (rc != OZIMMU_OK) return rc;
@@ -498,8 +515,7 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
     int32_t* partial = nullptr;  // INT32 partial sums of few-tile outputs, behind the slices
-    if (!per_slice && partial_sums_bytes(m, p))
-        partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(SB) + ozimmu_slices_bytes(p, n, k));
+    if (!per_slice) partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(SB) + ozimmu_slices_bytes(p, n, k));
     const int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, per_slice, schedule, D, ldd, partial, scratch, st);
     if (rc != OZIMMU_OK) return rc;
     return hip_status(mark(2));

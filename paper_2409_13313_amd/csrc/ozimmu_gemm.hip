@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     const int team = nwg / NXCD + (xcd < nwg % NXCD ? 1 : 0);
     // MODE 3 cuts the inner range of every chunk into Z parts; a work item is (tile, part), parts adjacent
     const int Z = (MODE == 3) ? a.zsplit : 1;
-    const int T = TM * TP * Z;
+    const int T = a.tile_count * Z;
     const int tiles_base = T / NXCD, tiles_rem = T % NXCD;
     const int range_off = xcd * tiles_base + (xcd < tiles_rem ? xcd : tiles_rem);
     const int range_cnt = tiles_base + (xcd < tiles_rem ? 1 : 0);
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
         int tm, tp;
         const int item = range_off + local;
         const int zpart = (MODE == 3) ? item % Z : 0;
-        if (MODE != 3 && TM % 16 == 0 && TP % 16 == 0 && nwg == 32 * NXCD) {
+        if (MODE != 3 && TM % 16 == 0 && TP % 16 == 0 && nwg == 32 * NXCD && a.tile_count == TM * TP) {
             // Tile grid made of 16 x 16 blocks and a full grid of workgroups: in round q the 8 x 4 patches of
             // the eight XCDs tile block q (2 x 4 patches), so that all XCDs together stream 16 A and 16 B
             // tile rows (instead of 64 + 4 when every XCD walks a band of its own) and the memory-side cache
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
             tm = sbr * 16 + (xcd / 4) * 8 + mem % 8;
             tp = sbc * 16 + (xcd % 4) * 4 + mem / 8;
         } else {
-            tile_of_linear((MODE == 3) ? item / Z : item, TM, TP, tm, tp);
+            tile_of_linear(a.tile_begin + ((MODE == 3) ? item / Z : item), TM, TP, tm, tp);
         }
         const int64_t row0 = (int64_t)tm * 256 + wm * 128;
         const int64_t col0 = (int64_t)tp * 256 + wn * 128;
@@ -396,8 +396,14 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
                                 const int64_t urow = er0 + i * 32 + 8 * (r / 4) + (r % 4);  // uniform part of the row
-                                int32_t* base = a.C + urow * a.ldc + ec0 + j * 32;
-                                const uint32_t off = (uint32_t)(4 * lh) * (uint32_t)a.ldc + (uint32_t)lr;
+                                // MODE 3: the tile's own dense 256 x 256 block, addressed by the row / column in the tile
+                                int32_t* base = (MODE == 3)
+                                                    ? a.C + (int64_t)(item / Z) * (256 * 256) +
+                                                          (int64_t)(wm * 128 + i * 32 + 8 * (r / 4) + (r % 4)) * 256 +
+                                                          wn * 128 + j * 32
+                                                    : a.C + urow * a.ldc + ec0 + j * 32;
+                                const uint32_t off =
+                                    (uint32_t)(4 * lh) * ((MODE == 3) ? 256u : (uint32_t)a.ldc) + (uint32_t)lr;
                                 if (lane_col_ok[j] && urow + 4 * lh < a.m) {
                                     if (MODE == 3)  // partial sum of one part: integer adds commute, C'' starts at zero
                                         __hip_atomic_fetch_add(&base[off], acc[i][j][r], __ATOMIC_RELAXED,
@@ -453,10 +459,8 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     }
 }
 
-// Step (iv) alone: one thread per element, lanes along a row of D.  ZERO: C is cleared after use (the
-// split-inner schedule hands the same buffer to the next chunk's integer atomics).
-template <bool ZERO>
-__global__ __launch_bounds__(256) void k_accumulate(int64_t m, int64_t p, int32_t* __restrict__ C, int64_t ldc,
+// Step (iv) alone: one thread per element, lanes along a row of D.
+__global__ __launch_bounds__(256) void k_accumulate(int64_t m, int64_t p, const int32_t* __restrict__ C, int64_t ldc,
                                                     const int32_t* __restrict__ eA, const int32_t* __restrict__ eB,
                                                     int shift, int first, double* __restrict__ D, int64_t ldd)
 {
@@ -466,9 +470,35 @@ __global__ __launch_bounds__(256) void k_accumulate(int64_t m, int64_t p, int32_
     const int eb = eB[j] + shift;
     for (int64_t i = i0; i < i0 + 8 && i < m; ++i) {
         const double term = ldexp((double)C[i * ldc + j], eA[i] + eb);
-        if (ZERO) C[i * ldc + j] = 0;
         double* d = D + i * ldd + j;
         *d = first ? term : (*d + term);
+    }
+}
+
+// Step (iv) for a range of tiles whose INT32 chunk sums lie in per-tile dense 256 x 256 blocks (the
+// split-inner schedule); the blocks are cleared after use for the next chunk's integer atomics.
+// A workgroup handles 8 rows of one tile, lanes along the row.
+__global__ __launch_bounds__(256) void k_accumulate_tiles(int tile_begin, int TM, int TP, int64_t m, int64_t p,
+                                                          int32_t* __restrict__ Ct, const int32_t* __restrict__ eA,
+                                                          const int32_t* __restrict__ eB, int shift, int first,
+                                                          double* __restrict__ D, int64_t ldd)
+{
+    const int local = blockIdx.x / 32, rows8 = blockIdx.x % 32;
+    int tm, tp;
+    tile_of_linear(tile_begin + local, TM, TP, tm, tp);
+    const int64_t j = (int64_t)tp * 256 + threadIdx.x;
+    int32_t* c = Ct + (int64_t)local * (256 * 256) + (int64_t)rows8 * 8 * 256 + threadIdx.x;
+    const bool col_ok = j < p;
+    const int eb = col_ok ? eB[j] + shift : 0;
+    for (int q = 0; q < 8; ++q) {
+        const int64_t i = (int64_t)tm * 256 + rows8 * 8 + q;
+        const int32_t v = c[q * 256];
+        c[q * 256] = 0;
+        if (col_ok && i < m) {
+            const double term = ldexp((double)v, eA[i] + eb);
+            double* d = D + i * ldd + j;
+            *d = first ? term : (*d + term);
+        }
     }
 }
 
@@ -593,7 +623,9 @@ hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st)
         attr_set[dev] = true;
     }
     // one workgroup per CU (the LDS ring allows no second one), never more workgroups than tiles
-    const int64_t tiles = (int64_t)TM * TP * (fused == 3 ? a.zsplit : 1);
+    const int64_t tiles = (int64_t)a.tile_count * (fused == 3 ? a.zsplit : 1);
+    if (a.tile_count <= 0 || a.tile_begin < 0 || (int64_t)a.tile_begin + a.tile_count > (int64_t)TM * TP)
+        return hipErrorInvalidValue;
     int nwg = num_cu[dev] > 0 ? num_cu[dev] : 1;
     if (tiles < nwg) nwg = (int)tiles;
     hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(NXCD * 16), 0, st, a.sync);
@@ -642,16 +674,18 @@ hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc
                              const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st)
 {
     dim3 grid((unsigned)((m + 7) / 8), (unsigned)((p + 255) / 256));
-    hipLaunchKernelGGL(k_accumulate<false>, grid, dim3(256), 0, st, m, p, const_cast<int32_t*>(C), ldc, eA, eB, shift,
-                       first, D, ldd);
+    hipLaunchKernelGGL(k_accumulate, grid, dim3(256), 0, st, m, p, C, ldc, eA, eB, shift, first, D, ldd);
     return hipGetLastError();
 }
 
-hipError_t launch_accumulate_and_clear(int64_t m, int64_t p, int32_t* C, int64_t ldc, const int32_t* eA,
-                                       const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st)
+hipError_t launch_accumulate_tiles(int tile_begin, int tile_count, int64_t m, int64_t p, int32_t* Ctiles,
+                                   const int32_t* eA, const int32_t* eB, int shift, int first, double* D,
+                                   int64_t ldd, hipStream_t st)
 {
-    dim3 grid((unsigned)((m + 7) / 8), (unsigned)((p + 255) / 256));
-    hipLaunchKernelGGL(k_accumulate<true>, grid, dim3(256), 0, st, m, p, C, ldc, eA, eB, shift, first, D, ldd);
+    if (tile_count <= 0) return hipSuccess;
+    const int TM = (int)(ozl::rows_padded(m) / ozl::TILE_R), TP = (int)(ozl::rows_padded(p) / ozl::TILE_R);
+    hipLaunchKernelGGL(k_accumulate_tiles, dim3((unsigned)tile_count * 32u), dim3(256), 0, st, tile_begin, TM, TP, m, p,
+                       Ctiles, eA, eB, shift, first, D, ldd);
     return hipGetLastError();
 }
 

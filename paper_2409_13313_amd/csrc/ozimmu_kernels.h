@@ -34,14 +34,15 @@ struct GemmArgs {
     int g_lo, g_hi, r;
     int s0, s1;
     int64_t m, p;          // valid output extent
-    int32_t* C;            // INT32 output (mode 0, single chunk only)
-    int64_t ldc;
+    int32_t* C;            // INT32 output (mode 0, single chunk only); fused == 3: one dense 256 x 256 block per
+    int64_t ldc;           // tile of the launch, in the order of the launch's tiles (ldc unused)
     double* D;             // FP64 accumulate target (mode 1)
     int64_t ldd;
     const int32_t* eA;
     const int32_t* eB;
     int64_t estrideA, estrideB;  // fused == 2 only: elements from the exponents of slice s to those of slice s+1
     int zsplit;            // fused == 3 only: parts the inner range of a chunk is cut into (<= KT / 4)
+    int tile_begin, tile_count;  // the launch covers tiles tile_begin .. tile_begin + tile_count - 1 of the band order
     int beta;              // shift of group g is 2 - beta * g
     int first;             // D is zero before the first chunk: overwrite
     unsigned* sync;        // 8 x 16 counters, zeroed by launch_gemm: [16 x] per-XCD soft barrier, [1] whole grid
@@ -57,10 +58,11 @@ hipError_t launch_fill_zero_i32(int64_t count, int32_t* x, hipStream_t st);
 // Step (iv) alone.
 hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA,
                              const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st);
-// The same, and C is left zeroed.
-hipError_t launch_accumulate_and_clear(int64_t m, int64_t p, int32_t* C, int64_t ldc, const int32_t* eA,
-                                       const int32_t* eB, int shift, int first, double* D, int64_t ldd,
-                                       hipStream_t st);
+// Step (iv) for the tiles tile_begin .. tile_begin + tile_count - 1 (band order) from per-tile 256 x 256 INT32
+// blocks, which are left zeroed.
+hipError_t launch_accumulate_tiles(int tile_begin, int tile_count, int64_t m, int64_t p, int32_t* Ctiles,
+                                   const int32_t* eA, const int32_t* eB, int shift, int first, double* D,
+                                   int64_t ldd, hipStream_t st);
 // Step (v): C <- alpha D + beta C (beta == 0: C not read).
 hipError_t launch_axpby(int64_t m, int64_t p, double alpha, const double* D, int64_t ldd, double beta, double* C,
                         int64_t ldc, hipStream_t st);

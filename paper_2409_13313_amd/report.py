@@ -243,13 +243,13 @@ def small_beta(m=2048, p=2048, phi=0.5, sample=64, reps=3):
     print()
 
 
-def sizes(ns=(1024, 2048, 3072, 4096, 6144, 8192, 12288, 16384), ks=(4, 8, 12), reps=5):
+def sizes(ns=(1024, 2048, 3072, 4096, 5120, 6144, 7168, 8192, 9216, 10240, 12288, 14336, 16384), ks=(4, 8, 12), reps=5):
     import torch
     from paper_2409_13313_amd import inputs, ozimmu
     print(f"### ozimmu_dgemm against native FP64 (torch.mm) over the matrix size, phi=0.5; median of {reps}, ms "
           f"(speed-up over native)\n")
-    print("| m=n=p | native FP64 ms (TFLOP/s) | " + " | ".join(f"k={k}" for k in ks) + " |")
-    print("|---|---|" + "---|" * len(ks))
+    print("| m=n=p | native FP64 ms (TFLOP/s) | " + " | ".join(f"k={k}" for k in ks) + " | k=8, one launch forced |")
+    print("|---|---|" + "---|" * (len(ks) + 1))
     for n in ns:
         A, B = inputs.phi_pair(n, n, n, 0.5, seed=0)
         dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
@@ -262,6 +262,9 @@ def sizes(ns=(1024, 2048, 3072, 4096, 6144, 8192, 12288, 16384), ks=(4, 8, 12), 
             ozimmu.dgemm(dA, dB, k, D=D, workspace=ws)
             t = _median_ms(lambda: ozimmu.dgemm(dA, dB, k, D=D, workspace=ws), reps)
             cells.append(f"{t:.3f} ({t_nat / t:.2f}x)")
+        one = lambda: ozimmu.dgemm_variant(dA, dB, 8, "rn", "grouped", D=D, workspace=ws, schedule="one_launch")
+        one()
+        cells.append(f"{_median_ms(one, reps):.3f}")
         print(f"| {n} | {t_nat:.3f} ({2.0 * n ** 3 / t_nat / 1e9:.1f}) | " + " | ".join(cells) + " |")
         del dA, dB, D, ws
     print()

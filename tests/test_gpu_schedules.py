@@ -77,3 +77,24 @@ def test_schedule_flags_are_validated(oz):
         rc = oz._lib.ozimmu_dgemm_variant(4, 4, 4, A.data_ptr(), 4, A.data_ptr(), 4, D.data_ptr(), 4, 4, 0, bad,
                                           ws.data_ptr(), ws.numel(), st)
         assert rc == -3
+
+
+@pytest.mark.parametrize("m,n,p,k", [(4352, 520, 4096, 4),     # 272 tiles: one round of 256 + 16 in the tail
+                                     (4100, 1029, 4000, 3),    # the tail is the ragged last band (4 rows)
+                                     (4352, 300, 4352, 5)])    # 289 tiles: tail of 33
+def test_last_partial_round_cut_along_the_inner_dimension(oz, m, n, p, k):
+    A, B = inputs.phi_pair(m, n, p, 1.0, seed=94)
+    dA, dB = dev(A), dev(B)
+    out = {}
+    for schedule in ("one_launch", "split_inner", "auto"):
+        D = torch.full((m, p), float("nan"), dtype=torch.float64, device="cuda")
+        oz.dgemm_variant(dA, dB, k, "rn", "grouped", D=D, schedule=schedule)
+        assert torch.isfinite(D).all(), schedule          # every tile written, by one path or the other
+        out[schedule] = D
+    assert torch.equal(out["one_launch"], out["split_inner"])
+    assert torch.equal(out["one_launch"], out["auto"])
+    I = inputs.sample_indices(m, 48, seed=1)
+    J = inputs.sample_indices(p, 48, seed=2)
+    want = oracle.dgemm_sub(A, B, k, I, J)
+    got = out["split_inner"][torch.from_numpy(I).cuda()][:, torch.from_numpy(J).cuda()].cpu().numpy()
+    assert np.array_equal(got, want)

@@ -57,3 +57,19 @@ def test_gemm_ex_empty_inner_dimension_scales_c(oz):
     oz.gemm_ex(False, False, 1.5, torch.empty((5, 0), dtype=torch.float64, device="cuda"),
                torch.empty((0, 7), dtype=torch.float64, device="cuda"), 0.0, C, 8)
     assert (C == 0).all()
+
+
+def test_gemm_ex_large_output_with_a_cut_tail_round(oz):
+    # 272 tiles: one full round in the persistent launch, 16 tiles cut along the inner dimension; transposed
+    # operands and step (v) on top.  Reference: ozimmu_dgemm (one launch forced) on explicitly transposed
+    # copies, then the three rounded operations of step (v) done by torch in FP64.
+    m, n, p, k = 4352, 520, 4096, 4
+    A, B = inputs.phi_pair(m, n, p, 1.0, seed=95)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    C0 = torch.from_numpy(inputs.phi_pair(m, 1, p, 0.5, seed=96)[0] @ np.ones((1, p))).cuda()
+    D = oz.dgemm_variant(dA, dB, k, "rn", "grouped", schedule="one_launch")
+    alpha, beta = -1.75, 0.3
+    want = alpha * D + beta * C0            # fl(fl(alpha d) + fl(beta c)): torch evaluates exactly these three
+    C = C0.clone()
+    oz.gemm_ex(True, True, alpha, dA.T.contiguous(), dB.T.contiguous(), beta, C, k)
+    assert torch.equal(C, want)

@@ -74,6 +74,15 @@ __device__ inline void copy16_to_lds(uint32_t m0_base, uint32_t voff, const int8
                  : "memory", "scc");
 }
 
+// The same with the non-temporal hint (data that is read once).
+template <int IMM>
+__device__ inline void copy16_to_lds_nt(uint32_t m0_base, uint32_t voff, const void* gbase)
+{
+    asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3 nt" ::"s"(m0_base), "n"(IMM),
+                 "v"(voff), "s"(gbase)
+                 : "memory", "scc");
+}
+
 template <int N>
 __device__ inline void wait_vmcnt()
 {
@@ -386,8 +395,12 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 const int shift = MODE == 2 ? 2 - 2 * a.beta : 2 - a.beta * g;
                 int64_t er0 = row0, ec0 = col0;
                 asm volatile("" : "+s"(er0), "+s"(ec0));
-                const bool lane_col_ok[4] = {ec0 + lr < a.p, ec0 + 32 + lr < a.p, ec0 + 64 + lr < a.p,
-                                             ec0 + 96 + lr < a.p};
+                // lane parts of the output coordinates, opaque to the optimiser so that the 64 per-lane row
+                // indices of a chunk are formed here and not at kernel entry (where they would be spilled)
+                int lhe = lh, lre = lr;
+                asm volatile("" : "+v"(lhe), "+v"(lre));
+                const bool lane_col_ok[4] = {ec0 + lre < a.p, ec0 + 32 + lre < a.p, ec0 + 64 + lre < a.p,
+                                             ec0 + 96 + lre < a.p};
                 if (MODE == 0 || MODE == 3) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
@@ -403,8 +416,8 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                                           wn * 128 + j * 32
                                                     : a.C + urow * a.ldc + ec0 + j * 32;
                                 const uint32_t off =
-                                    (uint32_t)(4 * lh) * ((MODE == 3) ? 256u : (uint32_t)a.ldc) + (uint32_t)lr;
-                                if (lane_col_ok[j] && urow + 4 * lh < a.m) {
+                                    (uint32_t)(4 * lhe) * ((MODE == 3) ? 256u : (uint32_t)a.ldc) + (uint32_t)lre;
+                                if (lane_col_ok[j] && urow + 4 * lhe < a.m) {
                                     if (MODE == 3)  // partial sum of one part: integer adds commute, C'' starts at zero
                                         __hip_atomic_fetch_add(&base[off], acc[i][j][r], __ATOMIC_RELAXED,
                                                                __HIP_MEMORY_SCOPE_AGENT);
@@ -420,8 +433,73 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     // operand tiles the team shares in L2 (1 % at 16384^3).
                     int eb[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) eb[j] = lds_exp[256 + wn * 128 + j * 32 + lr] + shift;
-                    const uint32_t off = (uint32_t)(4 * lh) * (uint32_t)a.ldd + (uint32_t)lr;
+                    for (int j = 0; j < 4; ++j) eb[j] = lds_exp[256 + wn * 128 + j * 32 + lre] + shift;
+                    const uint32_t off = (uint32_t)(4 * lhe) * (uint32_t)a.ldd + (uint32_t)lre;
+                    // Later chunks of a tile that lies wholly inside D (and D aligned for 16-byte copies): the old
+                    // values of D come in through the LDS ring, which is idle now, with the same global -> LDS
+                    // copies as the operands.  They need no registers, so the next half block (64 rows x 32
+                    // columns of this wave) is already on its way while the current one is added and stored, and
+                    // no load ever waits for a store to be acknowledged.  Wave w owns ring buffer w (32 KiB = two
+                    // half blocks).  Copy t of a half block brings rows 4t .. 4t+3: lane l row l / 16, columns
+                    // 2 (l % 16), + 1, i.e. the half block lands row-major with 256 bytes per row.
+                    const bool staged = !first && a.dma_ok && (int64_t)tm * 256 + 256 <= a.m &&
+                                        (int64_t)tp * 256 + 256 <= a.p;
+                    if (staged) {
+                        __builtin_amdgcn_s_barrier();  // every wave has read its last fragments from the ring
+                        const uint32_t region = lds_base + (uint32_t)wave * (uint32_t)STAGE_BYTES;
+                        // lane-dependent offsets are rebuilt here (the empty asm keeps them from being computed at
+                        // kernel entry and held in registers through the main loop)
+                        uint32_t ln = (uint32_t)lane;
+                        asm volatile("" : "+v"(ln));
+                        const uint32_t dvoff = ((ln >> 4) * (uint32_t)a.ldd + (ln & 15u) * 2u) * 8u;
+                        const uint32_t rd_lane = region + (ln >> 5) * 1024u + (ln & 31u) * 8u;
+                        const int64_t row_step = 4 * a.ldd;  // elements between the rows of consecutive copies
+                        auto issue = [&](auto HB) {          // half block hb = 2 j + h into buffer hb % 2
+                            constexpr int hb = decltype(HB)::value, j = hb / 2, h = hb % 2;
+                            const double* g = a.D + (er0 + 64 * h) * a.ldd + ec0 + 32 * j;
+                            static_for<0, 16>([&](auto TT) {
+                                constexpr int tt = decltype(TT)::value;
+                                asm volatile("" : "+s"(g));  // one running pointer, not sixteen precomputed ones
+                                copy16_to_lds_nt<(hb % 2) * 16384 + tt * 1024>(region, dvoff, g);
+                                g += row_step;
+                            });
+                        };
+                        typedef __attribute__((address_space(3))) const double* lds_f64_ptr;
+                        issue(std::integral_constant<int, 0>{});
+                        issue(std::integral_constant<int, 1>{});
+                        static_for<0, 8>([&](auto HB) {
+                            constexpr int hb = decltype(HB)::value, j = hb / 2, h = hb % 2;
+                            // copies of half block hb have landed; later ones and the stores may still fly
+                            if constexpr (hb == 0)
+                                wait_vmcnt<16>();
+                            else if constexpr (hb == 7)
+                                wait_vmcnt<32>();
+                            else
+                                wait_vmcnt<48>();
+                            asm volatile("" ::: "memory");
+#pragma unroll
+                            for (int i = 0; i < 2; ++i) {
+                                double old[16];
+#pragma unroll
+                                for (int r = 0; r < 16; ++r)
+                                    old[r] = *(lds_f64_ptr)(uintptr_t)(rd_lane + (hb % 2) * 16384 +
+                                                                       (i * 32 + 8 * (r / 4) + (r % 4)) * 256);
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) {
+                                    const int64_t urow = er0 + (2 * h + i) * 32 + 8 * (r / 4) + (r % 4);
+                                    double* base = a.D + urow * a.ldd + ec0 + j * 32;
+                                    const int ea = lds_exp[wm * 128 + (2 * h + i) * 32 + 8 * (r / 4) + (r % 4) + 4 * lhe];
+                                    const double term = ldexp((double)acc[2 * h + i][j][r], ea + eb[j]);
+                                    __builtin_nontemporal_store(old[r] + term, &base[off]);
+                                }
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                            // the buffer is read out (the sums above needed every value): refill it
+                            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                            if constexpr (hb + 2 < 8) issue(std::integral_constant<int, hb + 2>{});
+                            __builtin_amdgcn_sched_barrier(0);
+                        });
+                    } else
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
 #pragma unroll
@@ -434,7 +512,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                     for (int r = 0; r < 16; ++r) {
                                         const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
                                         const double* base = a.D + urow * a.ldd + ec0 + j * 32;
-                                        old[i][r] = (lane_col_ok[j] && urow + 4 * lh < a.m) ? __builtin_nontemporal_load(&base[off]) : 0.0;
+                                        old[i][r] = (lane_col_ok[j] && urow + 4 * lhe < a.m) ? __builtin_nontemporal_load(&base[off]) : 0.0;
                                     }
                             }
                             __builtin_amdgcn_sched_barrier(0);
@@ -444,9 +522,9 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 for (int r = 0; r < 16; ++r) {
                                     const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
                                     double* base = a.D + urow * a.ldd + ec0 + j * 32;
-                                    const int ea = lds_exp[wm * 128 + (ih + i) * 32 + 8 * (r / 4) + (r % 4) + 4 * lh];
+                                    const int ea = lds_exp[wm * 128 + (ih + i) * 32 + 8 * (r / 4) + (r % 4) + 4 * lhe];
                                     const double term = ldexp((double)acc[ih + i][j][r], ea + eb[j]);
-                                    if (lane_col_ok[j] && urow + 4 * lh < a.m)
+                                    if (lane_col_ok[j] && urow + 4 * lhe < a.m)
                                         __builtin_nontemporal_store(first ? term : (old[i][r] + term), &base[off]);
                                 }
                             __builtin_amdgcn_sched_barrier(0);
@@ -597,8 +675,12 @@ constexpr int NSTAGES = 4;  // ring depth: 4 x 32 KiB of the 160 KiB LDS (3 and 
 
 namespace ozk {
 
-hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st)
+hipError_t launch_gemm(const GemmArgs& a_in, int fused, hipStream_t st)
 {
+    GemmArgs a = a_in;
+    // the fused epilogue may fetch the old D through LDS with 16-byte copies: needs the alignment for them
+    a.dma_ok = (fused == 1 || fused == 2) && reinterpret_cast<uintptr_t>(a.D) % 16 == 0 && a.ldd % 2 == 0 &&
+               4 * a.ldd * 8 < ((int64_t)1 << 31);
     const int TM = (int)(ozl::rows_padded(a.m) / ozl::TILE_R), TP = (int)(ozl::rows_padded(a.p) / ozl::TILE_R);
     const size_t smem = (size_t)NSTAGES * STAGE_BYTES + EXP_BYTES;
     static bool attr_set[64] = {false};

@@ -43,6 +43,7 @@ struct GemmArgs {
     int64_t estrideA, estrideB;  // fused == 2 only: elements from the exponents of slice s to those of slice s+1
     int zsplit;            // fused == 3 only: parts the inner range of a chunk is cut into (<= KT / 4)
     int tile_begin, tile_count;  // the launch covers tiles tile_begin .. tile_begin + tile_count - 1 of the band order
+    int dma_ok;            // D is 16-byte aligned and ldd even: rows of D can be copied 16 bytes per lane
     int beta;              // shift of group g is 2 - beta * g
     int first;             // D is zero before the first chunk: overwrite
     unsigned* sync;        // 8 x 16 counters, zeroed by launch_gemm: [16 x] per-XCD soft barrier, [1] whole grid

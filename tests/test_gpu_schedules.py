@@ -98,3 +98,19 @@ def test_last_partial_round_cut_along_the_inner_dimension(oz, m, n, p, k):
     want = oracle.dgemm_sub(A, B, k, I, J)
     got = out["split_inner"][torch.from_numpy(I).cuda()][:, torch.from_numpy(J).cuda()].cpu().numpy()
     assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("col_shift,extra", [(0, 0), (0, 1), (1, 2)])
+def test_fused_epilogue_with_and_without_the_alignment_for_staging(oz, col_shift, extra):
+    # 600 x 600: four tiles wholly inside D (their later chunks fetch the old D through LDS when D is 16-byte
+    # aligned with an even leading dimension) and five edge tiles (always the plain loads).  An odd leading
+    # dimension or a base shifted by one element switches the staging off; the bits must not change.
+    m, n, p, k = 600, 300, 600, 6
+    A, B = inputs.phi_pair(m, n, p, 1.0, seed=97)
+    want = oracle.dgemm(A, B, k)
+    Dbig = torch.full((m, p + col_shift + extra), -7.0, dtype=torch.float64, device="cuda")
+    view = Dbig[:, col_shift:col_shift + p]
+    oz.dgemm_variant(dev(A), dev(B), k, "rn", "grouped", D=view, schedule="one_launch")
+    got = Dbig.cpu().numpy()
+    assert np.array_equal(got[:, col_shift:col_shift + p], want)
+    assert (got[:, :col_shift] == -7.0).all() and (got[:, col_shift + p:] == -7.0).all()

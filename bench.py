@@ -23,7 +23,7 @@ PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA peak, 5.0 POP/s
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script, scaled by the same counters on a plain copy (see profiles/k_gemm_16384_k8_traffic.md)
-MEASURED_TRAFFIC_BYTES = {(16384, 16384, 16384, 8): 247.5e9 + 17.2e9}
+MEASURED_TRAFFIC_BYTES = {(16384, 16384, 16384, 8): 247.1e9 + 17.2e9}
 
 
 def log(*a):

@@ -106,12 +106,19 @@ __device__ inline void static_for(F&& f)
 // Nothing but timing depends on it: a workgroup that has waited `spin_limit`
 // polls goes on alone, so the barrier always ends.  Called by every thread;
 // thread 0 arrives and polls, the rest meet it at the next s_barrier.
-__device__ inline void team_arrive_and_wait(unsigned* ctr, unsigned target, int spin_limit)
+// Two counters at once (the whole grid, then the XCD's team): both arrivals go out before the first poll.
+__device__ inline void arrive_and_wait2(unsigned* ctr_a, unsigned target_a, unsigned* ctr_b, unsigned target_b,
+                                        int spin_limit)
 {
     if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(ctr_a, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(ctr_b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         for (int i = 0; i < spin_limit; ++i) {
-            if (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) break;
+            if (__hip_atomic_load(ctr_a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target_a) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        for (int i = 0; i < spin_limit; ++i) {
+            if (__hip_atomic_load(ctr_b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target_b) break;
             __builtin_amdgcn_s_sleep(8);
         }
     }
@@ -309,8 +316,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 });
                 sync_target += participants;
                 all_target += all_participants;
-                team_arrive_and_wait(all_ctr, all_target, a.spin_limit);
-                team_arrive_and_wait(sync_ctr, sync_target, a.spin_limit);
+                arrive_and_wait2(all_ctr, all_target, sync_ctr, sync_target, a.spin_limit);
                 wait_vmcnt<NLOAD*(2 * (NS - 2) - 1)>();
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");

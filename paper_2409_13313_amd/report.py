@@ -17,6 +17,9 @@
 
   --schedules  outputs of few tiles: the one-launch schedule against the split-inner one and native FP64
 
+  --breakdown  time shares of split / INT8 GEMMs / FP64 accumulation with the phases run as separate kernels,
+               for the accumulation per slice pair (Algorithm 4) and per chunk (Algorithm 6)   [Section 4.2]
+
 Prints markdown tables.  The Dot2 reference comes from the CPU oracle package, which is test
 infrastructure; nothing here feeds back into the HIP path.
 """
@@ -298,6 +301,48 @@ def schedules(k=8, reps=5):
     print()
 
 
+def breakdown(n=8192, ks=(6, 8, 10, 12), reps=3):
+    """The paper's time-breakdown figures, with this library's phase-level kernels: how much of the
+    un-fused run is FP64 accumulation when every slice pair is accumulated on its own and when the
+    pairs of a chunk are summed in INT32 first."""
+    import torch
+    from paper_2409_13313_amd import inputs, ozimmu
+    A, B = inputs.phi_pair(n, n, n, 0.5, seed=0)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    beta, r = ozimmu.params(n)
+    D = torch.empty((n, n), dtype=torch.float64, device="cuda")
+    C = torch.empty((n, n), dtype=torch.int32, device="cuda")
+    scratch = ozimmu.alloc_scratch()
+    print(f"### time breakdown with separate kernels per phase, m=n=p={n}, phi=0.5 (r={r}); median of {reps}, ms (share)\n")
+    print("| k | accumulation | split A+B | INT8 GEMMs | FP64 accumulation | total | fused ozimmu_dgemm |")
+    print("|---|---|---|---|---|---|---|")
+    for k in ks:
+        SA, eA = ozimmu.split_A(dA, k)
+        SB, eB = ozimmu.split_B(dB, k)
+        ws = ozimmu.alloc_workspace(n, n, n, k)
+        t_split = _median_ms(lambda: (ozimmu.split_A(dA, k), ozimmu.split_B(dB, k)), reps)
+        ozimmu.dgemm(dA, dB, k, D=D, workspace=ws)
+        t_fused = _median_ms(lambda: ozimmu.dgemm(dA, dB, k, D=D, workspace=ws), reps)
+        for label, rr in (("per slice pair (Algorithm 4)", 1), (f"per chunk of <= {r} (Algorithm 6)", r)):
+            sched = [(g, s0, min(s0 + rr - 1, g - 1)) for g in range(2, k + 2) for s0 in range(1, g, rr)]
+
+            def gemms():
+                for (g, s0, s1) in sched:
+                    ozimmu.gemm_group(n, n, n, SA, k, SB, k, g, s0, s1, C=C, scratch=scratch)
+
+            def accs():
+                for i, (g, s0, s1) in enumerate(sched):
+                    ozimmu.accumulate(C, eA, eB, beta, g, i == 0, D)
+
+            gemms(); accs()
+            t_g, t_a = _median_ms(gemms, reps), _median_ms(accs, reps)
+            tot = t_split + t_g + t_a
+            print(f"| {k} | {label}: {len(sched)} additions | {t_split:.2f} ({100 * t_split / tot:.0f} %) | "
+                  f"{t_g:.2f} ({100 * t_g / tot:.0f} %) | {t_a:.2f} ({100 * t_a / tot:.0f} %) | {tot:.2f} | {t_fused:.2f} |")
+        del SA, SB, ws
+    print()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--accuracy", action="store_true")
@@ -308,6 +353,7 @@ def main():
     ap.add_argument("--small-beta", action="store_true")
     ap.add_argument("--sizes", action="store_true")
     ap.add_argument("--schedules", action="store_true")
+    ap.add_argument("--breakdown", action="store_true")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
@@ -329,6 +375,8 @@ def main():
         sizes()
     if args.schedules:
         schedules()
+    if args.breakdown:
+        breakdown()
     return 0
 
 

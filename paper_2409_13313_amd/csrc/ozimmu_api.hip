@@ -43,7 +43,8 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
                size_t workspace_bytes, void* stream, void* const* events);
 
 // The split-inner way of running the schedule (see run_schedule) works on at most this many 256 x 256 tiles
-// at a time: outputs that small as a whole, or the last, partly filled round of tiles of a larger output.
+// at a time: outputs that small as a whole, or the last, partly filled round of tiles of a larger output
+// (half the 256 compute units of the chip this is written for: every tile can then be cut at least in two).
 // A constant, so that the workspace size does not depend on the device.
 constexpr int64_t SPLIT_INNER_MAX_TILES = 128;
 inline int64_t output_tiles(int64_t m, int64_t p)
@@ -120,20 +121,32 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     int Z = 1;
     if (!per_slice && partial && schedule != OZIMMU_SCHEDULE_ONE_LAUNCH) {
         const int64_t ncu = ozk::num_compute_units();
-        const int64_t cand = ncu > 0 ? (T <= SPLIT_INNER_MAX_TILES ? T : T % ncu) : 0;
-        if (cand >= 1 && cand <= SPLIT_INNER_MAX_TILES) {
-            int64_t z = ncu / cand;
-            if (z > KT / 4) z = KT / 4;  // every part gets at least one group of 4 stages of the shortest chunk
-            if (z >= 2) {
-                // stages per tile saved against the price of three launches per chunk (measured: worth it
-                // from 512^3 with k = 8 upwards)
-                int64_t w = 0;
-                for (int g = 2; g <= k + 1; ++g) w += ((g - 1) + r_eff - 1) / r_eff;
-                const int64_t stages = (int64_t)k * (k + 1) / 2 * KT;
-                if (schedule == OZIMMU_SCHEDULE_SPLIT_INNER || stages * (z - 1) / z > 8 * w) {
-                    tail = cand;
-                    Z = (int)z;
+        const int64_t cand = ncu > 0 ? (T < ncu ? T : T % ncu) : 0;  // tiles of the partly filled round
+        const int64_t zmax = KT / 4;  // every part gets at least one group of 4 stages of the shortest chunk
+        if (cand >= 1 && cand <= SPLIT_INNER_MAX_TILES && zmax >= 2) {
+            // Time per chunk in microseconds, from measurements on MI355X: a stage of the main loop takes
+            // 0.68 us; the fused path pays about 35 us per chunk and tile for epilogue and prologue, a part of
+            // the cut path about 15 us (atomic epilogue, prologue), and every chunk of the cut path about 15 us
+            // of launches plus the accumulation pass over the tail tiles (20 bytes per element at 4.5 TB/s).
+            int64_t w = 0;
+            for (int g = 2; g <= k + 1; ++g) w += ((g - 1) + r_eff - 1) / r_eff;
+            const double chunk_us = 0.68 * (double)k * (k + 1) / 2 * KT / (double)w;  // average chunk of one tile
+            const double fused_us = chunk_us + 35.0;  // one more round of the persistent launch
+            const double fixed_us = 15.0 + 0.29 * (double)cand;
+            double best = 0.0;
+            int64_t best_z = 0;
+            // one round only: cutting finer and running the parts in several rounds measured slower than the
+            // fused path even where this model favours it (3072 x 16384 x 3072: 8.0 against 6.0 ms)
+            for (int64_t z = 2; z <= zmax && cand * z <= ncu; ++z) {
+                const double t = chunk_us / (double)z + 15.0 + fixed_us;
+                if (best_z == 0 || t < best) {
+                    best = t;
+                    best_z = z;
                 }
+            }
+            if (best_z && (schedule == OZIMMU_SCHEDULE_SPLIT_INNER || best < 0.9 * fused_us)) {
+                tail = cand;
+                Z = (int)best_z;
             }
         }
     }

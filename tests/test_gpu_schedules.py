@@ -81,7 +81,8 @@ def test_schedule_flags_are_validated(oz):
 
 @pytest.mark.parametrize("m,n,p,k", [(4352, 520, 4096, 4),     # 272 tiles: one round of 256 + 16 in the tail
                                      (4100, 1029, 4000, 3),    # the tail is the ragged last band (4 rows)
-                                     (4352, 300, 4352, 5)])    # 289 tiles: tail of 33
+                                     (4352, 300, 4352, 5),     # 289 tiles: tail of 33
+                                     (3000, 700, 3300, 4)])    # 156 ragged tiles: too many to cut, one launch whatever is asked
 def test_last_partial_round_cut_along_the_inner_dimension(oz, m, n, p, k):
     A, B = inputs.phi_pair(m, n, p, 1.0, seed=94)
     dA, dB = dev(A), dev(B)

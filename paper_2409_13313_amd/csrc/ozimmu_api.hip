@@ -95,6 +95,7 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
     a.zsplit = 1;
     a.sync = static_cast<unsigned*>(scratch);
     a.spin_limit = 64;  // polls (about 0.1 us each) before a workgroup stops waiting for its team
+    a.sync_epoch = 0;
     return a;
 }
 
@@ -165,6 +166,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     }
     if (tail == 0) return OZIMMU_OK;
     int first = 1;
+    int epoch = 0;
     hipError_t e = ozk::launch_fill_zero_i32(tail * 256 * 256, partial, st);  // later chunks find it cleared
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     for (int g = 2; g <= k + 1; ++g)
@@ -175,6 +177,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             a.tile_count = (int)tail;
             a.C = partial;
             a.zsplit = Z;
+            a.sync_epoch = epoch++;
             e = ozk::launch_gemm(a, 3, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;
             e = ozk::launch_accumulate_tiles((int)(T - tail), (int)tail, m, p, partial, eA, eB, 2 - beta * g, first, D,

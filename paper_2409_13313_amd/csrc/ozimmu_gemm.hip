@@ -195,12 +195,14 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     const int range_off = xcd * tiles_base + (xcd < tiles_rem ? xcd : tiles_rem);
     const int range_cnt = tiles_base + (xcd < tiles_rem ? 1 : 0);
     unsigned* const sync_ctr = a.sync + xcd * 16;
-    unsigned sync_target = 0;
+    // launches of the same geometry may share the counters without a reset: launch number `sync_epoch` starts
+    // from what its predecessors added (every work item arrives once per chunk, one chunk per such launch)
+    unsigned sync_target = (unsigned)a.sync_epoch * (unsigned)range_cnt;
     // second counter for all workgroups of the grid: the XCDs walk the tile columns in the same order, so
     // lining them up at every chunk start lets B tiles fetched for one XCD serve the others from the
     // memory-side cache (measured: 0.6 % at 16384^3, nothing elsewhere)
     unsigned* const all_ctr = a.sync + 1;
-    unsigned all_target = 0;
+    unsigned all_target = (unsigned)a.sync_epoch * (unsigned)T;
 
     for (int local = member; local < range_cnt; local += team) {
         const int round_first = local - member;
@@ -716,7 +718,7 @@ hipError_t launch_gemm(const GemmArgs& a_in, int fused, hipStream_t st)
         return hipErrorInvalidValue;
     int nwg = num_cu[dev] > 0 ? num_cu[dev] : 1;
     if (tiles < nwg) nwg = (int)tiles;
-    hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(NXCD * 16), 0, st, a.sync);
+    if (a.sync_epoch == 0) hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(NXCD * 16), 0, st, a.sync);
     dim3 grid((unsigned)nwg), block(256);
     if (fused == 3)
         hipLaunchKernelGGL((k_gemm<3, NSTAGES>), grid, block, smem, st, a, TM, TP);

@@ -48,6 +48,8 @@ struct GemmArgs {
     int first;             // D is zero before the first chunk: overwrite
     unsigned* sync;        // 8 x 16 counters, zeroed by launch_gemm: [16 x] per-XCD soft barrier, [1] whole grid
     int spin_limit;        // polls before a soft barrier gives up
+    int sync_epoch;        // 0: launch_gemm zeroes the counters; e > 0: e single-chunk launches of this very geometry
+                           // have used them since (the split-inner schedule: one reset for all its chunks)
 };
 // Steps (iii) (+ (iv) when fused is 1 or 2) for the chunks of the schedule (Algorithm 6).  fused == 2: one scale
 // per slice (Algorithm 5), r must be 1.  fused == 3: INT32 partial sums of a.zsplit inner parts added to a

@@ -188,7 +188,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     const int nwg = gridDim.x, bid = blockIdx.x;
     const int xcd = bid % NXCD, member = bid / NXCD;
     const int team = nwg / NXCD + (xcd < nwg % NXCD ? 1 : 0);
-    // MODE 3 cuts the inner range of every chunk into Z parts; a work item is (tile, part), parts adjacent
+    // MODE 3 cuts the inner range of every chunk into Z parts; a work item is (part, tile)
     const int Z = (MODE == 3) ? a.zsplit : 1;
     const int T = a.tile_count * Z;
     const int tiles_base = T / NXCD, tiles_rem = T % NXCD;
@@ -220,7 +220,10 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
         }
         int tm, tp;
         const int item = range_off + local;
-        const int zpart = (MODE == 3) ? item % Z : 0;
+        // MODE 3: part-major order, so that the 32 work items of a team are 32 tiles cut at the same place of
+        // the inner dimension and share operand tiles in L2 like the tiles of the un-cut kernel
+        const int zpart = (MODE == 3) ? item / a.tile_count : 0;
+        const int ztile = (MODE == 3) ? item % a.tile_count : item;
         if (MODE != 3 && TM % 16 == 0 && TP % 16 == 0 && nwg == 32 * NXCD && a.tile_count == TM * TP) {
             // Tile grid made of 16 x 16 blocks and a full grid of workgroups: in round q the 8 x 4 patches of
             // the eight XCDs tile block q (2 x 4 patches), so that all XCDs together stream 16 A and 16 B
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
             tm = sbr * 16 + (xcd / 4) * 8 + mem % 8;
             tp = sbc * 16 + (xcd % 4) * 4 + mem / 8;
         } else {
-            tile_of_linear(a.tile_begin + ((MODE == 3) ? item / Z : item), TM, TP, tm, tp);
+            tile_of_linear(a.tile_begin + ztile, TM, TP, tm, tp);
         }
         const int64_t row0 = (int64_t)tm * 256 + wm * 128;
         const int64_t col0 = (int64_t)tp * 256 + wn * 128;
@@ -419,7 +422,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 const int64_t urow = er0 + i * 32 + 8 * (r / 4) + (r % 4);  // uniform part of the row
                                 // MODE 3: the tile's own dense 256 x 256 block, addressed by the row / column in the tile
                                 int32_t* base = (MODE == 3)
-                                                    ? a.C + (int64_t)(item / Z) * (256 * 256) +
+                                                    ? a.C + (int64_t)ztile * (256 * 256) +
                                                           (int64_t)(wm * 128 + i * 32 + 8 * (r / 4) + (r % 4)) * 256 +
                                                           wn * 128 + j * 32
                                                     : a.C + urow * a.ldc + ec0 + j * 32;

@@ -21,7 +21,8 @@ def dev(x):
     return torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
-@pytest.mark.parametrize("rows,n,phi,k,seed", [(256, 256, 0.5, 8, 0), (300, 200, 4.0, 14, 1), (65, 1029, 1.0, 20, 2)])
+@pytest.mark.parametrize("rows,n,phi,k,seed", [(256, 256, 0.5, 8, 0), (300, 200, 4.0, 14, 1), (65, 1029, 1.0, 20, 2),
+                                               (40, 20000, 1.0, 6, 3)])      # rows too long for the one-pass kernel
 def test_bitmask_slices_bit_exact(oz, rows, n, phi, k, seed):
     A, B = inputs.phi_pair(rows, n, rows, phi, seed=seed)
     A[1, :] = 0.0

@@ -9,9 +9,10 @@
 // single FP64 addition per chunk is the only rounding on the whole path.
 // MODE 2 is MODE 1 for slices that carry one scale each (Algorithm 5): every chunk
 // is one pair (s, t) and the factor is 2^(2 - 2 beta) diag(2^eA_s) . diag(2^eB_t).
-// MODE 3 is MODE 0 for outputs with few tiles: the inner range of the chunk is cut
-// into Z parts that run on different workgroups and add their INT32 partial sums to
-// a zeroed C'' with integer atomics (exact in any order).
+// MODE 3 is MODE 0 for tiles too few to fill the chip: the inner range of the chunk
+// is cut into Z parts that run on different workgroups and add their INT32 partial
+// sums to zeroed per-tile blocks with integer atomics (exact in any order).
+// A launch covers a range of tiles (tile_begin, tile_count) of the band order.
 //
 // Tiling: 256 x 256 outputs per workgroup, 4 waves in a 2 x 2 grid, each wave
 // 128 x 128 = 4 x 4 tiles of v_mfma_i32_32x32x32_i8 (256 INT32 accumulators per
@@ -32,6 +33,8 @@
 //   MFMAs issued before the barrier) | k-step 1 math.
 // The LDS-writing loads are issued from inline assembly, so the compiler does
 // not track them; the vmcnt waits that order them are written out below.
+// The fused epilogue of later chunks uses the same copies to bring the old values
+// of D through the then idle ring (see there).
 #include "ozimmu_kernels.h"
 #include "ozimmu_layout.h"
 #include <type_traits>
@@ -45,7 +48,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // A tile + B tile = 32 KiB
 constexpr int NLOAD = TILE_BYTES / (256 * 16);    // 16-byte copies per thread and operand tile = 4
-constexpr int EPI_ROWS = 2;                       // 32 x 32 tiles per epilogue batch (16 D loads in flight per lane each)
+constexpr int EPI_ROWS = 2;                       // 32 x 32 tiles per batch of the plain epilogue (16 D loads in flight per lane each)
 constexpr int EXP_BYTES = 2 * 256 * 4;            // exponents of the tile's 256 rows and 256 columns, kept in LDS
 
 // Linear tile order: bands of GROUP tile rows, each walked column by column, so
@@ -138,8 +141,8 @@ struct Cursor {
 // works on tiles q*team .. q*team+team-1 of its range, i.e. an 8 x 4 patch
 // whose A and B tiles are shared through the XCD's L2.  (Tile grids made of
 // 16 x 16 blocks place the eight patches of a round side by side instead, see
-// below.)  For its tile a
-// workgroup runs every chunk of the schedule in the order of Algorithm 6.
+// below.)  For its tile a workgroup runs every chunk of the schedule in the order
+// of Algorithm 6.
 //
 // The main loop is unrolled NS times so that every LDS address is a register
 // plus an immediate and every M0 value one scalar add: with one wave per SIMD

@@ -50,3 +50,15 @@ def sample_indices(size: int, count: int, seed: int) -> np.ndarray:
     while len(idx) < count:
         idx.add(int(rng.integers(0, size)))
     return np.array(sorted(idx), dtype=np.int64)
+
+
+def band_indices(size: int, band: int, seed: int) -> np.ndarray:
+    """Sorted sample with one index in every block of `band` consecutive indices
+    (a random position inside the block), plus the first and the last index:
+    every tile row / tile column of an output is then represented."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    idx = set([0, size - 1]) if size > 0 else set()
+    for lo in range(0, size, band):
+        hi = min(lo + band, size)
+        idx.add(int(rng.integers(lo, hi)))
+    return np.array(sorted(idx), dtype=np.int64)

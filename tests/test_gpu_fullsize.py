@@ -20,9 +20,10 @@ def oz():
 
 
 FULL = [
-    (8192, 8192, 8192, 0.5, [8]),                 # config 3
-    (16384, 16384, 16384, 0.5, [8, 14]),          # config 4 (headline)
-    (16384, 16384, 16384, 4.0, [12]),             # config 4, wide exponent range
+    (4096, 4096, 4096, 0.0, [3, 8, 12]),          # Section 4.3 workload (throughput against accuracy, phi = 0)
+    (8192, 8192, 8192, 0.5, [6, 8, 10]),          # config 3
+    (16384, 16384, 16384, 0.5, [8, 12, 14]),      # config 4 (headline)
+    (16384, 16384, 16384, 4.0, [8, 12, 14]),      # config 4, wide exponent range
     (4096, 65536, 4096, 1.0, [10]),               # config 5: r = 2, 30 chunks
 ]
 
@@ -32,8 +33,10 @@ def test_full_size_sampled_entries(oz, m, n, p, phi, ks):
     A, B = inputs.phi_pair(m, n, p, phi, seed=0)
     dA = torch.from_numpy(A).cuda()
     dB = torch.from_numpy(B).cuda()
-    I = inputs.sample_indices(m, 40, seed=1)
-    J = inputs.sample_indices(p, 40, seed=2)
+    # one row in every band of 256 rows and one column in every band of 256 columns (every tile row and
+    # tile column of the kernel's 256 x 256 output tiles), plus the first and last row / column
+    I = inputs.band_indices(m, 256, seed=1)
+    J = inputs.band_indices(p, 256, seed=2)
     D = torch.empty((m, p), dtype=torch.float64, device="cuda")
     native = torch.mm(dA, dB)
     bound = torch.mm(dA.abs(), dB.abs())          # |A||B|: the scale of the error bounds of Section 5
@@ -51,5 +54,6 @@ def test_full_size_sampled_entries(oz, m, n, p, phi, ks):
         # properties that hold at any size: every entry of D was written, and every entry agrees with the
         # native FP64 product to the accuracy k >= 8 slices give (catches a tile computed from wrong operands)
         assert torch.isfinite(D).all()
-        assert bool(((D - native).abs() <= 1e-11 * bound).all())
+        tol = max(1e-11, 2.0 ** (12 - 7 * k))    # few slices: the truncation error of k slices of 7 bits dominates
+        assert bool(((D - native).abs() <= tol * bound).all())
         del ws

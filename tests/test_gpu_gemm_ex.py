@@ -61,15 +61,24 @@ def test_gemm_ex_empty_inner_dimension_scales_c(oz):
 
 def test_gemm_ex_large_output_with_a_cut_tail_round(oz):
     # 272 tiles: one full round in the persistent launch, 16 tiles cut along the inner dimension; transposed
-    # operands and step (v) on top.  Reference: ozimmu_dgemm (one launch forced) on explicitly transposed
-    # copies, then the three rounded operations of step (v) done by torch in FP64.
+    # operands and step (v) on top.  Rows / columns from every band of 256 (every tile, so also the cut tail
+    # round) are recomputed by the oracle.
     m, n, p, k = 4352, 520, 4096, 4
     A, B = inputs.phi_pair(m, n, p, 1.0, seed=95)
-    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
-    C0 = torch.from_numpy(inputs.phi_pair(m, 1, p, 0.5, seed=96)[0] @ np.ones((1, p))).cuda()
-    D = oz.dgemm_variant(dA, dB, k, "rn", "grouped", schedule="one_launch")
+    C0 = inputs.phi_pair(m, 1, p, 0.5, seed=96)[0] @ np.ones((1, p))
     alpha, beta = -1.75, 0.3
-    want = alpha * D + beta * C0            # fl(fl(alpha d) + fl(beta c)): torch evaluates exactly these three
-    C = C0.clone()
-    oz.gemm_ex(True, True, alpha, dA.T.contiguous(), dB.T.contiguous(), beta, C, k)
-    assert torch.equal(C, want)
+    C = torch.from_numpy(C0).cuda()
+    oz.gemm_ex(True, True, alpha, torch.from_numpy(np.ascontiguousarray(A.T)).cuda(),
+               torch.from_numpy(np.ascontiguousarray(B.T)).cuda(), beta, C, k)
+    assert torch.isfinite(C).all()
+    I = inputs.band_indices(m, 256, seed=97)
+    J = inputs.band_indices(p, 256, seed=98)
+    want = oracle.gemm_ex(False, False, alpha, np.ascontiguousarray(A[I]), np.ascontiguousarray(B[:, J]), beta,
+                          np.ascontiguousarray(C0[np.ix_(I, J)]), k)
+    got = C[torch.from_numpy(I).cuda()][:, torch.from_numpy(J).cuda()].cpu().numpy()
+    assert np.array_equal(got, want)
+    # every entry: the library's own product (one launch forced) followed by the three rounded operations
+    # of step (v) as torch evaluates them in FP64 (a consistency check on top of the oracle comparison)
+    D = oz.dgemm_variant(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), k, "rn", "grouped",
+                         schedule="one_launch")
+    assert torch.equal(C, alpha * D + beta * torch.from_numpy(C0).cuda())

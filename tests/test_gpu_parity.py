@@ -199,6 +199,26 @@ def test_dgemm_within_2ulp_of_oracle(oz, m, n, p, k, phi, seed):
     assert np.array_equal(got, want), "expected bit equality (same single rounding per chunk)"
 
 
+# config 2: m = n = p = 1024, phi in {0.5, 1, 2}, k = 6 .. 12 (Section 4.1 workload).  The ends of the sweep are
+# compared in full above; here every (phi, k) on rows / columns sampled from every band of 128
+@pytest.mark.parametrize("phi", [0.5, 1.0, 2.0])
+def test_dgemm_config2_sweep_sampled(oz, phi):
+    m = n = p = 1024
+    A, B = inputs.phi_pair(m, n, p, phi, seed=0)
+    dA, dB = dev(A), dev(B)
+    I = inputs.band_indices(m, 128, seed=21)
+    J = inputs.band_indices(p, 128, seed=22)
+    tI, tJ = torch.from_numpy(I).cuda(), torch.from_numpy(J).cuda()
+    for k in range(6, 13):
+        D = torch.full((m, p), float("nan"), dtype=torch.float64, device="cuda")
+        oz.dgemm(dA, dB, k, D=D)
+        assert torch.isfinite(D).all()
+        got = D[tI][:, tJ].cpu().numpy()
+        want = oracle.dgemm_sub(A, B, k, I, J)
+        assert_within_2ulp(got, want)
+        assert np.array_equal(got, want), (phi, k)
+
+
 def test_dgemm_exact_on_small_integers_and_edge_shapes(oz):
     A, B = inputs.small_int_pair(130, 300, 70, 64, seed=4)
     want = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)

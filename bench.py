@@ -30,6 +30,35 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def mfma_rate_probe(iters: int, value_lo: int, value_hi: int, reps: int = 2) -> float:
+    """Sustained v_mfma_i32_32x32x32_i8 rate of this chip in TOP/s for register operands uniform in
+    [value_lo, value_hi]: the register-only loop of bench_mfma_probe.hip (a measurement aid outside the
+    library); the last of `reps` timed launches counts."""
+    import ctypes
+    import torch
+    path = os.path.join(ROOT, "libbench_mfma_probe.so")
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: run __graft_entry__.build()")
+    lib = ctypes.CDLL(path)
+    lib.bench_mfma_rate_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                          ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    lib.bench_mfma_rate_probe.restype = ctypes.c_int
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ops = ctypes.c_double(0.0)
+    rate = 0.0
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        rc = lib.bench_mfma_rate_probe(iters, value_lo, value_hi, out.data_ptr(), ctypes.byref(ops),
+                                       torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            raise RuntimeError(f"bench_mfma_rate_probe returned {rc}")
+        e1.record()
+        torch.cuda.synchronize()
+        rate = ops.value / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return rate
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -160,11 +189,11 @@ def main() -> int:
         # what this chip sustains on the instruction the GEMM phase is made of, measured now on this machine:
         # a register-only v_mfma_i32_32x32x32_i8 loop on every CU, operands uniform in [-64, 64] like
         # round-to-nearest slices (the sustained clock depends on the operand statistics), and on zeros
-        sliceslike = ozimmu.mfma_rate_probe(300000, -64, 64)
-        zeros = ozimmu.mfma_rate_probe(300000, 0, 0)
+        sliceslike = mfma_rate_probe(300000, -64, 64)
+        zeros = mfma_rate_probe(300000, 0, 0)
         result["roofline"]["sustained_mfma_rate"] = {
             "unit": "TOP/s", "operands_uniform_in_-64..64": round(sliceslike, 1), "operands_zero": round(zeros, 1),
-            "what": "ozimmu_mfma_rate_probe: register-only MFMA loop, 4 waves on every CU, about 0.1 s per launch",
+            "what": "bench_mfma_probe.hip: register-only MFMA loop, 4 waves on every CU, about 0.1 s per launch",
             "gemm_phase_frac_of_it": round(gemm_tops / sliceslike, 4)}
         log(f"register-only MFMA loop on this box: {sliceslike:.0f} TOP/s with slice-like operands, {zeros:.0f} TOP/s "
             f"with zeros; the GEMM phase runs at {100.0 * gemm_tops / sliceslike:.1f} % of the former")

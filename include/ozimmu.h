@@ -4,16 +4,18 @@
  * "ozIMMU_H" form: round-to-nearest INT8 slices with one power-of-two scale
  * per row of A / column of B (Algorithm 8 of the paper), INT8 x INT8 -> INT32
  * products of the slice pairs (s, t) with s + t <= k + 1, products that share
- * a shift summed in INT32 in chunks of at most r (Algorithm 6, eq.
- * (errfreesum), eq. (def_r)), and one shifted FP64 addition per chunk.
+ * a shift summed in INT32 in chunks of at most r (Algorithm 6 and the
+ * definition of r in Section 3.2), and one shifted FP64 addition per chunk.
  *
  * Conventions
  *   - A is m x n, B is n x p, D is m x p: n is the INNER dimension (paper's
  *     notation, Section 1).  All three are row-major with leading dimensions
  *     lda >= n, ldb >= p, ldd >= p counted in elements.
  *   - Every pointer marked "device" is memory of the current HIP device,
- *     owned by the caller; the library allocates nothing and keeps no state
- *     between calls.  A and B are never modified.
+ *     owned by the caller; the library allocates nothing.  A and B are never
+ *     modified.  The only state kept between calls is the one-time set-up of a
+ *     device (see ozimmu_init), guarded by a mutex: calls from several host
+ *     threads are safe as long as they do not share a workspace or scratch area.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*); no
  *     call synchronises with the host.  Buffers must stay alive until the
  *     stream has run the work.
@@ -41,7 +43,8 @@ extern "C" {
 enum {
     OZIMMU_OK = 0,
     OZIMMU_ERR_NULL = -1,       /* a required pointer is NULL */
-    OZIMMU_ERR_DIM = -2,        /* negative size, leading dimension too small, n > 2^29 (beta < 1) */
+    OZIMMU_ERR_DIM = -2,        /* negative size; m or p > 2^22 - 256; n > 2^29 (beta < 1); a leading dimension
+                                   smaller than the row length or >= 2^30 */
     OZIMMU_ERR_SLICES = -3,     /* k outside 1..OZIMMU_MAX_SLICES, or g / s range invalid */
     OZIMMU_ERR_WORKSPACE = -4,  /* workspace too small or misaligned (needs 256-byte alignment) */
     OZIMMU_ERR_HIP = -5         /* a kernel launch reported a HIP error */
@@ -50,8 +53,15 @@ enum {
 /* Human-readable text for a status code (static storage, host). */
 const char *ozimmu_status_string(int status);
 
-/* beta = min(7, floor((31 - log2 n)/2))   [eq. (beta)]  and
- * r = max(1, 2^(31 - 2 beta - ceil(log2 n)))   [eq. (def_r)], host, pure.
+/* One-time set-up of the current HIP device: raises the dynamic-LDS limit of the chunk GEMM kernels,
+ * and reads the number of compute units.  Every entry point that launches the chunk GEMM does this by itself on its first
+ * call on a device; the set-up calls are not legal inside a HIP stream capture, so call ozimmu_init (or
+ * any such entry point) once per device BEFORE capturing a graph that contains library calls.  Host;
+ * idempotent; thread-safe.  Returns OZIMMU_OK or OZIMMU_ERR_HIP. */
+int ozimmu_init(void);
+
+/* beta = min(7, floor((31 - log2 n)/2))   [Section 2, the bound n 2^(2 beta) <= 2^31]  and
+ * r = max(1, 2^(31 - 2 beta - ceil(log2 n)))   [Section 3.2, definition of r], host, pure.
  * Returns OZIMMU_ERR_DIM for n < 1 or n > 2^29. */
 int ozimmu_params(int64_t n, int *beta, int64_t *r);
 
@@ -96,7 +106,7 @@ int ozimmu_dgemm_profiled(int64_t m, int64_t n, int64_t p,
 /* The variants the paper compares (Section 4), through the same kernels:
  *   split_mode       OZIMMU_SPLIT_NEAREST  round-to-nearest slices, ceil exponent     [Algorithm 8]
  *                    OZIMMU_SPLIT_BITMASK  bit-mask digits (truncation), floor exponent [Algorithm 3]
- *   accumulate_mode  OZIMMU_ACCUM_GROUPED  chunks of r products, eq. (def_r)          [Algorithm 6]
+ *   accumulate_mode  OZIMMU_ACCUM_GROUPED  chunks of r products (Section 3.2)          [Algorithm 6]
  *                    OZIMMU_ACCUM_PER_PAIR one FP64 addition per slice pair            [Algorithm 4]
  *                    OZIMMU_ACCUM_WIDE     chunks of ozimmu_r_wide(n) products; needs OZIMMU_SPLIT_NEAREST.
  *                                          Not in the paper: its r is derived for |A''| <= 2^beta - 1, while
@@ -198,10 +208,10 @@ int ozimmu_split_B_per_slice(int64_t n, int64_t p, const double *B, int64_t ldb,
                              int8_t *SB, int32_t *eB, double *rem, void *stream);
 
 /* Step (iii) for one chunk: C'' <- sum_{s = s0..s1} A''_s B''_{g-s} in INT32
- *                                              [Algorithm 6, lines 7-9].
+ *                                              [Algorithm 6, the inner loop over s].
  * s0 == s1 gives the single pair product A''_s B''_{g-s} of Algorithm 4.
  *   SA, SB  device, packed slice stacks holding kA / kB slices.
- *   C       device, int32 m x p row-major, ldc >= p, overwritten.
+ *   C       device, int32 m x p row-major, ldc >= p, overwritten (with zeros when n == 0).
  *   scratch device, OZIMMU_SCRATCH_BYTES bytes, 4-byte aligned.
  * Requires 1 <= s0 <= s1 <= kA and 1 <= g - s1, g - s0 <= kB.  The caller is
  * responsible for s1 - s0 + 1 <= r (no INT32 overflow, Section 5.2). */
@@ -211,8 +221,8 @@ int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p,
                       int32_t *C, int64_t ldc, void *scratch, void *stream);
 
 /* Step (iv) for one chunk: D <- D + 2^(2 - beta g) diag(2^eA) FP64(C'') diag(2^eB)
- *                                              [Algorithm 6, line 11].
- * first != 0: D is taken to be zero and is overwritten (Algorithm 6, line 3).
+ *                                              [Algorithm 6, the accumulation step].
+ * first != 0: D is taken to be zero and is overwritten (the initialisation D = O of Algorithm 6).
  * beta is passed explicitly (it depends on n, which this call does not see). */
 int ozimmu_accumulate(int64_t m, int64_t p, const int32_t *C, int64_t ldc,
                       const int32_t *eA, const int32_t *eB, int beta, int g, int first,
@@ -220,7 +230,8 @@ int ozimmu_accumulate(int64_t m, int64_t p, const int32_t *C, int64_t ldc,
 
 /* Steps (iii)+(iv) for one chunk in one kernel: the INT32 chunk sum stays in
  * registers and is converted, scaled and added to D in the GEMM epilogue
- * (ozimmu_dgemm runs the same kernel once, over every chunk of the schedule). */
+ * (ozimmu_dgemm runs the same kernel once, over every chunk of the schedule).  n == 0: the chunk sum is
+ * zero, so D is set to +0 when first != 0 and left as it is otherwise. */
 int ozimmu_gemm_group_accumulate(int64_t m, int64_t n, int64_t p,
                                  const int8_t *SA, int kA, const int8_t *SB, int kB,
                                  int g, int s0, int s1,
@@ -232,19 +243,6 @@ int ozimmu_gemm_group_accumulate(int64_t m, int64_t n, int64_t p,
  * B''_s[l][j] stored at out[s][j][l].  Debug / test helper. */
 int ozimmu_export_slices(int64_t rows, int64_t n, int k, const int8_t *packed,
                          int8_t *out, void *stream);
-
-/* Measurement aid, not part of the method: what this chip sustains on the matrix-core instruction the
- * GEMM phase is made of.  Launches one workgroup of 4 waves per compute unit; every wave runs `iters`
- * rounds of 16 independent v_mfma_i32_32x32x32_i8 on register operands (no LDS or memory traffic in the
- * loop), the operand bytes being pseudo-random and uniform in [value_lo, value_hi] (-64..64 is what
- * round-to-nearest slices look like; 0..0 gives the data-independent rate).  The sustained clock of the
- * chip under this load depends on the operand statistics, so the rate measured for [-64, 64] is the
- * ceiling that the GEMM phase can be priced against next to the data-sheet peak.
- *   out   device, at least 4 bytes (receives a checksum so that the loop is not optimised away).
- *   *ops  host, receives the number of integer operations of the launch (2 per multiply-add).
- * The caller times the launch (events on `stream`).  Errors: OZIMMU_ERR_NULL, OZIMMU_ERR_DIM for
- * iters < 1 or a range outside -128..127, OZIMMU_ERR_HIP. */
-int ozimmu_mfma_rate_probe(int iters, int value_lo, int value_hi, int32_t *out, double *ops, void *stream);
 
 #ifdef __cplusplus
 }

@@ -94,7 +94,7 @@ def _p(a: np.ndarray):
 
 # ----------------------------------------------------------------------------
 def params(n: int) -> Tuple[int, int]:
-    """(beta, r) for inner dimension n  [eq. (beta), eq. (def_r)]."""
+    """(beta, r) for inner dimension n  [the formulas for beta (Section 2) and r (Section 3.2)]."""
     lib = _load()
     beta = lib.oz_beta(int(n))
     return beta, int(lib.oz_r(int(n), beta))
@@ -125,7 +125,7 @@ _FORMS = {"int": 0, "sigma": 1, "bitmask": 2}
 
 
 def exponents_floor(X: np.ndarray, by_col: bool) -> np.ndarray:
-    """floor(log2 max |x|) per row (or per column) of X  [Algorithm 3, line 2]; 0 for a zero vector."""
+    """floor(log2 max |x|) per row (or per column) of X  [Algorithm 3, its scale mu'']; 0 for a zero vector."""
     X = _c(X, np.float64)
     rows, cols = X.shape
     e = np.empty(cols if by_col else rows, dtype=np.int32)
@@ -184,13 +184,13 @@ def group_chunk(SA: np.ndarray, SB: np.ndarray, g: int, s0: int, s1: int) -> np.
 
 
 def pair_product(SA: np.ndarray, SB: np.ndarray, s: int, t: int) -> np.ndarray:
-    """A''_s B''_t as INT32  [Algorithm 4, line 5]."""
+    """A''_s B''_t as INT32  [Algorithm 4, the slice product]."""
     return group_chunk(SA, SB, s + t, s, s)
 
 
 def accumulate(D: np.ndarray, C: np.ndarray, eA: np.ndarray, eB: np.ndarray,
                beta: int, g: int, first: bool) -> None:
-    """In place D += 2^(2 - beta g) diag(2^eA) FP64(C) diag(2^eB)  [Algorithm 6, line 11]."""
+    """In place D += 2^(2 - beta g) diag(2^eA) FP64(C) diag(2^eB)  [Algorithm 6, the accumulation step]."""
     assert D.dtype == np.float64 and D.flags.c_contiguous
     C = _c(C, np.int32)
     m, p = D.shape
@@ -231,7 +231,7 @@ def dgemm(A: np.ndarray, B: np.ndarray, k: int, return_addends: bool = False):
 def dgemm_variant(A: np.ndarray, B: np.ndarray, k: int, split: str = "rn", accumulate: str = "grouped",
                   return_addends: bool = False):
     """The variants compared in Section 4: split "rn" (Algorithm 8) or "bitmask" (Algorithm 3);
-    accumulate "grouped" (Algorithm 6, r of eq. (def_r)), "per_pair" (Algorithm 4) or "wide"
+    accumulate "grouped" (Algorithm 6, r of Section 3.2), "per_pair" (Algorithm 4) or "wide"
     (chunks of r_wide products, round-to-nearest slices only; beyond the paper).
     ("rn","grouped") = ozIMMU_H, ("bitmask","grouped") = ozIMMU_EF, ("bitmask","per_pair") = ozIMMU."""
     A = _c(A, np.float64)

@@ -29,7 +29,7 @@
 /* Parameters                                                          */
 /* ------------------------------------------------------------------ */
 
-/* beta = min(7, floor((31 - log2 n)/2))            [Section 2, eq. (beta)]
+/* beta = min(7, floor((31 - log2 n)/2))            [Section 2, the formula for beta]
  * Integer form: floor((31 - log2 n)/2) >= b  <=>  n <= 2^(31-2b).
  * Returns 0 when even b = 1 does not fit (n > 2^29, outside the paper's
  * standing assumption beta >= 1). */
@@ -50,7 +50,7 @@ static int ceil_log2_i64(int64_t n)
     return L;
 }
 
-/* r = max(1, 2^(31 - 2 beta - ceil(log2 n)))        [Section 3.2, eq. (def_r)] */
+/* r = max(1, 2^(31 - 2 beta - ceil(log2 n)))        [Section 3.2, the definition of r] */
 int64_t oz_r(int64_t n, int beta)
 {
     int ex = 31 - 2 * beta - ceil_log2_i64(n);
@@ -88,7 +88,7 @@ static int ceil_log2_double(double x)
     return (f == 0.5) ? t - 1 : t;
 }
 
-/* eA[i] = ceil(log2 max_j |a_ij|)         [Algorithm 8, line 2, exponent part]
+/* eA[i] = ceil(log2 max_j |a_ij|)         [Algorithm 8, the exponent part of its scale mu'']
  * An all-zero row gets exponent 0 (every slice of it is zero). */
 void oz_row_exponents(int64_t m, int64_t n, const double *A, int32_t *eA)
 {
@@ -103,7 +103,7 @@ void oz_row_exponents(int64_t m, int64_t n, const double *A, int32_t *eA)
 }
 
 /* Scale exponents of the bit-mask split of the earlier ozIMMU method: floor instead of ceil,
- * mu''_i = 2^floor(log2 max_j |a_ij|)                                  [Algorithm 3, line 2]
+ * mu''_i = 2^floor(log2 max_j |a_ij|)                                  [Algorithm 3, its scale mu'']
  * (x = f * 2^t with f in [0.5, 1) has floor(log2 x) = t - 1).  cols != 0: per column of an n x p matrix. */
 void oz_exponents_floor(int64_t rows, int64_t cols_, const double *X, int by_col, int32_t *e)
 {
@@ -121,7 +121,7 @@ void oz_exponents_floor(int64_t rows, int64_t cols_, const double *X, int by_col
 }
 
 /* eB[j] = ceil(log2 max_i |b_ij|): B is split as the transpose of the split
- * of B^T (Section 2, remark after eq. (splitB')), i.e. one scale per column. */
+ * of B^T (Section 2, the remark after the expansions of A and B), i.e. one scale per column. */
 void oz_col_exponents(int64_t n, int64_t p, const double *B, int32_t *eB)
 {
     for (int64_t j = 0; j < p; ++j) {
@@ -139,7 +139,7 @@ void oz_col_exponents(int64_t n, int64_t p, const double *B, int32_t *eB)
 /* ------------------------------------------------------------------ */
 
 /* Round-to-nearest-even slices of ONE number a with scale exponent e
- * (|a| <= 2^e), in exact integer arithmetic.       [Algorithm 8, lines 3-8]
+ * (|a| <= 2^e), in exact integer arithmetic.       [Algorithm 8, the loop over the slices]
  *
  * Slice s lives on the grid 2^(e+1-s*beta) (= mu'' * 2^(-beta(s-1)) with
  * mu'' = 2^e * 2^(1-beta)); q_s is the integer nearest to remainder/grid,
@@ -199,7 +199,7 @@ static void split_one_sigma(double a, int e, int beta, int k, int8_t *q, int64_t
 /* Bit-mask slices of ONE number a with scale exponent e = floor(log2 max) (|a| < 2^(e+1)):
  * slice s holds the s-th group of beta bits of |a| below 2^(e+1), with the sign of a, i.e. the
  * remainder divided by the grid 2^(e+1-s*beta) and truncated toward zero; |q_s| <= 2^beta - 1.
- *                                           [Algorithm 3, line 4; eq. (splitA'')]
+ *                                           [the digit extraction of Algorithm 3; the expansion of A in Section 2]
  * The paper describes the earlier method only this far ("extract the s-th beta bits of the mantissa
  * via bit masking"); truncation toward zero of a sign-magnitude number is that operation. */
 static void split_one_trunc(double a, int e, int beta, int k, int8_t *q, int64_t stride)
@@ -307,7 +307,7 @@ void oz_split_per_slice(int64_t rows, int64_t cols_, const double *X, int by_col
 /* ------------------------------------------------------------------ */
 
 /* C'' = sum_{s=s0..s1} A''_s B''_{g-s} for one chunk of one group
- *                                   [Algorithm 6, inner loop; eq. (errfreesum)]
+ *                                   [inner loop of Algorithm 6; the grouped sum of Section 3.2]
  * Dot products are taken in int64 and every chunk sum is checked to fit
  * INT32 (the overflow bound of Section 5.2).  s0 == s1 gives one slice pair
  * A''_s B''_t of Algorithm 4.  Returns the number of results that did NOT fit
@@ -343,10 +343,10 @@ int64_t oz_group_chunk(int64_t m, int64_t n, int64_t p,
 /* ------------------------------------------------------------------ */
 
 /* D <- D + 2^(-beta g + 2) diag(2^eA) FP64(C'') diag(2^eB)
- *                                                     [Algorithm 6, line 11]
- * (mu'', nu'' of eq. (splitA''), (splitB'') are 2^eA, 2^eB.)  The conversion
+ *                                                     [Algorithm 6, the accumulation step]
+ * (mu'', nu'' of the expansions of A and B in Section 2 are 2^eA, 2^eB.)  The conversion
  * and the power-of-two scaling are exact; the addition is the only rounding.
- * first != 0 means D is the zero matrix (Algorithm 6, line 3). */
+ * first != 0 means D is the zero matrix (the initialisation D = O of Algorithm 6). */
 void oz_accumulate(int64_t m, int64_t p, const int32_t *C,
                    const int32_t *eA, const int32_t *eB,
                    int beta, int g, int first, double *D)
@@ -364,7 +364,7 @@ void oz_accumulate(int64_t m, int64_t p, const int32_t *C,
 /* ------------------------------------------------------------------ */
 
 /* Largest power of two r_w with r_w * n * (2^(beta-1))^2 <= 2^31 - 1: the number of products of
- * round-to-nearest slices (|q| <= 2^(beta-1), tighter than the 2^beta - 1 behind eq. (def_r)) that
+ * round-to-nearest slices (|q| <= 2^(beta-1), tighter than the 2^beta - 1 behind the paper's r) that
  * can share an INT32 accumulator.  An option beyond the paper; never below the paper's r. */
 int64_t oz_r_wide(int64_t n, int beta)
 {
@@ -377,7 +377,7 @@ int64_t oz_r_wide(int64_t n, int beta)
 /* D = A B emulated with k slices, in the variants the paper compares (Section 4):
  *   split_mode 0: round-to-nearest slices, one scale per row/column     [Algorithm 8]
  *   split_mode 1: bit-mask slices                                        [Algorithm 3]
- *   r_mode 0: chunks of r products, eq. (def_r)                         [Algorithm 6]
+ *   r_mode 0: chunks of r products (Section 3.2)                        [Algorithm 6]
  *   r_mode 1: one FP64 addition per slice pair                           [Algorithm 4]
  *   r_mode 2: chunks of oz_r_wide products (split_mode 0 only; beyond the paper)
  * (0,0) = ozIMMU_H, (1,0) = ozIMMU_EF, (1,1) = ozIMMU.

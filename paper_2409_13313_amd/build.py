@@ -37,5 +37,14 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_single(source: str, lib: str) -> str:
+    """One-file shared library with the same flags (bench.py's measurement probe is built this way)."""
+    cmd = ["hipcc", *FLAGS, "-shared", source, "-o", lib]
+    pr = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if pr.returncode != 0:
+        raise RuntimeError(f"hipcc failed: {' '.join(cmd)}\n{pr.stdout}")
+    return lib
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))

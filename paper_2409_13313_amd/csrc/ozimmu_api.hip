@@ -1,15 +1,47 @@
 // C ABI of the library (declared in include/ozimmu.h): argument checks, the
 // host-side schedule of Algorithm 6 (groups g = 2..k+1, chunks of at most r
 // consecutive s), workspace carving and kernel launches.  No allocation, no
-// host synchronisation, no state between calls.
+// host synchronisation.  The only state kept between calls is what the one-time
+// set-up of a device leaves behind (ozimmu_init).
 #include "../../include/ozimmu.h"
 #include "ozimmu_kernels.h"
 #include "ozimmu_layout.h"
+#include <mutex>
 
 namespace {
 
-constexpr int64_t MAX_OUTER = (int64_t)1 << 22;   // keeps every grid dimension within HIP limits
+// m, p <= 2^22 - 256: every grid dimension stays within the HIP limits (the column split launches
+// rows_padded(p) / 64 <= 65535 workgroups along y)
+constexpr int64_t MAX_OUTER = ((int64_t)1 << 22) - 256;
 constexpr int64_t MAX_INNER = (int64_t)1 << 29;   // beta >= 1 (Section 2)
+constexpr int64_t MAX_LD = ((int64_t)1 << 30) - 1;  // the kernels form 4 * ld in 32 bits
+
+constexpr int MAX_DEVICES = 64;
+struct DeviceState {
+    bool ready;
+    int num_cu;       // compute units: size of the persistent grid
+};
+std::mutex g_state_mutex;
+DeviceState g_state[MAX_DEVICES];
+
+// State of the current device, set up on first use.
+int device_state(DeviceState* out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return OZIMMU_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_state_mutex);
+    DeviceState& s = g_state[dev];
+    if (!s.ready) {
+        if (ozk::setup_gemm_kernels() != hipSuccess) return OZIMMU_ERR_HIP;
+        int ncu = 0;
+        if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu < 1)
+            return OZIMMU_ERR_HIP;
+        s.num_cu = ncu;
+        s.ready = true;
+    }
+    *out = s;
+    return OZIMMU_OK;
+}
 
 inline int64_t align256(int64_t x) { return (x + 255) / 256 * 256; }
 
@@ -74,9 +106,10 @@ int check_gemm_args(int64_t m, int64_t n, int64_t p, const void* SA, int kA, con
 
 // single chunk (s0 > 0): g, s = s0..s1; full schedule (s0 == 0): g = g_lo..g_hi, chunks of r
 ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, int g_lo, int g_hi,
-                        int r, int s0, int s1, void* scratch)
+                        int r, int s0, int s1, void* scratch, int num_cu)
 {
     ozk::GemmArgs a{};
+    a.num_cu = num_cu;
     a.SA = SA;
     a.SB = SB;
     a.strideA = ozl::slice_bytes(m, n);
@@ -111,7 +144,7 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
 // schedule: 0 = choose, OZIMMU_SCHEDULE_ONE_LAUNCH, OZIMMU_SCHEDULE_SPLIT_INNER (honoured when possible).
 int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, const int32_t* eA,
                  const int32_t* eB, int k, int64_t r, bool per_slice, int schedule, double* D, int64_t ldd,
-                 int32_t* partial, void* scratch, hipStream_t st)
+                 int32_t* partial, void* scratch, int num_cu, hipStream_t st)
 {
     const int beta = beta_of(n);
     const int r_eff = (int)(r < k ? r : k);
@@ -121,7 +154,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     int64_t tail = 0;
     int Z = 1;
     if (!per_slice && partial && schedule != OZIMMU_SCHEDULE_ONE_LAUNCH) {
-        const int64_t ncu = ozk::num_compute_units();
+        const int64_t ncu = num_cu;
         const int64_t cand = ncu > 0 ? (T < ncu ? T : T % ncu) : 0;  // tiles of the partly filled round
         const int64_t zmax = KT / 4;  // every part gets at least one group of 4 stages of the shortest chunk
         if (cand >= 1 && cand <= SPLIT_INNER_MAX_TILES && zmax >= 2) {
@@ -152,7 +185,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         }
     }
     if (T - tail > 0) {
-        ozk::GemmArgs a = make_args(m, n, p, SA, SB, 2, k + 1, r_eff, 0, 0, scratch);
+        ozk::GemmArgs a = make_args(m, n, p, SA, SB, 2, k + 1, r_eff, 0, 0, scratch, num_cu);
         a.tile_count = (int)(T - tail);
         a.D = D;
         a.ldd = ldd;
@@ -172,7 +205,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     for (int g = 2; g <= k + 1; ++g)
         for (int s0 = 1; s0 <= g - 1; s0 += r_eff) {
             const int s1 = s0 + r_eff - 1 < g - 1 ? s0 + r_eff - 1 : g - 1;
-            ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch);
+            ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch, num_cu);
             a.tile_begin = (int)(T - tail);
             a.tile_count = (int)tail;
             a.C = partial;
@@ -238,7 +271,7 @@ size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k)
 
 int ozimmu_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int8_t* SA, int32_t* eA, void* stream)
 {
-    if (m < 0 || n < 0 || m > MAX_OUTER || n > MAX_INNER || lda < n) return OZIMMU_ERR_DIM;
+    if (m < 0 || n < 0 || m > MAX_OUTER || n > MAX_INNER || lda < n || lda > MAX_LD) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
     if (m == 0 || n == 0) return OZIMMU_OK;
     if (!A || !SA || !eA) return OZIMMU_ERR_NULL;
@@ -248,7 +281,7 @@ int ozimmu_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, in
 
 int ozimmu_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int8_t* SB, int32_t* eB, void* stream)
 {
-    if (p < 0 || n < 0 || p > MAX_OUTER || n > MAX_INNER || ldb < p) return OZIMMU_ERR_DIM;
+    if (p < 0 || n < 0 || p > MAX_OUTER || n > MAX_INNER || ldb < p || ldb > MAX_LD) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
     if (p == 0 || n == 0) return OZIMMU_OK;
     if (!B || !SB || !eB) return OZIMMU_ERR_NULL;
@@ -261,11 +294,17 @@ int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA,
 {
     int st = check_gemm_args(m, n, p, SA, kA, SB, kB, g, s0, s1);
     if (st != OZIMMU_OK) return st;
-    if (ldc < p) return OZIMMU_ERR_DIM;
-    if (m == 0 || p == 0 || n == 0) return OZIMMU_OK;
-    if (!C || !scratch) return OZIMMU_ERR_NULL;
+    if (ldc < p || ldc > MAX_LD) return OZIMMU_ERR_DIM;
+    if (m == 0 || p == 0) return OZIMMU_OK;
+    if (!C) return OZIMMU_ERR_NULL;
+    if (n == 0) return hip_status(ozk::launch_fill_zero_i32_2d(m, p, C, ldc, (hipStream_t)stream));  // empty sum
+    if (!scratch) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(scratch) % 4) return OZIMMU_ERR_WORKSPACE;
-    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch);
+    DeviceState ds;
+    st = device_state(&ds);
+    if (st != OZIMMU_OK) return st;
+    const int num_cu = ds.num_cu;
+    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch, num_cu);
     a.C = C;
     a.ldc = ldc;
     return hip_status(ozk::launch_gemm(a, 0, (hipStream_t)stream));
@@ -274,7 +313,8 @@ int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA,
 int ozimmu_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA, const int32_t* eB,
                       int beta, int g, int first, double* D, int64_t ldd, void* stream)
 {
-    if (m < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || ldc < p || ldd < p) return OZIMMU_ERR_DIM;
+    if (m < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || ldc < p || ldd < p || ldc > MAX_LD || ldd > MAX_LD)
+        return OZIMMU_ERR_DIM;
     if (beta < 1 || beta > 7 || g < 2 || g > 2 * OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
     if (m == 0 || p == 0) return OZIMMU_OK;
     if (!C || !eA || !eB || !D) return OZIMMU_ERR_NULL;
@@ -288,11 +328,18 @@ int ozimmu_gemm_group_accumulate(int64_t m, int64_t n, int64_t p, const int8_t* 
 {
     int st = check_gemm_args(m, n, p, SA, kA, SB, kB, g, s0, s1);
     if (st != OZIMMU_OK) return st;
-    if (ldd < p) return OZIMMU_ERR_DIM;
-    if (m == 0 || p == 0 || n == 0) return OZIMMU_OK;
-    if (!eA || !eB || !D || !scratch) return OZIMMU_ERR_NULL;
+    if (ldd < p || ldd > MAX_LD) return OZIMMU_ERR_DIM;
+    if (m == 0 || p == 0) return OZIMMU_OK;
+    if (!D) return OZIMMU_ERR_NULL;
+    if (n == 0)  // empty sum: D <- D + 0, or D <- +0 when D is taken to be zero
+        return first ? hip_status(ozk::launch_fill_zero_f64(m, p, D, ldd, (hipStream_t)stream)) : OZIMMU_OK;
+    if (!eA || !eB || !scratch) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(scratch) % 4) return OZIMMU_ERR_WORKSPACE;
-    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch);
+    DeviceState ds;
+    st = device_state(&ds);
+    if (st != OZIMMU_OK) return st;
+    const int num_cu = ds.num_cu;
+    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch, num_cu);
     a.D = D;
     a.ldd = ldd;
     a.eA = eA;
@@ -322,6 +369,7 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
 {
     if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
     if (lda < (transA ? m : n) || ldb < (transB ? n : p) || ldc < p) return OZIMMU_ERR_DIM;
+    if (lda > MAX_LD || ldb > MAX_LD || ldc > MAX_LD) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
     if (m == 0 || p == 0) return OZIMMU_OK;
     if (!C) return OZIMMU_ERR_NULL;
@@ -334,6 +382,9 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
     if (reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < ozimmu_workspace_bytes_ex(m, n, p, k))
         return OZIMMU_ERR_WORKSPACE;
 
+    DeviceState ds;
+    const int drc = device_state(&ds);
+    if (drc != OZIMMU_OK) return drc;
     const int bt = beta_of(n);
     const int64_t r = r_of(n, bt);
     char* ws = static_cast<char*>(workspace);
@@ -361,7 +412,7 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
     const bool direct = (alpha == 1.0 && beta == 0.0);  // D is C
     int32_t* partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(Dw) + align256(8 * m * p));
     int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, false, 0, direct ? C : Dw, direct ? ldc : p, partial,
-                          scratch, st);
+                          scratch, ds.num_cu, st);
     if (rc != OZIMMU_OK) return rc;
     if (!direct) {
         e = ozk::launch_axpby(m, p, alpha, Dw, p, beta, C, ldc, st);
@@ -405,7 +456,7 @@ size_t ozimmu_workspace_bytes_variant(int64_t m, int64_t n, int64_t p, int k, in
 int ozimmu_split_A_per_slice(int64_t m, int64_t n, const double* A, int64_t lda, int k, int8_t* SA, int32_t* eA,
                              double* rem, void* stream)
 {
-    if (m < 0 || n < 0 || m > MAX_OUTER || n > MAX_INNER || lda < n) return OZIMMU_ERR_DIM;
+    if (m < 0 || n < 0 || m > MAX_OUTER || n > MAX_INNER || lda < n || lda > MAX_LD) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
     if (m == 0 || n == 0) return OZIMMU_OK;
     if (!A || !SA || !eA || !rem) return OZIMMU_ERR_NULL;
@@ -416,7 +467,7 @@ int ozimmu_split_A_per_slice(int64_t m, int64_t n, const double* A, int64_t lda,
 int ozimmu_split_B_per_slice(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int8_t* SB, int32_t* eB,
                              double* rem, void* stream)
 {
-    if (p < 0 || n < 0 || p > MAX_OUTER || n > MAX_INNER || ldb < p) return OZIMMU_ERR_DIM;
+    if (p < 0 || n < 0 || p > MAX_OUTER || n > MAX_INNER || ldb < p || ldb > MAX_LD) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
     if (p == 0 || n == 0) return OZIMMU_OK;
     if (!B || !SB || !eB || !rem) return OZIMMU_ERR_NULL;
@@ -442,7 +493,7 @@ int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p, const double* A, int64
 int ozimmu_split_A_variant(int64_t m, int64_t n, const double* A, int64_t lda, int k, int split_mode, int8_t* SA,
                            int32_t* eA, void* stream)
 {
-    if (m < 0 || n < 0 || m > MAX_OUTER || n > MAX_INNER || lda < n) return OZIMMU_ERR_DIM;
+    if (m < 0 || n < 0 || m > MAX_OUTER || n > MAX_INNER || lda < n || lda > MAX_LD) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES || (split_mode != 0 && split_mode != 1)) return OZIMMU_ERR_SLICES;
     if (m == 0 || n == 0) return OZIMMU_OK;
     if (!A || !SA || !eA) return OZIMMU_ERR_NULL;
@@ -453,7 +504,7 @@ int ozimmu_split_A_variant(int64_t m, int64_t n, const double* A, int64_t lda, i
 int ozimmu_split_B_variant(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int split_mode, int8_t* SB,
                            int32_t* eB, void* stream)
 {
-    if (p < 0 || n < 0 || p > MAX_OUTER || n > MAX_INNER || ldb < p) return OZIMMU_ERR_DIM;
+    if (p < 0 || n < 0 || p > MAX_OUTER || n > MAX_INNER || ldb < p || ldb > MAX_LD) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES || (split_mode != 0 && split_mode != 1)) return OZIMMU_ERR_SLICES;
     if (p == 0 || n == 0) return OZIMMU_OK;
     if (!B || !SB || !eB) return OZIMMU_ERR_NULL;
@@ -461,11 +512,10 @@ int ozimmu_split_B_variant(int64_t n, int64_t p, const double* B, int64_t ldb, i
     return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), split_mode, SB, eB, (hipStream_t)stream));
 }
 
-int ozimmu_mfma_rate_probe(int iters, int value_lo, int value_hi, int32_t* out, double* ops, void* stream)
+int ozimmu_init(void)
 {
-    if (!out || !ops) return OZIMMU_ERR_NULL;
-    if (iters < 1 || value_lo < -128 || value_hi > 127 || value_lo > value_hi) return OZIMMU_ERR_DIM;
-    return hip_status(ozk::launch_mfma_rate_probe(iters, value_lo, value_hi, out, ops, (hipStream_t)stream));
+    DeviceState ds;
+    return device_state(&ds);
 }
 
 int64_t ozimmu_r_wide(int64_t n)
@@ -483,7 +533,7 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
                size_t workspace_bytes, void* stream, void* const* events)
 {
     if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
-    if (lda < n || ldb < p || ldd < p) return OZIMMU_ERR_DIM;
+    if (lda < n || ldb < p || ldd < p || lda > MAX_LD || ldb > MAX_LD || ldd > MAX_LD) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
     if (m == 0 || p == 0) return OZIMMU_OK;
     if (!D) return OZIMMU_ERR_NULL;
@@ -493,6 +543,9 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     if (reinterpret_cast<uintptr_t>(workspace) % 256 ||
         workspace_bytes < ozimmu_workspace_bytes_variant(m, n, p, k, split_mode))
         return OZIMMU_ERR_WORKSPACE;
+    DeviceState ds;
+    const int drc = device_state(&ds);
+    if (drc != OZIMMU_OK) return drc;
 
     const int schedule = accumulate_mode & (OZIMMU_SCHEDULE_ONE_LAUNCH | OZIMMU_SCHEDULE_SPLIT_INNER);
     accumulate_mode &= 0xff;
@@ -532,7 +585,8 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
 
     int32_t* partial = nullptr;  // INT32 partial sums of few-tile outputs, behind the slices
     if (!per_slice) partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(SB) + ozimmu_slices_bytes(p, n, k));
-    const int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, per_slice, schedule, D, ldd, partial, scratch, st);
+    const int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, per_slice, schedule, D, ldd, partial, scratch,
+                                ds.num_cu, st);
     if (rc != OZIMMU_OK) return rc;
     return hip_status(mark(2));
 }

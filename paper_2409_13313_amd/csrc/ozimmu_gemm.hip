@@ -601,6 +601,13 @@ __global__ __launch_bounds__(256) void k_zero_f64(int64_t m, int64_t p, double* 
     if (j < p && i < m) D[i * ldd + j] = 0.0;
 }
 
+__global__ __launch_bounds__(256) void k_zero_i32_2d(int64_t m, int64_t p, int32_t* __restrict__ C, int64_t ldc)
+{
+    const int64_t j = (int64_t)blockIdx.y * 256 + threadIdx.x;
+    const int64_t i = blockIdx.x;
+    if (j < p && i < m) C[i * ldc + j] = 0;
+}
+
 // Step (v) of the scheme: c <- fl(fl(alpha d) + fl(beta c)); beta == 0 leaves the old c unread.
 // HBM-bound: 8 bytes read (16 with beta != 0) and 8 written per element.
 __global__ __launch_bounds__(256) void k_axpby(int64_t m, int64_t p, double alpha, const double* __restrict__ D,
@@ -619,57 +626,6 @@ __global__ __launch_bounds__(256) void k_axpby(int64_t m, int64_t p, double alph
             *c = t1 + t2;
         }
     }
-}
-
-// Measurement aid: 16 independent accumulator tiles per wave, operands in registers, nothing else in the loop.
-// One operand register set is rotated per round so that consecutive rounds do not repeat the same products.
-__global__ __launch_bounds__(256) void k_mfma_rate_probe(int iters, int lo, int span, int32_t* out)
-{
-    uint32_t x = (uint32_t)(blockIdx.x * 256 + threadIdx.x) * 2654435761u + 12345u;
-    auto next_byte = [&]() -> uint32_t {
-        x = x * 1664525u + 1013904223u;
-        return (uint32_t)(lo + (int)((x >> 16) % (uint32_t)span)) & 0xffu;
-    };
-    auto next_v4i = [&]() -> v4i {
-        v4i v;
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const uint32_t b0 = next_byte(), b1 = next_byte(), b2 = next_byte(), b3 = next_byte();
-            v[d] = (int)(b0 | (b1 << 8) | (b2 << 16) | (b3 << 24));
-        }
-        return v;
-    };
-    v4i fa[4], fb[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        fa[i] = next_v4i();
-        fb[i] = next_v4i();
-    }
-    v16i acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (v16i){0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    for (int it = 0; it < iters; ++it) {
-        const v4i tmp = fa[0];
-        fa[0] = fa[1];
-        fa[1] = fa[2];
-        fa[2] = fa[3];
-        fa[3] = tmp;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    int sum = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
-    if (sum == 0x5a5a5a5a) out[0] = sum;  // practically never: keeps the loop alive without memory traffic
 }
 
 __global__ __launch_bounds__(256) void k_zero_i32(int64_t count, int32_t* __restrict__ x)
@@ -697,32 +653,11 @@ hipError_t launch_gemm(const GemmArgs& a_in, int fused, hipStream_t st)
                4 * a.ldd * 8 < ((int64_t)1 << 31);
     const int TM = (int)(ozl::rows_padded(a.m) / ozl::TILE_R), TP = (int)(ozl::rows_padded(a.p) / ozl::TILE_R);
     const size_t smem = (size_t)NSTAGES * STAGE_BYTES + EXP_BYTES;
-    static bool attr_set[64] = {false};
-    static int num_cu[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!attr_set[dev]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<0, NSTAGES>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<1, NSTAGES>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<3, NSTAGES>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2, NSTAGES>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        e = hipDeviceGetAttribute(&num_cu[dev], hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        attr_set[dev] = true;
-    }
     // one workgroup per CU (the LDS ring allows no second one), never more workgroups than tiles
     const int64_t tiles = (int64_t)a.tile_count * (fused == 3 ? a.zsplit : 1);
     if (a.tile_count <= 0 || a.tile_begin < 0 || (int64_t)a.tile_begin + a.tile_count > (int64_t)TM * TP)
         return hipErrorInvalidValue;
-    int nwg = num_cu[dev] > 0 ? num_cu[dev] : 1;
+    int nwg = a.num_cu > 0 ? a.num_cu : 1;
     if (tiles < nwg) nwg = (int)tiles;
     if (a.sync_epoch == 0) hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(NXCD * 16), 0, st, a.sync);
     dim3 grid((unsigned)nwg), block(256);
@@ -737,32 +672,34 @@ hipError_t launch_gemm(const GemmArgs& a_in, int fused, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_rate_probe(int iters, int lo, int hi, int32_t* out, double* ops, hipStream_t st)
+// One-time set-up of the current device: the chunk GEMM kernels need more dynamic LDS than the default limit.
+hipError_t setup_gemm_kernels()
 {
-    int dev = 0, ncu = 0;
-    hipError_t e = hipGetDevice(&dev);
+    const int smem = NSTAGES * STAGE_BYTES + EXP_BYTES;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<0, NSTAGES>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<1, NSTAGES>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    if (ncu < 1) ncu = 1;
-    hipLaunchKernelGGL(k_mfma_rate_probe, dim3((unsigned)ncu), dim3(256), 0, st, iters, lo, hi - lo + 1, out);
-    // per wave and round: 16 MFMAs of 32 x 32 x 32 multiply-adds
-    *ops = (double)ncu * 4.0 * (double)iters * 16.0 * 2.0 * 32.0 * 32.0 * 32.0;
-    return hipGetLastError();
-}
-
-int num_compute_units()
-{
-    int dev = 0, ncu = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    return ncu;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2, NSTAGES>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<3, NSTAGES>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
 }
 
 hipError_t launch_fill_zero_i32(int64_t count, int32_t* x, hipStream_t st)
 {
     if (count <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)((count + 1023) / 1024)), dim3(256), 0, st, count, x);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_zero_i32_2d(int64_t m, int64_t p, int32_t* C, int64_t ldc, hipStream_t st)
+{
+    dim3 grid((unsigned)m, (unsigned)((p + 255) / 256));
+    hipLaunchKernelGGL(k_zero_i32_2d, grid, dim3(256), 0, st, m, p, C, ldc);
     return hipGetLastError();
 }
 

@@ -48,6 +48,7 @@ struct GemmArgs {
     int first;             // D is zero before the first chunk: overwrite
     unsigned* sync;        // 8 x 16 counters, zeroed by launch_gemm: [16 x] per-XCD soft barrier, [1] whole grid
     int spin_limit;        // polls before a soft barrier gives up
+    int num_cu;            // compute units of the device: the persistent grid has one workgroup on each
     int sync_epoch;        // 0: launch_gemm zeroes the counters; e > 0: e single-chunk launches of this very geometry
                            // have used them since (the split-inner schedule: one reset for all its chunks)
 };
@@ -55,9 +56,10 @@ struct GemmArgs {
 // per slice (Algorithm 5), r must be 1.  fused == 3: INT32 partial sums of a.zsplit inner parts added to a
 // zeroed C (single chunk).
 hipError_t launch_gemm(const GemmArgs& a, int fused, hipStream_t st);
-// Compute units of the current device (0 on error).
-int num_compute_units();
+// One-time set-up of the current device for launch_gemm (raises the dynamic LDS limit of the chunk GEMM kernels).
+hipError_t setup_gemm_kernels();
 hipError_t launch_fill_zero_i32(int64_t count, int32_t* x, hipStream_t st);
+hipError_t launch_fill_zero_i32_2d(int64_t m, int64_t p, int32_t* C, int64_t ldc, hipStream_t st);
 // Step (iv) alone.
 hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA,
                              const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st);
@@ -69,8 +71,6 @@ hipError_t launch_accumulate_tiles(int tile_begin, int tile_count, int64_t m, in
 // Step (v): C <- alpha D + beta C (beta == 0: C not read).
 hipError_t launch_axpby(int64_t m, int64_t p, double alpha, const double* D, int64_t ldd, double beta, double* C,
                         int64_t ldc, hipStream_t st);
-// Register-only MFMA loop on every compute unit (measurement aid); *ops receives the operation count.
-hipError_t launch_mfma_rate_probe(int iters, int lo, int hi, int32_t* out, double* ops, hipStream_t st);
 hipError_t launch_fill_zero_f64(int64_t m, int64_t p, double* D, int64_t ldd, hipStream_t st);
 
 }  // namespace ozk

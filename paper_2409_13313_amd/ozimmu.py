@@ -71,8 +71,8 @@ _lib.ozimmu_split_A_per_slice.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp,
 _lib.ozimmu_split_A_per_slice.restype = _int
 _lib.ozimmu_split_B_per_slice.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _vp]
 _lib.ozimmu_split_B_per_slice.restype = _int
-_lib.ozimmu_mfma_rate_probe.argtypes = [_int, _int, _int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
-_lib.ozimmu_mfma_rate_probe.restype = _int
+_lib.ozimmu_init.argtypes = []
+_lib.ozimmu_init.restype = _int
 _lib.ozimmu_export_slices.argtypes = [_i64, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_export_slices.restype = _int
 
@@ -81,7 +81,7 @@ EXPORTS = ["ozimmu_status_string", "ozimmu_params", "ozimmu_num_chunks", "ozimmu
            "ozimmu_r_wide", "ozimmu_split_A_variant", "ozimmu_split_B_variant", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
            "ozimmu_accumulate", "ozimmu_gemm_group_accumulate", "ozimmu_export_slices",
            "ozimmu_workspace_bytes_variant", "ozimmu_remainder_bytes", "ozimmu_split_A_per_slice",
-           "ozimmu_split_B_per_slice", "ozimmu_mfma_rate_probe"]
+           "ozimmu_split_B_per_slice", "ozimmu_init"]
 
 
 SPLIT_MODES = {"rn": 0, "bitmask": 1, "per_slice": 2}
@@ -298,20 +298,9 @@ def gemm_group_accumulate(m: int, n: int, p: int, SA: torch.Tensor, kA: int, SB:
     return D
 
 
-def mfma_rate_probe(iters: int, value_lo: int, value_hi: int, reps: int = 2) -> float:
-    """Sustained v_mfma_i32_32x32x32_i8 rate of this chip in TOP/s for register operands uniform in
-    [value_lo, value_hi] (measurement aid; the last of `reps` timed launches counts)."""
-    out = torch.zeros(1, dtype=torch.int32, device="cuda")
-    ops = ctypes.c_double(0.0)
-    rate = 0.0
-    for _ in range(reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        _check(_lib.ozimmu_mfma_rate_probe(iters, value_lo, value_hi, out.data_ptr(), ctypes.byref(ops), _stream()))
-        e1.record()
-        torch.cuda.synchronize()
-        rate = ops.value / (e0.elapsed_time(e1) * 1e-3) / 1e12
-    return rate
+def init() -> None:
+    """One-time set-up of the current device (needed before the first library call inside a graph capture)."""
+    _check(_lib.ozimmu_init())
 
 
 def export_slices(rows: int, n: int, k: int, packed: torch.Tensor) -> torch.Tensor:

@@ -40,6 +40,10 @@ def test_full_size_sampled_entries(oz, m, n, p, phi, ks):
     D = torch.empty((m, p), dtype=torch.float64, device="cuda")
     native = torch.mm(dA, dB)
     bound = torch.mm(dA.abs(), dB.abs())          # |A||B|: the scale of the error bounds of Section 5
+    # unit in the first place of the largest entry of every row of A / column of B (g and f of Section 5)
+    g = torch.ldexp(torch.ones(m, dtype=torch.float64, device="cuda"), torch.frexp(dA.abs().amax(1))[1] - 1)
+    f = torch.ldexp(torch.ones(p, dtype=torch.float64, device="cuda"), torch.frexp(dB.abs().amax(0))[1] - 1)
+    beta, _ = oracle.params(n)
     for k in ks:
         D.fill_(float("nan"))                     # a tile the kernel never wrote would stay NaN
         print(f"full-size case m={m} n={n} p={p} k={k}", flush=True)
@@ -52,8 +56,9 @@ def test_full_size_sampled_entries(oz, m, n, p, phi, ks):
         assert (np.abs(got - want) <= 2 * sp).all()
         assert np.array_equal(got, want)
         # properties that hold at any size: every entry of D was written, and every entry agrees with the
-        # native FP64 product to the accuracy k >= 8 slices give (catches a tile computed from wrong operands)
+        # native FP64 product within the truncation bound of Section 5.2, 4 (k+1) n 2^(-beta k) g f^T, plus
+        # the rounding of both products (catches a tile computed from wrong operands)
         assert torch.isfinite(D).all()
-        tol = max(1e-11, 2.0 ** (12 - 7 * k))    # few slices: the truncation error of k slices of 7 bits dominates
-        assert bool(((D - native).abs() <= tol * bound).all())
+        trunc = 4.0 * (k + 1) * n * 2.0 ** (-beta * k) * torch.outer(g, f)
+        assert bool(((D - native).abs() <= trunc + 1e-11 * bound).all())
         del ws

@@ -317,18 +317,3 @@ def test_dgemm_captured_in_a_hip_graph_replays_bit_identically(oz):
         del other
     want = oracle.dgemm(A, B, k)
     assert (np.abs(eager.cpu().numpy() - want) <= 2 * np.spacing(np.abs(want))).all()
-
-
-def test_mfma_rate_probe_runs_and_reports_its_operation_count(oz):
-    import ctypes
-    out = torch.zeros(1, dtype=torch.int32, device="cuda")
-    ops = ctypes.c_double(0.0)
-    st = torch.cuda.current_stream().cuda_stream
-    assert oz._lib.ozimmu_mfma_rate_probe(10, -64, 64, out.data_ptr(), ctypes.byref(ops), st) == 0
-    torch.cuda.synchronize()
-    ncu = torch.cuda.get_device_properties(0).multi_processor_count
-    assert ops.value == ncu * 4 * 10 * 16 * 2 * 32 ** 3
-    assert oz._lib.ozimmu_mfma_rate_probe(0, -64, 64, out.data_ptr(), ctypes.byref(ops), st) == -2
-    assert oz._lib.ozimmu_mfma_rate_probe(10, 5, 4, out.data_ptr(), ctypes.byref(ops), st) == -2
-    assert oz._lib.ozimmu_mfma_rate_probe(10, -64, 64, None, ctypes.byref(ops), st) == -1
-    assert oz.mfma_rate_probe(2000, -64, 64) > 100.0      # TOP/s; a tenth of a millisecond of work

@@ -40,8 +40,8 @@ def test_host_functions(lib):
     for n in [1, 2, 3, 255, 256, 257, 1024, 5000, 16384, 65536, 2 ** 17, 2 ** 17 + 1, 2 ** 20, 2 ** 29]:
         beta, r = ctypes.c_int(), ctypes.c_int64()
         assert lib.ozimmu_params(n, ctypes.byref(beta), ctypes.byref(r)) == 0
-        want_beta = min(7, math.floor((31 - math.log2(n)) / 2))                   # eq. (beta)
-        want_r = max(1, 2 ** (31 - 2 * want_beta - math.ceil(math.log2(n))))     # eq. (def_r)
+        want_beta = min(7, math.floor((31 - math.log2(n)) / 2))                   # beta as printed in Section 2
+        want_r = max(1, 2 ** (31 - 2 * want_beta - math.ceil(math.log2(n))))     # r as printed in Section 3.2
         assert (beta.value, r.value) == (want_beta, want_r)
         for k in (1, 5, 8, 14, 20):
             w = math.ceil(k / want_r) * (k - (want_r / 2) * ((k - 1) // want_r))  # Section 5.2
@@ -73,3 +73,27 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.ozimmu_workspace_bytes(257, 257, 1, 3) == 512 + 1280 + 256 + 3 * 512 * 512 + 3 * 256 * 512 + 2 * blk
     big = lib.ozimmu_workspace_bytes(4096, 256, 4096, 1)       # 256 tiles: blocks for 128 of them
     assert big == 512 + 2 * 4 * 4096 + 2 * 4096 * 256 + 128 * blk
+
+
+def test_limits_are_reported_as_dimension_errors(lib):
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.ozimmu_dgemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp, ctypes.c_size_t, vp]
+    lib.ozimmu_split_B.argtypes = [i64, i64, vp, i64, ci, vp, vp, vp]
+    lib.ozimmu_gemm_group.argtypes = [i64, i64, i64, vp, ci, vp, ci, ci, ci, ci, vp, i64, vp, vp]
+    lib.ozimmu_accumulate.argtypes = [i64, i64, vp, i64, vp, vp, ci, ci, ci, vp, i64, vp]
+    lib.ozimmu_gemm_ex.argtypes = [ci, ci, i64, i64, i64, ctypes.c_double, vp, i64, vp, i64, ctypes.c_double, vp, i64,
+                                   ci, vp, ctypes.c_size_t, vp]
+    fake = 4096
+    # leading dimensions of 2^30 elements or more would overflow the 32-bit row offsets of the kernels
+    assert lib.ozimmu_dgemm(4, 4, 4, fake, 2 ** 30, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -2
+    assert lib.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 2 ** 30, fake, 4, 8, fake, 1 << 30, None) == -2
+    assert lib.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 2 ** 30, 8, fake, 1 << 30, None) == -2
+    assert lib.ozimmu_gemm_group(4, 4, 4, fake, 1, fake, 1, 2, 1, 1, fake, 2 ** 30, fake, None) == -2
+    assert lib.ozimmu_accumulate(4, 4, fake, 4, fake, fake, 7, 2, 1, fake, 2 ** 30, None) == -2
+    assert lib.ozimmu_gemm_ex(0, 0, 4, 4, 4, 1.0, fake, 4, fake, 4, 0.0, fake, 2 ** 30, 8, fake, 1 << 30, None) == -2
+    # outer dimensions: at most 2^22 - 256, so that every grid dimension of every kernel stays legal
+    top = 2 ** 22 - 256
+    assert lib.ozimmu_split_B(4, top + 1, fake, top + 1, 8, fake, fake, None) == -2
+    assert lib.ozimmu_dgemm(top + 1, 4, 4, fake, 4, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -2
+    assert lib.ozimmu_dgemm(4, 4, top + 1, fake, 4, fake, top + 1, fake, top + 1, 8, fake, 1 << 30, None) == -2
+    assert lib.ozimmu_dgemm(4, 4, top, fake, 4, fake, top, fake, top, 8, fake, 16, None) == -4   # accepted size

@@ -12,11 +12,11 @@ import pytest
 import oracle
 
 
-def paper_beta(n):  # eq. (beta), evaluated as printed
+def paper_beta(n):  # the formula for beta of Section 2, evaluated as printed
     return min(7, math.floor((31 - math.log2(n)) / 2))
 
 
-def paper_r(n, beta):  # eq. (def_r), evaluated as printed
+def paper_r(n, beta):  # the definition of r of Section 3.2, evaluated as printed
     return max(1, 2 ** (31 - 2 * beta - math.ceil(math.log2(n))))
 
 

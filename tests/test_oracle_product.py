@@ -109,7 +109,7 @@ def test_whole_path_equals_brute_force_walk(m, n, p, k, phi):
     Dbf, exact, mag, w, beta, r = brute_force_alg6(A, B, k)
     assert w_oracle == w == oracle.count_addends(k, r)
     assert np.array_equal(D, Dbf)
-    # order-independent check: D is within (w-1) u sum|terms| of the unrounded sum (eq. (error_sum))
+    # order-independent check: D is within (w-1) u sum|terms| of the unrounded sum (the summation error bound of Section 5)
     for i in range(m):
         for j in range(p):
             assert abs(Fraction(float(D[i, j])) - exact[i][j]) <= (w - 1) * Fraction(U) * mag[i][j] * Fraction(101, 100)

@@ -46,7 +46,7 @@ def check_slices(X, S, e, beta, ties_expected=False):
                     assert q % 2 == 0
                     saw_tie = True
                 rem = rem_new
-            # eq. (VW_bound): |V_k| <= 2^(-beta k + 1) * ufp(row max); 2^e <= 2 ufp
+            # the bound on V_k of Section 5.1: |V_k| <= 2^(-beta k + 1) * ufp(row max); 2^e <= 2 ufp
             assert abs(rem) <= two(int(e[i]) - k * beta)
     if ties_expected:
         assert saw_tie
@@ -131,7 +131,7 @@ def test_two_forms_agree_on_special_values_in_fp_range():
 
 
 def test_slices_reconstruct_bit_exactly_once_k_covers_the_mantissa():
-    # eq. (splitA''): A = diag(2^eA) sum_s 2^(1 - s beta) A''_s + V_k.  Entries within
+    # the expansion of A of Section 2: A = diag(2^eA) sum_s 2^(1 - s beta) A''_s + V_k.  Entries within
     # one binade of the row maximum have all 53 bits above 2^(eA - 54), so
     # k * beta - 1 >= 54 (k = 8, beta = 7) leaves V_k = 0 and in-order FP64
     # summation of the slices returns a_ij bit for bit.
@@ -144,7 +144,7 @@ def test_slices_reconstruct_bit_exactly_once_k_covers_the_mantissa():
     for s in range(1, k + 1):
         R = R + np.ldexp(S[s - 1].astype(np.float64), (e[:, None] + 1 - s * beta).astype(np.int32))
     assert np.array_equal(R, A)
-    # with one slice fewer the residual is not zero everywhere, and it obeys eq. (VW_bound)
+    # with one slice fewer the residual is not zero everywhere, and it obeys the bound on V_k of Section 5.1
     S7 = S[:7]
     R7 = sum(np.ldexp(S7[s - 1].astype(np.float64), (e[:, None] + 1 - s * beta).astype(np.int32)) for s in range(1, 8))
     V = A - R7

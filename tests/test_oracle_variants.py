@@ -28,7 +28,7 @@ def test_bitmask_slices_are_truncated_digits_of_the_magnitude(phi, beta, k):
         if mx == 0:
             assert e[i] == 0 and not S[:, i, :].any()
             continue
-        assert two(int(e[i])) <= mx < two(int(e[i]) + 1)                  # floor(log2 max), Algorithm 3 line 2
+        assert two(int(e[i])) <= mx < two(int(e[i]) + 1)                  # floor(log2 max), Algorithm 3, its scale
         for j in range(A.shape[1]):
             a = Fraction(float(A[i, j]))
             sign = 1 if a >= 0 else -1
@@ -41,7 +41,7 @@ def test_bitmask_slices_are_truncated_digits_of_the_magnitude(phi, beta, k):
                 rem_new = rem - abs(q) * grid
                 assert 0 <= rem_new < grid                                # truncation: the next beta bits
                 rem = rem_new
-            assert rem < two(int(e[i]) + 1 - k * beta)                    # eq. (VW_bound)
+            assert rem < two(int(e[i]) + 1 - k * beta)                    # the bound on V_k of Section 5.1
 
 
 def test_bitmask_split_of_columns_is_the_transpose():

@@ -54,7 +54,8 @@ enum {
 const char *ozimmu_status_string(int status);
 
 /* One-time set-up of the current HIP device: raises the dynamic-LDS limit of the chunk GEMM kernels,
- * and reads the number of compute units.  Every entry point that launches the chunk GEMM does this by itself on its first
+ * reads the number of compute units and resolves the device address of the static workspace of
+ * ozimmu_dgemm_static.  Every entry point that launches the chunk GEMM does this by itself on its first
  * call on a device; the set-up calls are not legal inside a HIP stream capture, so call ozimmu_init (or
  * any such entry point) once per device BEFORE capturing a graph that contains library calls.  Host;
  * idempotent; thread-safe.  Returns OZIMMU_OK or OZIMMU_ERR_HIP. */
@@ -243,6 +244,24 @@ int ozimmu_gemm_group_accumulate(int64_t m, int64_t n, int64_t p,
  * B''_s[l][j] stored at out[s][j][l].  Debug / test helper. */
 int ozimmu_export_slices(int64_t rows, int64_t n, int k, const int8_t *packed,
                          int8_t *out, void *stream);
+
+/* ozimmu_dgemm for callers that cannot allocate device memory and have no workspace to hand over
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid allocation): the workspace is
+ * a static device array of OZIMMU_STATIC_WORKSPACE_BYTES inside the library, one copy on every GPU the
+ * library is loaded on, held until the process ends.  The call allocates nothing and frees nothing.
+ * Arguments and results as for ozimmu_dgemm (bit-identical D).
+ *   Returns OZIMMU_ERR_WORKSPACE when ozimmu_workspace_bytes(m, n, p, k) exceeds
+ *   OZIMMU_STATIC_WORKSPACE_BYTES (1024^3 with k <= 20 and 2048^3 with k <= 5 fit).
+ * All calls on one GPU share that GPU's array: two calls that may run at the same time on one GPU (different
+ * streams, or different host threads) race and give undefined results; calls on one stream are ordered and
+ * safe.  What a call needs cleared it clears itself; nothing carries over from the previous call.  Before
+ * the first use inside a stream capture, call ozimmu_init on that device. */
+#define OZIMMU_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
+int ozimmu_dgemm_static(int64_t m, int64_t n, int64_t p,
+                        const double *A, int64_t lda,
+                        const double *B, int64_t ldb,
+                        double *D, int64_t ldd,
+                        int k, void *stream);
 
 #ifdef __cplusplus
 }

@@ -16,10 +16,16 @@ constexpr int64_t MAX_OUTER = ((int64_t)1 << 22) - 256;
 constexpr int64_t MAX_INNER = (int64_t)1 << 29;   // beta >= 1 (Section 2)
 constexpr int64_t MAX_LD = ((int64_t)1 << 30) - 1;  // the kernels form 4 * ld in 32 bits
 
+// Workspace of ozimmu_dgemm_static: device memory of the library itself, one copy on every GPU the library
+// is loaded on.  In host code this name is only a handle for hipGetSymbolAddress; the address kernels and
+// launchers get is DeviceState::static_ws.
+static __device__ __align__(256) unsigned char scratch[OZIMMU_STATIC_WORKSPACE_BYTES];
+
 constexpr int MAX_DEVICES = 64;
 struct DeviceState {
     bool ready;
     int num_cu;       // compute units: size of the persistent grid
+    void* static_ws;  // device address of `scratch` on this device
 };
 std::mutex g_state_mutex;
 DeviceState g_state[MAX_DEVICES];
@@ -36,7 +42,10 @@ int device_state(DeviceState* out)
         int ncu = 0;
         if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu < 1)
             return OZIMMU_ERR_HIP;
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return OZIMMU_ERR_HIP;
         s.num_cu = ncu;
+        s.static_ws = ptr;
         s.ready = true;
     }
     *out = s;
@@ -516,6 +525,20 @@ int ozimmu_init(void)
 {
     DeviceState ds;
     return device_state(&ds);
+}
+
+int ozimmu_dgemm_static(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
+                        double* D, int64_t ldd, int k, void* stream)
+{
+    if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
+    if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
+    if (ozimmu_workspace_bytes(m, n, p, k) > (size_t)OZIMMU_STATIC_WORKSPACE_BYTES) return OZIMMU_ERR_WORKSPACE;
+    if (m == 0 || p == 0) return OZIMMU_OK;
+    DeviceState ds;
+    const int rc = device_state(&ds);
+    if (rc != OZIMMU_OK) return rc;
+    return dgemm_impl(m, n, p, A, lda, B, ldb, D, ldd, k, OZIMMU_SPLIT_NEAREST, OZIMMU_ACCUM_GROUPED, ds.static_ws,
+                      (size_t)OZIMMU_STATIC_WORKSPACE_BYTES, stream, nullptr);
 }
 
 int64_t ozimmu_r_wide(int64_t n)

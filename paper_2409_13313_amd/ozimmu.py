@@ -73,6 +73,8 @@ _lib.ozimmu_split_B_per_slice.argtypes = [_i64, _i64, _vp, _i64, _int, _vp, _vp,
 _lib.ozimmu_split_B_per_slice.restype = _int
 _lib.ozimmu_init.argtypes = []
 _lib.ozimmu_init.restype = _int
+_lib.ozimmu_dgemm_static.argtypes = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _vp]
+_lib.ozimmu_dgemm_static.restype = _int
 _lib.ozimmu_export_slices.argtypes = [_i64, _i64, _int, _vp, _vp, _vp]
 _lib.ozimmu_export_slices.restype = _int
 
@@ -81,7 +83,7 @@ EXPORTS = ["ozimmu_status_string", "ozimmu_params", "ozimmu_num_chunks", "ozimmu
            "ozimmu_r_wide", "ozimmu_split_A_variant", "ozimmu_split_B_variant", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
            "ozimmu_accumulate", "ozimmu_gemm_group_accumulate", "ozimmu_export_slices",
            "ozimmu_workspace_bytes_variant", "ozimmu_remainder_bytes", "ozimmu_split_A_per_slice",
-           "ozimmu_split_B_per_slice", "ozimmu_init"]
+           "ozimmu_split_B_per_slice", "ozimmu_init", "ozimmu_dgemm_static"]
 
 
 SPLIT_MODES = {"rn": 0, "bitmask": 1, "per_slice": 2}
@@ -301,6 +303,21 @@ def gemm_group_accumulate(m: int, n: int, p: int, SA: torch.Tensor, kA: int, SB:
 def init() -> None:
     """One-time set-up of the current device (needed before the first library call inside a graph capture)."""
     _check(_lib.ozimmu_init())
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def dgemm_static(A: torch.Tensor, B: torch.Tensor, k: int, D: torch.Tensor) -> torch.Tensor:
+    """dgemm on the library's static workspace: the call allocates nothing (D is the caller's)."""
+    _dev(A, torch.float64), _dev(B, torch.float64), _dev(D, torch.float64)
+    m, n = A.shape
+    n2, p = B.shape
+    if n != n2 or tuple(D.shape) != (m, p):
+        raise ValueError("shapes do not match")
+    _check(_lib.ozimmu_dgemm_static(m, n, p, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), D.data_ptr(), _ld(D), k,
+                                    _stream()))
+    return D
 
 
 def export_slices(rows: int, n: int, k: int, packed: torch.Tensor) -> torch.Tensor:

@@ -97,3 +97,15 @@ def test_limits_are_reported_as_dimension_errors(lib):
     assert lib.ozimmu_dgemm(top + 1, 4, 4, fake, 4, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -2
     assert lib.ozimmu_dgemm(4, 4, top + 1, fake, 4, fake, top + 1, fake, top + 1, 8, fake, 1 << 30, None) == -2
     assert lib.ozimmu_dgemm(4, 4, top, fake, 4, fake, top, fake, top, 8, fake, 16, None) == -4   # accepted size
+
+
+def test_static_workspace_size_check_needs_no_gpu(lib):
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.ozimmu_dgemm_static.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
+    lib.ozimmu_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    lib.ozimmu_workspace_bytes.restype = ctypes.c_size_t
+    fake = 4096
+    assert lib.ozimmu_workspace_bytes(1024, 1024, 1024, 20) <= 64 << 20 < lib.ozimmu_workspace_bytes(4096, 4096, 4096, 8)
+    assert lib.ozimmu_dgemm_static(4096, 4096, 4096, fake, 4096, fake, 4096, fake, 4096, 8, None) == -4
+    assert lib.ozimmu_dgemm_static(4, 4, 4, fake, 4, fake, 4, fake, 4, 21, None) == -3
+    assert lib.ozimmu_dgemm_static(0, 4, 4, None, 4, None, 4, None, 4, 8, None) == 0   # empty: nothing to do

@@ -21,6 +21,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ozaki_oracle.c")
 _LIB = os.path.join(_HERE, "liboz_oracle.so")
+# A build of the same source made elsewhere (the sanitizer test points this at an instrumented build)
+_LIB_OVERRIDE = os.environ.get("OZ_ORACLE_LIB")
 
 _i64 = ctypes.c_int64
 _int = ctypes.c_int
@@ -42,8 +44,11 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        if _LIB_OVERRIDE:
+            lib = ctypes.CDLL(_LIB_OVERRIDE)
+        else:
+            build()
+            lib = ctypes.CDLL(_LIB)
         lib.oz_beta.argtypes = [_i64]
         lib.oz_beta.restype = _int
         lib.oz_r.argtypes = [_i64, _int]

@@ -72,7 +72,10 @@ int64_t ozimmu_num_chunks(int64_t n, int k);
 
 /* Bytes of the packed INT8 slice stack of a matrix with `rows` scaled vectors
  * (m for A, p for B) of inner length n and k slices; host.  The packed layout
- * is private to the library (tile-major, see ozimmu_export_slices). */
+ * is private to the library (tile-major slices stored with an offset, followed
+ * by the row sums that take the offset out again and a trailer naming it; use
+ * ozimmu_export_slices to read the slice integers).  A stack is only ever
+ * valid for the k it was made with: pass that k as kA / kB below. */
 size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k);
 
 /* Bytes of device workspace ozimmu_dgemm needs (scheduling scratch, exponents, the two slice stacks and
@@ -151,18 +154,21 @@ int64_t ozimmu_r_wide(int64_t n);
  *   op(A) is m x n: A is stored row-major m x n (lda >= n) or, transposed, n x m (lda >= m).
  *   op(B) is n x p: B is stored row-major n x p (ldb >= p) or, transposed, p x n (ldb >= n).
  *   C       device, m x p row-major, ldc >= p; read unless beta == 0, then overwritten.
- *   workspace  device, >= ozimmu_workspace_bytes_ex(m,n,p,k) bytes, 256-byte aligned.
+ *   workspace  device, 256-byte aligned; >= ozimmu_workspace_bytes_ex(m,n,p,k) bytes, or, when
+ *              beta == 0, only >= ozimmu_workspace_bytes(m,n,p,k) (the sum is then formed in C itself).
  * The product D is formed exactly as by ozimmu_dgemm; then, per element, t1 = fl(alpha d),
  * t2 = fl(beta c), c = fl(t1 + t2) (three rounded FP64 operations, no fused multiply-add); with
- * beta == 0 the old C is not read and c = fl(alpha d).  Transposition costs nothing: a transposed
- * operand is split by the kernel that otherwise handles the other operand.
+ * beta == 0 the old C is not read and c = fl(alpha d).  Step (v) costs no pass of its own: the last
+ * chunk of every output tile applies it in its epilogue.  Transposition costs nothing either: a
+ * transposed operand is split by the kernel that otherwise handles the other operand.
  * m == 0 or p == 0: nothing to do; n == 0: C <- beta C (or +0 when beta == 0). */
 int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p,
                    double alpha, const double *A, int64_t lda, const double *B, int64_t ldb,
                    double beta, double *C, int64_t ldc,
                    int k, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Bytes of device workspace ozimmu_gemm_ex needs (ozimmu_dgemm's plus an m x p FP64 buffer); host. */
+/* Bytes of device workspace ozimmu_gemm_ex needs when beta != 0 (ozimmu_dgemm's plus an m x p FP64 buffer for
+ * the running sum, because the old C is needed until the very end); host. */
 size_t ozimmu_workspace_bytes_ex(int64_t m, int64_t n, int64_t p, int k);
 
 /* ---- phase-level entry points (the same kernels ozimmu_dgemm runs) ---- */
@@ -211,7 +217,7 @@ int ozimmu_split_B_per_slice(int64_t n, int64_t p, const double *B, int64_t ldb,
 /* Step (iii) for one chunk: C'' <- sum_{s = s0..s1} A''_s B''_{g-s} in INT32
  *                                              [Algorithm 6, the inner loop over s].
  * s0 == s1 gives the single pair product A''_s B''_{g-s} of Algorithm 4.
- *   SA, SB  device, packed slice stacks holding kA / kB slices.
+ *   SA, SB  device, packed slice stacks made with kA / kB slices.
  *   C       device, int32 m x p row-major, ldc >= p, overwritten (with zeros when n == 0).
  *   scratch device, OZIMMU_SCRATCH_BYTES bytes, 4-byte aligned.
  * Requires 1 <= s0 <= s1 <= kA and 1 <= g - s1, g - s0 <= kB.  The caller is

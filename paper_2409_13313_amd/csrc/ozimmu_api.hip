@@ -113,14 +113,29 @@ int check_gemm_args(int64_t m, int64_t n, int64_t p, const void* SA, int kA, con
     return OZIMMU_OK;
 }
 
-// single chunk (s0 > 0): g, s = s0..s1; full schedule (s0 == 0): g = g_lo..g_hi, chunks of r
-ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, int g_lo, int g_hi,
-                        int r, int s0, int s1, void* scratch, int num_cu)
+// Offset of the stored bytes (see ozimmu_layout.h): 63 moves round-to-nearest slices (|q| <= 64) into [-1, 127];
+// bit-mask slices (|q| <= 127) have no room for one, and neither have the wide chunks, whose length is derived
+// from |q| <= 64.
+#ifndef OZIMMU_RN_OFFSET
+#define OZIMMU_RN_OFFSET 63
+#endif
+constexpr int RN_OFFSET = OZIMMU_RN_OFFSET;
+
+// single chunk (s0 > 0): g, s = s0..s1; full schedule (s0 == 0): g = g_lo..g_hi, chunks of r.
+// SA / SB are whole stacks of kA / kB slices (slices, prefix row sums, trailer).
+ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA, const int8_t* SB, int kB, int g_lo,
+                        int g_hi, int r, int s0, int s1, void* scratch, int num_cu)
 {
     ozk::GemmArgs a{};
     a.num_cu = num_cu;
     a.SA = SA;
     a.SB = SB;
+    a.PA = reinterpret_cast<const int32_t*>(SA + ozl::sums_offset(m, n, kA));
+    a.PB = reinterpret_cast<const int32_t*>(SB + ozl::sums_offset(p, n, kB));
+    a.pstrideA = ozl::rows_padded(m);
+    a.pstrideB = ozl::rows_padded(p);
+    a.cA = reinterpret_cast<const int32_t*>(SA + ozl::trailer_offset(m, n, kA));
+    a.cB = reinterpret_cast<const int32_t*>(SB + ozl::trailer_offset(p, n, kB));
     a.strideA = ozl::slice_bytes(m, n);
     a.strideB = ozl::slice_bytes(p, n);
     a.KT = (int)(ozl::inner_padded(n) / ozl::TILE_K);
@@ -138,8 +153,17 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
     a.sync = static_cast<unsigned*>(scratch);
     a.spin_limit = 64;  // polls (about 0.1 us each) before a workgroup stops waiting for its team
     a.sync_epoch = 0;
+    a.alpha = 1.0;
     return a;
 }
+
+// Step (v) applied by the last chunk of every tile: out = fl(fl(alpha d) + fl(cbeta c_old)).
+struct Finish {
+    bool on;
+    double alpha, cbeta;
+    double* Cout;   // == D when cbeta == 0 (the sum is formed in C itself)
+    int64_t ldco;
+};
 
 // Steps (iii) + (iv) for the whole schedule of Algorithm 6 (groups g = 2..k+1 ascending, chunks of at most r
 // consecutive s), into D.  Two ways to run it, with bit-identical results:
@@ -153,7 +177,7 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, const
 // schedule: 0 = choose, OZIMMU_SCHEDULE_ONE_LAUNCH, OZIMMU_SCHEDULE_SPLIT_INNER (honoured when possible).
 int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, const int32_t* eA,
                  const int32_t* eB, int k, int64_t r, bool per_slice, int schedule, double* D, int64_t ldd,
-                 int32_t* partial, void* scratch, int num_cu, hipStream_t st)
+                 const Finish& fin, int32_t* partial, void* scratch, int num_cu, hipStream_t st)
 {
     const int beta = beta_of(n);
     const int r_eff = (int)(r < k ? r : k);
@@ -194,7 +218,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         }
     }
     if (T - tail > 0) {
-        ozk::GemmArgs a = make_args(m, n, p, SA, SB, 2, k + 1, r_eff, 0, 0, scratch, num_cu);
+        ozk::GemmArgs a = make_args(m, n, p, SA, k, SB, k, 2, k + 1, r_eff, 0, 0, scratch, num_cu);
         a.tile_count = (int)(T - tail);
         a.D = D;
         a.ldd = ldd;
@@ -203,6 +227,11 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         a.estrideA = m;
         a.estrideB = p;
         a.first = 1;
+        a.finish = fin.on ? 1 : 0;
+        a.alpha = fin.alpha;
+        a.cbeta = fin.cbeta;
+        a.Cout = fin.Cout;
+        a.ldco = fin.ldco;
         const hipError_t e = ozk::launch_gemm(a, per_slice ? 2 : 1, st);
         if (e != hipSuccess) return OZIMMU_ERR_HIP;
     }
@@ -214,7 +243,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     for (int g = 2; g <= k + 1; ++g)
         for (int s0 = 1; s0 <= g - 1; s0 += r_eff) {
             const int s1 = s0 + r_eff - 1 < g - 1 ? s0 + r_eff - 1 : g - 1;
-            ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch, num_cu);
+            ozk::GemmArgs a = make_args(m, n, p, SA, k, SB, k, g, g, s1 - s0 + 1, s0, s1, scratch, num_cu);
             a.tile_begin = (int)(T - tail);
             a.tile_count = (int)tail;
             a.C = partial;
@@ -222,8 +251,25 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             a.sync_epoch = epoch++;
             e = ozk::launch_gemm(a, 3, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;
-            e = ozk::launch_accumulate_tiles((int)(T - tail), (int)tail, m, p, partial, eA, eB, 2 - beta * g, first, D,
-                                             ldd, st);
+            ozk::TileAccArgs t{};
+            t.tile_begin = (int)(T - tail);
+            t.tile_count = (int)tail;
+            t.m = m;
+            t.p = p;
+            t.Ct = partial;
+            t.eA = eA;
+            t.eB = eB;
+            t.shift = 2 - beta * g;
+            t.first = first;
+            t.D = D;
+            t.ldd = ldd;
+            const bool last = (g == k + 1 && s1 == g - 1);
+            t.finish = (fin.on && last) ? 1 : 0;
+            t.alpha = fin.alpha;
+            t.cbeta = fin.cbeta;
+            t.Cout = fin.Cout;
+            t.ldco = fin.ldco;
+            e = ozk::launch_accumulate_tiles(t, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;
             first = 0;
         }
@@ -268,7 +314,7 @@ int64_t ozimmu_num_chunks(int64_t n, int k)
 size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k)
 {
     if (rows < 0 || n < 0 || k < 0) return 0;
-    return (size_t)k * (size_t)ozl::slice_bytes(rows, n);
+    return (size_t)ozl::stack_bytes(rows, n, k);
 }
 
 size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k)
@@ -285,7 +331,7 @@ int ozimmu_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, in
     if (m == 0 || n == 0) return OZIMMU_OK;
     if (!A || !SA || !eA) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(SA) % 256) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), 0, SA, eA, (hipStream_t)stream));
+    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), 0, RN_OFFSET, SA, eA, (hipStream_t)stream));
 }
 
 int ozimmu_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int8_t* SB, int32_t* eB, void* stream)
@@ -295,7 +341,7 @@ int ozimmu_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, in
     if (p == 0 || n == 0) return OZIMMU_OK;
     if (!B || !SB || !eB) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(SB) % 256) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), 0, SB, eB, (hipStream_t)stream));
+    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), 0, RN_OFFSET, SB, eB, (hipStream_t)stream));
 }
 
 int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA, const int8_t* SB, int kB, int g,
@@ -313,7 +359,7 @@ int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA,
     st = device_state(&ds);
     if (st != OZIMMU_OK) return st;
     const int num_cu = ds.num_cu;
-    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch, num_cu);
+    ozk::GemmArgs a = make_args(m, n, p, SA, kA, SB, kB, g, g, s1 - s0 + 1, s0, s1, scratch, num_cu);
     a.C = C;
     a.ldc = ldc;
     return hip_status(ozk::launch_gemm(a, 0, (hipStream_t)stream));
@@ -348,7 +394,7 @@ int ozimmu_gemm_group_accumulate(int64_t m, int64_t n, int64_t p, const int8_t* 
     st = device_state(&ds);
     if (st != OZIMMU_OK) return st;
     const int num_cu = ds.num_cu;
-    ozk::GemmArgs a = make_args(m, n, p, SA, SB, g, g, s1 - s0 + 1, s0, s1, scratch, num_cu);
+    ozk::GemmArgs a = make_args(m, n, p, SA, kA, SB, kB, g, g, s1 - s0 + 1, s0, s1, scratch, num_cu);
     a.D = D;
     a.ldd = ldd;
     a.eA = eA;
@@ -388,8 +434,9 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
         return hip_status(ozk::launch_axpby(m, p, 0.0, nullptr, 0, beta, C, ldc, st));
     }
     if (!A || !B || !workspace) return OZIMMU_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < ozimmu_workspace_bytes_ex(m, n, p, k))
-        return OZIMMU_ERR_WORKSPACE;
+    // beta == 0: the sum is formed in C itself, no m x p buffer
+    const size_t need = beta == 0.0 ? ozimmu_workspace_bytes(m, n, p, k) : ozimmu_workspace_bytes_ex(m, n, p, k);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need) return OZIMMU_ERR_WORKSPACE;
 
     DeviceState ds;
     const int drc = device_state(&ds);
@@ -407,27 +454,26 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
     ws += ozimmu_slices_bytes(m, n, k);
     int8_t* SB = reinterpret_cast<int8_t*>(ws);
     ws += ozimmu_slices_bytes(p, n, k);
-    double* Dw = reinterpret_cast<double*>(ws);
+    int32_t* partial = reinterpret_cast<int32_t*>(ws);
+    ws += partial_sums_bytes(m, p);
+    double* Dw = reinterpret_cast<double*>(ws);  // beta != 0 only
 
     // op(A): one scale per row of op(A).  Stored transposed (n x m), those rows are the columns of the
     // stored matrix, which is what the column-wise split kernel handles; likewise for op(B).
-    hipError_t e = transA ? ozk::launch_split_B(n, m, A, lda, k, bt, 0, SA, eA, st)
-                          : ozk::launch_split_A(m, n, A, lda, k, bt, 0, SA, eA, st);
+    hipError_t e = transA ? ozk::launch_split_B(n, m, A, lda, k, bt, 0, RN_OFFSET, SA, eA, st)
+                          : ozk::launch_split_A(m, n, A, lda, k, bt, 0, RN_OFFSET, SA, eA, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
-    e = transB ? ozk::launch_split_A(p, n, B, ldb, k, bt, 0, SB, eB, st)
-               : ozk::launch_split_B(n, p, B, ldb, k, bt, 0, SB, eB, st);
+    e = transB ? ozk::launch_split_A(p, n, B, ldb, k, bt, 0, RN_OFFSET, SB, eB, st)
+               : ozk::launch_split_B(n, p, B, ldb, k, bt, 0, RN_OFFSET, SB, eB, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
-    const bool direct = (alpha == 1.0 && beta == 0.0);  // D is C
-    int32_t* partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(Dw) + align256(8 * m * p));
-    int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, false, 0, direct ? C : Dw, direct ? ldc : p, partial,
-                          scratch, ds.num_cu, st);
-    if (rc != OZIMMU_OK) return rc;
-    if (!direct) {
-        e = ozk::launch_axpby(m, p, alpha, Dw, p, beta, C, ldc, st);
-        if (e != hipSuccess) return OZIMMU_ERR_HIP;
-    }
-    return OZIMMU_OK;
+    // Step (v) rides on the epilogue of every tile's last chunk.  beta == 0: the running sum lives in C and the
+    // last chunk stores fl(alpha d) there.  Otherwise the running sum lives in the workspace buffer and the last
+    // chunk reads the old C and writes the new one.
+    const bool in_place = beta == 0.0;
+    const Finish fin = {!(alpha == 1.0 && beta == 0.0), alpha, beta, C, ldc};
+    return run_schedule(m, n, p, SA, SB, eA, eB, k, r, false, 0, in_place ? C : Dw, in_place ? ldc : p, fin, partial,
+                        scratch, ds.num_cu, st);
 }
 
 int ozimmu_dgemm(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
@@ -507,7 +553,8 @@ int ozimmu_split_A_variant(int64_t m, int64_t n, const double* A, int64_t lda, i
     if (m == 0 || n == 0) return OZIMMU_OK;
     if (!A || !SA || !eA) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(SA) % 256) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), split_mode, SA, eA, (hipStream_t)stream));
+    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), split_mode, split_mode == 0 ? RN_OFFSET : 0, SA, eA,
+                                          (hipStream_t)stream));
 }
 
 int ozimmu_split_B_variant(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int split_mode, int8_t* SB,
@@ -518,7 +565,8 @@ int ozimmu_split_B_variant(int64_t n, int64_t p, const double* B, int64_t ldb, i
     if (p == 0 || n == 0) return OZIMMU_OK;
     if (!B || !SB || !eB) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(SB) % 256) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), split_mode, SB, eB, (hipStream_t)stream));
+    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), split_mode, split_mode == 0 ? RN_OFFSET : 0, SB, eB,
+                                          (hipStream_t)stream));
 }
 
 int ozimmu_init(void)
@@ -597,19 +645,21 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     };
     hipError_t e = mark(0);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
+    const int offset = (split_mode == OZIMMU_SPLIT_NEAREST && accumulate_mode != OZIMMU_ACCUM_WIDE) ? RN_OFFSET : 0;
     e = per_slice ? ozk::launch_split_A_per_slice(m, n, A, lda, k, beta, SA, eA, remA, st)
-                  : ozk::launch_split_A(m, n, A, lda, k, beta, split_mode, SA, eA, st);
+                  : ozk::launch_split_A(m, n, A, lda, k, beta, split_mode, offset, SA, eA, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     e = per_slice ? ozk::launch_split_B_per_slice(n, p, B, ldb, k, beta, SB, eB, remB, st)
-                  : ozk::launch_split_B(n, p, B, ldb, k, beta, split_mode, SB, eB, st);
+                  : ozk::launch_split_B(n, p, B, ldb, k, beta, split_mode, offset, SB, eB, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     e = mark(1);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
     int32_t* partial = nullptr;  // INT32 partial sums of few-tile outputs, behind the slices
     if (!per_slice) partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(SB) + ozimmu_slices_bytes(p, n, k));
-    const int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, per_slice, schedule, D, ldd, partial, scratch,
-                                ds.num_cu, st);
+    const Finish no_finish = {false, 1.0, 0.0, D, ldd};
+    const int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, per_slice, schedule, D, ldd, no_finish, partial,
+                                scratch, ds.num_cu, st);
     if (rc != OZIMMU_OK) return rc;
     return hip_status(mark(2));
 }

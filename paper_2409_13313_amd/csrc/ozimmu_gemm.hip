@@ -14,6 +14,17 @@
 // sums to zeroed per-tile blocks with integer atomics (exact in any order).
 // A launch covers a range of tiles (tile_begin, tile_count) of the band order.
 //
+// The stored bytes are the slice integers plus the offset of their stack (cA for A, cB for B, see
+// ozimmu_layout.h), so the MFMAs sum a' b'.  The offsets are taken out by STARTING the accumulators of a
+// chunk at -(ra[i] + cb[j]) instead of zero,
+//     ra[i] = cB SA'[i] - pairs N cA cB,   cb[j] = cA SB'[j],
+// SA' / SB' being the sums of the stored bytes of row i / column j over the chunk's slices (differences of
+// the prefix sums the split kernels left behind the slices) and N the padded inner length: what the
+// epilogue finds in the accumulators is then C'' itself.  Every partial sum on the way lies in
+// [-12033, 4096] x (inner length of the chunk), inside INT32 under the paper's bound on the chunk length.
+// With `finish` set the last chunk of a tile also applies step (v) of the scheme in its epilogue:
+//     out = fl(fl(alpha d) + fl(cbeta c_old))   (cbeta == 0: c_old is not read),  d the finished sum.
+//
 // Tiling: 256 x 256 outputs per workgroup, 4 waves in a 2 x 2 grid, each wave
 // 128 x 128 = 4 x 4 tiles of v_mfma_i32_32x32x32_i8 (256 INT32 accumulators per
 // lane, one wave per SIMD).  A stage is one packed 16 KiB tile of A and one of B
@@ -49,7 +60,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // A tile + B tile = 32 KiB
 constexpr int NLOAD = TILE_BYTES / (256 * 16);    // 16-byte copies per thread and operand tile = 4
 constexpr int EPI_ROWS = 2;                       // 32 x 32 tiles per batch of the plain epilogue (16 D loads in flight per lane each)
-constexpr int EXP_BYTES = 2 * 256 * 4;            // exponents of the tile's 256 rows and 256 columns, kept in LDS
+constexpr int EXP_BYTES = 2 * 256 * 8;            // (exponent, offset correction) of the tile's 256 rows and 256 columns, kept in LDS
 
 // Linear tile order: bands of GROUP tile rows, each walked column by column, so
 // that 32 consecutive tiles form an 8 x 4 patch (8 A tiles + 4 B tiles per stage).
@@ -187,6 +198,10 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     }
     typedef __attribute__((address_space(3))) const v4i* lds_v4i_ptr;
 
+    // offsets of the two stacks (stored byte = slice integer + offset)
+    const int cA = a.cA[0], cB = a.cB[0];
+    const bool offsets = (cA | cB) != 0;
+
     // team geometry
     const int nwg = gridDim.x, bid = blockIdx.x;
     const int xcd = bid % NXCD, member = bid / NXCD;
@@ -243,7 +258,10 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
         const int64_t row0 = (int64_t)tm * 256 + wm * 128;
         const int64_t col0 = (int64_t)tp * 256 + wn * 128;
         int first = a.first;
+        // per row [0, 256) and column [256, 512) of the tile: scale exponents (fused modes) and the start values
+        // of the chunk's accumulators (minus the offset corrections)
         int* const lds_exp = reinterpret_cast<int*>(lds + NS * STAGE_BYTES);
+        int* const lds_corr = lds_exp + 512;
         if (MODE == 1) {
             // exponents of this tile's rows and columns go to LDS once (every wave is past the previous
             // tile's epilogue; the chunk prologue's barrier publishes them)
@@ -282,10 +300,6 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 };
 
                 v16i acc[4][4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[i][j] = (v16i){0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
                 // the 4 MFMAs of A row tile i for one k-step
                 auto math_row = [&](const v4i* fa, const v4i* fb, int i) {
 #pragma unroll
@@ -307,6 +321,16 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     lds_exp[t] = gr < a.m ? a.eA[(int64_t)(c0 - 1) * a.estrideA + gr] : 0;
                     lds_exp[256 + t] = gc < a.p ? a.eB[(int64_t)(g - c0 - 1) * a.estrideB + gc] : 0;
                 }
+                // sums of the stored bytes over the chunk's slices (A: c0 .. c1, B: g - c1 .. g - c0) for this
+                // thread's row and column of the tile, as differences of prefix sums; the loads are in flight
+                // while the first stages are issued and the team lines up, the corrections go to LDS after that
+                int sumA = 0, sumB = 0;
+                if (offsets) {
+                    const int64_t gr = (int64_t)tm * 256 + t, gc = (int64_t)tp * 256 + t;  // inside the padded stacks
+                    sumA = a.PA[(int64_t)(c1 - 1) * a.pstrideA + gr] - (c0 > 1 ? a.PA[(int64_t)(c0 - 2) * a.pstrideA + gr] : 0);
+                    const int t_lo = g - c1, t_hi = g - c0;
+                    sumB = a.PB[(int64_t)(t_hi - 1) * a.pstrideB + gc] - (t_lo > 1 ? a.PB[(int64_t)(t_lo - 2) * a.pstrideB + gc] : 0);
+                }
                 static_for<0, NS - 1>([&](auto S) {
                     constexpr int sidx = decltype(S)::value;
                     static_for<0, NLOAD>([&](auto Q) {
@@ -325,6 +349,12 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 sync_target += participants;
                 all_target += all_participants;
                 arrive_and_wait2(all_ctr, all_target, sync_ctr, sync_target, a.spin_limit);
+                {
+                    // every wave is past the previous chunk (first barrier above); the barrier below publishes
+                    const uint32_t pairs_n = (uint32_t)(c1 - c0 + 1) * (uint32_t)(KT * TILE_K);
+                    lds_corr[t] = (int)(pairs_n * (uint32_t)(cA * cB) - (uint32_t)cB * (uint32_t)sumA);  // -ra
+                    lds_corr[256 + t] = (int)(0u - (uint32_t)cA * (uint32_t)sumB);                       // -cb
+                }
                 wait_vmcnt<NLOAD*(2 * (NS - 2) - 1)>();
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
@@ -332,6 +362,29 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 for (int i = 0; i < 4; ++i) {
                     fa0[i] = *(lds_v4i_ptr)(uintptr_t)(fragA[0][0] + i * 2048);
                     fb0[i] = *(lds_v4i_ptr)(uintptr_t)(fragB[0][0] + TILE_BYTES + i * 2048);
+                }
+                // accumulators start at -(ra[row] + cb[column]) (see the head of this file); of a chunk that is cut
+                // into parts (MODE 3) only part 0 carries the start value, the others start at zero
+                {
+                    int ncb[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) ncb[j] = lds_corr[256 + wn * 128 + j * 32 + lr];
+                    const bool carries = (MODE != 3) || zpart == 0;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        int nra[16];
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) nra[r] = lds_corr[wm * 128 + i * 32 + 8 * (r / 4) + (r % 4) + 4 * lh];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) acc[i][j][r] = carries ? (int)((uint32_t)nra[r] + (uint32_t)ncb[j]) : 0;
+                            // the tile goes to its accumulation registers now, not when the first MFMA asks for it
+                            // (256 start values waiting in ordinary registers would not fit)
+                            asm volatile("" : "+a"(acc[i][j]));
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
                 }
 
                 // One stage whose ring buffer index U is a compile-time constant.  32 MFMAs, 16 fragment
@@ -415,6 +468,10 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 asm volatile("" : "+v"(lhe), "+v"(lre));
                 const bool lane_col_ok[4] = {ec0 + lre < a.p, ec0 + 32 + lre < a.p, ec0 + 64 + lre < a.p,
                                              ec0 + 96 + lre < a.p};
+                // exponent + shift of this lane's column in each of the 4 column tiles
+                int eb[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) eb[j] = lds_exp[256 + wn * 128 + j * 32 + lre] + shift;
                 if (MODE == 0 || MODE == 3) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
@@ -422,11 +479,11 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                         for (int i = 0; i < 4; ++i)
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
-                                const int64_t urow = er0 + i * 32 + 8 * (r / 4) + (r % 4);  // uniform part of the row
+                                const int rt = i * 32 + 8 * (r / 4) + (r % 4);           // uniform part of the row in the wave's block
+                                const int64_t urow = er0 + rt;
                                 // MODE 3: the tile's own dense 256 x 256 block, addressed by the row / column in the tile
                                 int32_t* base = (MODE == 3)
-                                                    ? a.C + (int64_t)ztile * (256 * 256) +
-                                                          (int64_t)(wm * 128 + i * 32 + 8 * (r / 4) + (r % 4)) * 256 +
+                                                    ? a.C + (int64_t)ztile * (256 * 256) + (int64_t)(wm * 128 + rt) * 256 +
                                                           wn * 128 + j * 32
                                                     : a.C + urow * a.ldc + ec0 + j * 32;
                                 const uint32_t off =
@@ -440,14 +497,18 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 }
                             }
                 } else {
-                    // Exponents come from LDS (the compiler cannot prove that D does not alias eA / eB and
-                    // would order global exponent loads behind every store).  Per column of 32 x 32 tiles and
-                    // per pair of row tiles: 32 loads of D in flight, then the adds and stores.  D is touched
-                    // once per chunk, a millisecond apart: non-temporal accesses keep it from displacing the
-                    // operand tiles the team shares in L2 (1 % at 16384^3).
-                    int eb[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) eb[j] = lds_exp[256 + wn * 128 + j * 32 + lre] + shift;
+                    // Exponents come from LDS (the compiler cannot prove that D does not alias eA / eB and would
+                    // order global exponent loads behind every store).  D is
+                    // touched once per chunk, a millisecond apart: non-temporal accesses keep it from displacing
+                    // the operand tiles the team shares in L2 (1 % at 16384^3).
+                    // The last chunk of a tile applies step (v) when asked to (finish): its result goes to Cout.
+                    const bool last = a.finish && g == a.g_hi && c1 == s_hi;
+                    const bool with_c = last && a.cbeta != 0.0;
+                    // the FP64 addend of this chunk for accumulator (i, j, r)
+                    auto addend = [&](int i, int j, int r) -> double {
+                        const int ea = lds_exp[wm * 128 + i * 32 + 8 * (r / 4) + (r % 4) + 4 * lhe];
+                        return ldexp((double)acc[i][j][r], ea + eb[j]);
+                    };
                     const uint32_t off = (uint32_t)(4 * lhe) * (uint32_t)a.ldd + (uint32_t)lre;
                     // Later chunks of a tile that lies wholly inside D (and D aligned for 16-byte copies): the old
                     // values of D come in through the LDS ring, which is idle now, with the same global -> LDS
@@ -456,7 +517,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     // no load ever waits for a store to be acknowledged.  Wave w owns ring buffer w (32 KiB = two
                     // half blocks).  Copy t of a half block brings rows 4t .. 4t+3: lane l row l / 16, columns
                     // 2 (l % 16), + 1, i.e. the half block lands row-major with 256 bytes per row.
-                    const bool staged = !first && a.dma_ok && (int64_t)tm * 256 + 256 <= a.m &&
+                    const bool staged = !first && !with_c && a.dma_ok && (int64_t)tm * 256 + 256 <= a.m &&
                                         (int64_t)tp * 256 + 256 <= a.p;
                     if (staged) {
                         __builtin_amdgcn_s_barrier();  // every wave has read its last fragments from the ring
@@ -470,15 +531,16 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                         const int64_t row_step = 4 * a.ldd;  // elements between the rows of consecutive copies
                         auto issue = [&](auto HB) {          // half block hb = 2 j + h into buffer hb % 2
                             constexpr int hb = decltype(HB)::value, j = hb / 2, h = hb % 2;
-                            const double* g = a.D + (er0 + 64 * h) * a.ldd + ec0 + 32 * j;
+                            const double* gp = a.D + (er0 + 64 * h) * a.ldd + ec0 + 32 * j;
                             static_for<0, 16>([&](auto TT) {
                                 constexpr int tt = decltype(TT)::value;
-                                asm volatile("" : "+s"(g));  // one running pointer, not sixteen precomputed ones
-                                copy16_to_lds_nt<(hb % 2) * 16384 + tt * 1024>(region, dvoff, g);
-                                g += row_step;
+                                asm volatile("" : "+s"(gp));  // one running pointer, not sixteen precomputed ones
+                                copy16_to_lds_nt<(hb % 2) * 16384 + tt * 1024>(region, dvoff, gp);
+                                gp += row_step;
                             });
                         };
                         typedef __attribute__((address_space(3))) const double* lds_f64_ptr;
+                        const double alpha = last ? a.alpha : 1.0;  // fl(1.0 * x) = x
                         issue(std::integral_constant<int, 0>{});
                         issue(std::integral_constant<int, 1>{});
                         static_for<0, 8>([&](auto HB) {
@@ -502,9 +564,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 for (int r = 0; r < 16; ++r) {
                                     const int64_t urow = er0 + (2 * h + i) * 32 + 8 * (r / 4) + (r % 4);
                                     double* base = a.D + urow * a.ldd + ec0 + j * 32;
-                                    const int ea = lds_exp[wm * 128 + (2 * h + i) * 32 + 8 * (r / 4) + (r % 4) + 4 * lhe];
-                                    const double term = ldexp((double)acc[2 * h + i][j][r], ea + eb[j]);
-                                    __builtin_nontemporal_store(old[r] + term, &base[off]);
+                                    __builtin_nontemporal_store(alpha * (old[r] + addend(2 * h + i, j, r)), &base[off]);
                                 }
                                 __builtin_amdgcn_sched_barrier(0);
                             }
@@ -513,36 +573,69 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                             if constexpr (hb + 2 < 8) issue(std::integral_constant<int, hb + 2>{});
                             __builtin_amdgcn_sched_barrier(0);
                         });
-                    } else
+                    } else {
+                        // Edge tiles, first chunks, unaligned D, and the last chunk when it also reads the old C:
+                        // per column of 32 x 32 tiles and per batch of ROWS row tiles, 16 ROWS loads of D (and of C)
+                        // in flight, then the adds and stores.
+                        auto plain = [&](auto ROWS, auto WITH_C, auto LAST) {
+                            constexpr int rows = decltype(ROWS)::value;
+                            constexpr bool wc = decltype(WITH_C)::value;
+                            constexpr bool fin = decltype(LAST)::value;
+                            const uint32_t offc = (uint32_t)(4 * lhe) * (uint32_t)a.ldco + (uint32_t)lre;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
+                            for (int j = 0; j < 4; ++j) {
 #pragma unroll
-                        for (int ih = 0; ih < 4; ih += EPI_ROWS) {
-                            double old[EPI_ROWS][16];
-                            if (!first) {
+                                for (int ih = 0; ih < 4; ih += rows) {
+                                    double old[rows][16], cold[wc ? rows : 1][16];
+                                    if (!first) {
 #pragma unroll
-                                for (int i = 0; i < EPI_ROWS; ++i)
+                                        for (int i = 0; i < rows; ++i)
 #pragma unroll
-                                    for (int r = 0; r < 16; ++r) {
-                                        const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
-                                        const double* base = a.D + urow * a.ldd + ec0 + j * 32;
-                                        old[i][r] = (lane_col_ok[j] && urow + 4 * lhe < a.m) ? __builtin_nontemporal_load(&base[off]) : 0.0;
+                                            for (int r = 0; r < 16; ++r) {
+                                                const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
+                                                const double* base = a.D + urow * a.ldd + ec0 + j * 32;
+                                                old[i][r] = (lane_col_ok[j] && urow + 4 * lhe < a.m) ? __builtin_nontemporal_load(&base[off]) : 0.0;
+                                            }
                                     }
-                            }
-                            __builtin_amdgcn_sched_barrier(0);
+                                    if constexpr (wc) {
 #pragma unroll
-                            for (int i = 0; i < EPI_ROWS; ++i)
+                                        for (int i = 0; i < rows; ++i)
 #pragma unroll
-                                for (int r = 0; r < 16; ++r) {
-                                    const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
-                                    double* base = a.D + urow * a.ldd + ec0 + j * 32;
-                                    const int ea = lds_exp[wm * 128 + (ih + i) * 32 + 8 * (r / 4) + (r % 4) + 4 * lhe];
-                                    const double term = ldexp((double)acc[ih + i][j][r], ea + eb[j]);
-                                    if (lane_col_ok[j] && urow + 4 * lhe < a.m)
-                                        __builtin_nontemporal_store(first ? term : (old[i][r] + term), &base[off]);
+                                            for (int r = 0; r < 16; ++r) {
+                                                const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
+                                                const double* cbase = a.Cout + urow * a.ldco + ec0 + j * 32;
+                                                cold[i][r] = (lane_col_ok[j] && urow + 4 * lhe < a.m) ? __builtin_nontemporal_load(&cbase[offc]) : 0.0;
+                                            }
+                                    }
+                                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                                    for (int i = 0; i < rows; ++i) {
+#pragma unroll
+                                        for (int r = 0; r < 16; ++r) {
+                                            const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
+                                            const double term = addend(ih + i, j, r);
+                                            double val = first ? term : (old[i][r] + term);
+                                            if constexpr (fin) {
+                                                val = a.alpha * val;                                   // t1 = fl(alpha d)
+                                                if constexpr (wc) val = val + a.cbeta * cold[i][r];    // fl(t1 + fl(cbeta c))
+                                                double* cbase = a.Cout + urow * a.ldco + ec0 + j * 32;
+                                                if (lane_col_ok[j] && urow + 4 * lhe < a.m) __builtin_nontemporal_store(val, &cbase[offc]);
+                                            } else {
+                                                double* base = a.D + urow * a.ldd + ec0 + j * 32;
+                                                if (lane_col_ok[j] && urow + 4 * lhe < a.m) __builtin_nontemporal_store(val, &base[off]);
+                                            }
+                                        }
+                                    }
+                                    __builtin_amdgcn_sched_barrier(0);
                                 }
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
+                            }
+                        };
+                        if (with_c)
+                            plain(std::integral_constant<int, 1>{}, std::true_type{}, std::true_type{});
+                        else if (last)
+                            plain(std::integral_constant<int, EPI_ROWS>{}, std::false_type{}, std::true_type{});
+                        else
+                            plain(std::integral_constant<int, EPI_ROWS>{}, std::false_type{}, std::false_type{});
                     }
                 }
                 first = 0;
@@ -569,27 +662,32 @@ __global__ __launch_bounds__(256) void k_accumulate(int64_t m, int64_t p, const 
 
 // Step (iv) for a range of tiles whose INT32 chunk sums lie in per-tile dense 256 x 256 blocks (the
 // split-inner schedule); the blocks are cleared after use for the next chunk's integer atomics.
-// A workgroup handles 8 rows of one tile, lanes along the row.
-__global__ __launch_bounds__(256) void k_accumulate_tiles(int tile_begin, int TM, int TP, int64_t m, int64_t p,
-                                                          int32_t* __restrict__ Ct, const int32_t* __restrict__ eA,
-                                                          const int32_t* __restrict__ eB, int shift, int first,
-                                                          double* __restrict__ D, int64_t ldd)
+// A workgroup handles 8 rows of one tile, lanes along the row.  t.finish: step (v) on the result.
+__global__ __launch_bounds__(256) void k_accumulate_tiles(ozk::TileAccArgs t)
 {
     const int local = blockIdx.x / 32, rows8 = blockIdx.x % 32;
     int tm, tp;
-    tile_of_linear(tile_begin + local, TM, TP, tm, tp);
+    tile_of_linear(t.tile_begin + local, t.TM, t.TP, tm, tp);
     const int64_t j = (int64_t)tp * 256 + threadIdx.x;
-    int32_t* c = Ct + (int64_t)local * (256 * 256) + (int64_t)rows8 * 8 * 256 + threadIdx.x;
-    const bool col_ok = j < p;
-    const int eb = col_ok ? eB[j] + shift : 0;
+    int32_t* c = t.Ct + (int64_t)local * (256 * 256) + (int64_t)rows8 * 8 * 256 + threadIdx.x;
+    const bool col_ok = j < t.p;
+    const int eb = col_ok ? t.eB[j] + t.shift : 0;
     for (int q = 0; q < 8; ++q) {
         const int64_t i = (int64_t)tm * 256 + rows8 * 8 + q;
         const int32_t v = c[q * 256];
         c[q * 256] = 0;
-        if (col_ok && i < m) {
-            const double term = ldexp((double)v, eA[i] + eb);
-            double* d = D + i * ldd + j;
-            *d = first ? term : (*d + term);
+        if (col_ok && i < t.m) {
+            const double term = ldexp((double)v, t.eA[i] + eb);
+            double* d = t.D + i * t.ldd + j;
+            double val = t.first ? term : (*d + term);
+            if (t.finish) {
+                val = t.alpha * val;
+                double* out = t.Cout + i * t.ldco + j;
+                if (t.cbeta != 0.0) val = val + t.cbeta * *out;
+                *out = val;
+            } else {
+                *d = val;
+            }
         }
     }
 }
@@ -711,14 +809,13 @@ hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc
     return hipGetLastError();
 }
 
-hipError_t launch_accumulate_tiles(int tile_begin, int tile_count, int64_t m, int64_t p, int32_t* Ctiles,
-                                   const int32_t* eA, const int32_t* eB, int shift, int first, double* D,
-                                   int64_t ldd, hipStream_t st)
+hipError_t launch_accumulate_tiles(const TileAccArgs& t_in, hipStream_t st)
 {
-    if (tile_count <= 0) return hipSuccess;
-    const int TM = (int)(ozl::rows_padded(m) / ozl::TILE_R), TP = (int)(ozl::rows_padded(p) / ozl::TILE_R);
-    hipLaunchKernelGGL(k_accumulate_tiles, dim3((unsigned)tile_count * 32u), dim3(256), 0, st, tile_begin, TM, TP, m, p,
-                       Ctiles, eA, eB, shift, first, D, ldd);
+    if (t_in.tile_count <= 0) return hipSuccess;
+    TileAccArgs t = t_in;
+    t.TM = (int)(ozl::rows_padded(t.m) / ozl::TILE_R);
+    t.TP = (int)(ozl::rows_padded(t.p) / ozl::TILE_R);
+    hipLaunchKernelGGL(k_accumulate_tiles, dim3((unsigned)t.tile_count * 32u), dim3(256), 0, st, t);
     return hipGetLastError();
 }
 

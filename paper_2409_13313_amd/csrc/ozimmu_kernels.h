@@ -8,12 +8,13 @@
 namespace ozk {
 
 // Step (i): row exponents + slices of A.  split_mode 0: round to nearest, ceil exponent (Algorithm 8);
-// 1: bit-mask digits, floor exponent (Algorithm 3).
+// 1: bit-mask digits, floor exponent (Algorithm 3).  SA is a whole stack (ozl::stack_bytes): slices, prefix row
+// sums, trailer; `offset` is the stack's offset c (stored byte = slice integer + c; 63 needs |q| <= 64).
 hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int split_mode,
-                          int8_t* SA, int32_t* eA, hipStream_t st);
+                          int offset, int8_t* SA, int32_t* eA, hipStream_t st);
 // Step (ii): column exponents + slices of B (the same applied to B^T).
 hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int split_mode,
-                          int8_t* SB, int32_t* eB, hipStream_t st);
+                          int offset, int8_t* SB, int32_t* eB, hipStream_t st);
 // Algorithm 5: round-to-nearest slices with one scale per slice.  e holds k arrays of exponents (slice-major);
 // rem is scratch for the remainders: m x inner_padded(n) doubles for A, n x p doubles for B.
 hipError_t launch_split_A_per_slice(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int8_t* SA,
@@ -25,6 +26,11 @@ hipError_t launch_export(int64_t rows, int64_t n, int k, const int8_t* packed, i
 struct GemmArgs {
     const int8_t* SA;      // packed stack of A slices
     const int8_t* SB;      // packed stack of B slices
+    const int32_t* PA;     // prefix sums over the slices of the row sums of the stored bytes of A: k arrays of pstrideA
+    const int32_t* PB;     // the same for B
+    int64_t pstrideA, pstrideB;  // = padded rows of the stack
+    const int32_t* cA;     // device: offset of the A stack (stored byte = slice integer + offset)
+    const int32_t* cB;     // device: offset of the B stack
     int64_t strideA;       // bytes per A slice
     int64_t strideB;       // bytes per B slice
     int KT;                // inner tiles per slice
@@ -46,6 +52,12 @@ struct GemmArgs {
     int dma_ok;            // D is 16-byte aligned and ldd even: rows of D can be copied 16 bytes per lane
     int beta;              // shift of group g is 2 - beta * g
     int first;             // D is zero before the first chunk: overwrite
+    // step (v) in the epilogue of a tile's last chunk (fused modes): out = fl(fl(alpha d) + fl(cbeta c_old)) into
+    // Cout (leading dimension ldco); cbeta == 0: c_old is not read, and Cout must be D itself
+    int finish;
+    double alpha, cbeta;
+    double* Cout;
+    int64_t ldco;
     unsigned* sync;        // 8 x 16 counters, zeroed by launch_gemm: [16 x] per-XCD soft barrier, [1] whole grid
     int spin_limit;        // polls before a soft barrier gives up
     int num_cu;            // compute units of the device: the persistent grid has one workgroup on each
@@ -63,11 +75,24 @@ hipError_t launch_fill_zero_i32_2d(int64_t m, int64_t p, int32_t* C, int64_t ldc
 // Step (iv) alone.
 hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA,
                              const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st);
-// Step (iv) for the tiles tile_begin .. tile_begin + tile_count - 1 (band order) from per-tile 256 x 256 INT32
-// blocks, which are left zeroed.
-hipError_t launch_accumulate_tiles(int tile_begin, int tile_count, int64_t m, int64_t p, int32_t* Ctiles,
-                                   const int32_t* eA, const int32_t* eB, int shift, int first, double* D,
-                                   int64_t ldd, hipStream_t st);
+// Step (iv) for the tiles tile_begin .. tile_begin + tile_count - 1 (band order) of one chunk (group g, slices
+// s0 .. s1 of A) from per-tile 256 x 256 INT32 blocks holding the chunk sums; the blocks are left zeroed.
+// finish: step (v) as in GemmArgs.
+struct TileAccArgs {
+    int tile_begin, tile_count, TM, TP;  // TM, TP are filled in by the launcher
+    int64_t m, p;
+    int32_t* Ct;
+    const int32_t* eA;
+    const int32_t* eB;
+    int shift, first;
+    double* D;
+    int64_t ldd;
+    int finish;
+    double alpha, cbeta;
+    double* Cout;
+    int64_t ldco;
+};
+hipError_t launch_accumulate_tiles(const TileAccArgs& t, hipStream_t st);
 // Step (v): C <- alpha D + beta C (beta == 0: C not read).
 hipError_t launch_axpby(int64_t m, int64_t p, double alpha, const double* D, int64_t ldd, double beta, double* C,
                         int64_t ldc, hipStream_t st);

@@ -14,6 +14,24 @@
 // global-load-to-LDS instruction can do: lane i lands at base + 16 i), and the
 // 16-byte operand fetches of v_mfma_i32_32x32x32_i8 (consecutive rows, one
 // logical chunk) of any 16 consecutive lanes cover all 64 LDS banks once.
+//
+// Stored bytes are OFFSET-ENCODED: a stack carries one offset c (0 or 63) and
+// the byte of an element is q + c, q being the slice integer of the method
+// (inner padding is q = 0 like any zero; padding ROWS may hold anything that is
+// consistent with their row sums: their results are never stored).  Round-to-nearest
+// slices obey -64 <= q <= 64, so with c = 63 every byte lies in [-1, 127] and
+// practically all are non-negative: the matrix cores draw measurably less
+// power on operands of one sign (their sustained clock is higher), and
+//   sum_l (a'_l - cA)(b'_l - cB) = sum_l a'_l b'_l - cB sum_l a'_l - cA sum_l b'_l + N cA cB
+// (l over the N = inner_padded(n) stored positions)
+// gives the product of the slice integers back exactly from the product of the
+// stored bytes and the row sums of the stored bytes (INT32, wrap-around exact:
+// |a'|, |b'| <= 127 keeps even the uncorrected sums of a chunk below 2^31 under
+// the paper's bound on the chunk length).  Behind the k slices a stack therefore
+// holds, for every padded row R, the PREFIX sums P[s][R] = sum over slices
+// 1..s+1 and all inner l of the stored bytes (k arrays of rows_padded INT32; the
+// sum over any range of consecutive slices is a difference of two entries), and
+// a 256-byte trailer whose first INT32 is c.
 #pragma once
 #include <cstdint>
 #include <cstddef>
@@ -36,6 +54,19 @@ __host__ __device__ inline int64_t rowblock_bytes(int64_t KT) { return KT * TILE
 __host__ __device__ inline int64_t slice_bytes(int64_t rows, int64_t n)
 {
     return rows_padded(rows) / TILE_R * rowblock_bytes(inner_padded(n) / TILE_K);
+}
+
+// a whole stack of k slices: slices, prefix row sums, trailer
+__host__ __device__ inline int64_t sums_bytes(int64_t rows, int64_t k) { return round_up(4 * k * rows_padded(rows), 256); }
+constexpr int64_t TRAILER_BYTES = 256;
+__host__ __device__ inline int64_t sums_offset(int64_t rows, int64_t n, int64_t k) { return k * slice_bytes(rows, n); }
+__host__ __device__ inline int64_t trailer_offset(int64_t rows, int64_t n, int64_t k)
+{
+    return sums_offset(rows, n, k) + sums_bytes(rows, k);
+}
+__host__ __device__ inline int64_t stack_bytes(int64_t rows, int64_t n, int64_t k)
+{
+    return trailer_offset(rows, n, k) + TRAILER_BYTES;
 }
 
 __host__ __device__ inline int swizzle(int r, int c) { return c ^ ((r >> 2) & 3); }

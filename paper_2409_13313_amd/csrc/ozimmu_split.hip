@@ -12,12 +12,18 @@
 // which yields the same integers: y_s is remainder / grid_s at every step.
 // Both kernels are HBM-bound: 8 bytes read (A twice when its row does not stay
 // in cache) and k bytes written per element.
+// The bytes stored are q_s + c (c = offset of the stack, see ozimmu_layout.h;
+// inner padding counts as a real zero, padding rows of A are all zero bytes); with them go the prefix sums over the slices
+// of the row sums of the stored bytes, which the GEMM epilogue needs to take the
+// offsets out again.
 #include "ozimmu_kernels.h"
 #include "ozimmu_layout.h"
 
 namespace {
 
 using namespace ozl;
+
+constexpr int OZIMMU_MAX_SLICES_DEV = 20;  // OZIMMU_MAX_SLICES of the C ABI
 
 // ceil(log2 x) key of a positive finite double given as its bit pattern,
 // monotone in x so that maxima can be taken on keys:
@@ -61,23 +67,31 @@ __device__ inline uint64_t wave_max_u64(uint64_t v)
     return v;
 }
 
-// k slices of 4 consecutive inner elements, packed one dword per slice.
-// y[] enters as x * 2^(beta-1-e).  out advances by slice_stride bytes per slice.
-template <bool MASK>
-__device__ inline void emit_slices4(double y0, double y1, double y2, double y3, int k, double two_beta,
-                                    int8_t* out, int64_t slice_stride)
+__device__ inline int wave_sum_i32(int v)
 {
-    for (int s = 0; s < k; ++s) {
-        double q0 = digit<MASK>(y0), q1 = digit<MASK>(y1), q2 = digit<MASK>(y2), q3 = digit<MASK>(y3);
-        uint32_t w = ((uint32_t)(int)q0 & 0xffu) | (((uint32_t)(int)q1 & 0xffu) << 8) |
-                     (((uint32_t)(int)q2 & 0xffu) << 16) | (((uint32_t)(int)q3 & 0xffu) << 24);
-        *reinterpret_cast<uint32_t*>(out) = w;
-        out += slice_stride;
-        y0 = (y0 - q0) * two_beta;
-        y1 = (y1 - q1) * two_beta;
-        y2 = (y2 - q2) * two_beta;
-        y3 = (y3 - q3) * two_beta;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// One slice of 4 consecutive inner elements: digits of y[], remainders updated in place, the 4 stored
+// bytes (digit + c, c = the stack's offset) packed into a dword.  Returns the dword; *sum receives the sum
+// of the 4 stored bytes.  Inner padding (l >= n) enters as y = 0 like a real zero and is stored as c.
+template <bool MASK>
+__device__ inline uint32_t slice_word4(double* y, int c, double two_beta, int* sum)
+{
+    uint32_t w = 0;
+    int sm = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const double q = digit<MASK>(y[j]);
+        const int b = (int)q + c;
+        w |= ((uint32_t)b & 0xffu) << (8 * j);
+        sm += b;
+        y[j] = (y[j] - q) * two_beta;
     }
+    *sum = sm;
+    return w;
 }
 
 // ---------------------------------------------------------------------------
@@ -90,17 +104,22 @@ __device__ inline void emit_slices4(double y0, double y1, double y2, double y3, 
 // ---------------------------------------------------------------------------
 template <bool VEC, bool MASK>
 __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const double* __restrict__ A, int64_t lda,
-                                                 int k, int beta, int8_t* __restrict__ SA, int32_t* __restrict__ eA,
-                                                 int64_t Npad, int64_t slice_stride)
+                                                 int k, int beta, int c, int8_t* __restrict__ SA,
+                                                 int32_t* __restrict__ eA, int32_t* __restrict__ P,
+                                                 int32_t* __restrict__ trailer, int64_t Npad, int64_t Rpad,
+                                                 int64_t slice_stride)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t R = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    __shared__ int lsum[4][OZIMMU_MAX_SLICES_DEV][64];  // per-lane sums of the stored bytes, per slice
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t R = (int64_t)blockIdx.x * 4 + w;
     const int64_t KT = Npad / TILE_K;
+    if (blockIdx.x == 0 && threadIdx.x == 0) trailer[0] = c;
 
-    if (R >= m) {  // padding row: zeros in every slice
+    if (R >= m) {  // padding row: zeros in every slice, zero sums
         for (int64_t l = 4 * lane; l < Npad; l += 256)
             for (int s = 0; s < k; ++s)
                 *reinterpret_cast<uint32_t*>(SA + s * slice_stride + packed_offset(R, l, KT)) = 0u;
+        if (lane < k) P[(int64_t)lane * Rpad + R] = 0;
         return;
     }
     const double* row = A + R * lda;
@@ -131,12 +150,25 @@ __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const dou
     if (lane == 0) eA[R] = e;
     const int sc = beta - 1 - e;
     const double two_beta = (double)(1 << beta);
+    for (int s = 0; s < k; ++s) lsum[w][s][lane] = 0;
 
     for (int64_t l = 4 * lane; l < Npad; l += 256) {
-        double v[4];
-        load4(l, v);
-        emit_slices4<MASK>(ldexp(v[0], sc), ldexp(v[1], sc), ldexp(v[2], sc), ldexp(v[3], sc), k, two_beta,
-                     SA + packed_offset(R, l, KT), slice_stride);
+        double y[4];
+        load4(l, y);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) y[j] = ldexp(y[j], sc);
+        int8_t* out = SA + packed_offset(R, l, KT);
+        for (int s = 0; s < k; ++s) {
+            int sm;
+            *reinterpret_cast<uint32_t*>(out) = slice_word4<MASK>(y, c, two_beta, &sm);
+            out += slice_stride;
+            lsum[w][s][lane] += sm;
+        }
+    }
+    int run = 0;
+    for (int s = 0; s < k; ++s) {
+        run += wave_sum_i32(lsum[w][s][lane]);
+        if (lane == 0) P[(int64_t)s * Rpad + R] = run;
     }
 }
 
@@ -152,20 +184,25 @@ __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const dou
 // ---------------------------------------------------------------------------
 template <int GROUPS, bool VEC, bool MASK>
 __global__ __launch_bounds__(256) void k_split_A_row(int64_t m, int64_t n, const double* __restrict__ A, int64_t lda,
-                                                     int k, int beta, int8_t* __restrict__ SA,
-                                                     int32_t* __restrict__ eA, int64_t Npad, int64_t slice_stride)
+                                                     int k, int beta, int c, int8_t* __restrict__ SA,
+                                                     int32_t* __restrict__ eA, int32_t* __restrict__ P,
+                                                     int32_t* __restrict__ trailer, int64_t Npad, int64_t Rpad,
+                                                     int64_t slice_stride)
 {
     __shared__ uint64_t part[4];
+    __shared__ int wsum[4][OZIMMU_MAX_SLICES_DEV];  // per-wave sums of the stored bytes, per slice
     const int t = threadIdx.x;
     // the grid has rows_padded(m) workgroups, a multiple of 256, so b / 8 and b % 8 cover whole groups of 32 rows
     const int64_t b = blockIdx.x, x = b % 8, j = b / 8;
     const int64_t R = ((j / 4) * 8 + x) * 4 + (j % 4);
     const int64_t KT = Npad / TILE_K;
+    if (b == 0 && t == 0) trailer[0] = c;
 
-    if (R >= m) {  // padding row: zeros in every slice
+    if (R >= m) {  // padding row: zeros in every slice, zero sums
         for (int64_t l = 4 * t; l < Npad; l += 1024)
             for (int s = 0; s < k; ++s)
                 *reinterpret_cast<uint32_t*>(SA + s * slice_stride + packed_offset(R, l, KT)) = 0u;
+        if (t < k) P[(int64_t)t * Rpad + R] = 0;
         return;
     }
     const double* row = A + R * lda;
@@ -176,8 +213,8 @@ __global__ __launch_bounds__(256) void k_split_A_row(int64_t m, int64_t n, const
         const int64_t l = 4 * t + 1024 * g;
         if (VEC && l + 3 < n) {
             double2 a = *reinterpret_cast<const double2*>(row + l);
-            double2 c = *reinterpret_cast<const double2*>(row + l + 2);
-            v[g][0] = a.x; v[g][1] = a.y; v[g][2] = c.x; v[g][3] = c.y;
+            double2 d = *reinterpret_cast<const double2*>(row + l + 2);
+            v[g][0] = a.x; v[g][1] = a.y; v[g][2] = d.x; v[g][3] = d.y;
         } else {
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[g][q] = (l + q < n) ? row[l + q] : 0.0;
@@ -200,11 +237,32 @@ __global__ __launch_bounds__(256) void k_split_A_row(int64_t m, int64_t n, const
     const int sc = beta - 1 - e;
     const double two_beta = (double)(1 << beta);
 #pragma unroll
-    for (int g = 0; g < GROUPS; ++g) {
-        const int64_t l = 4 * t + 1024 * g;
-        if (l < Npad)
-            emit_slices4<MASK>(ldexp(v[g][0], sc), ldexp(v[g][1], sc), ldexp(v[g][2], sc), ldexp(v[g][3], sc), k,
-                               two_beta, SA + packed_offset(R, l, KT), slice_stride);
+    for (int g = 0; g < GROUPS; ++g)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[g][q] = ldexp(v[g][q], sc);
+    // slice after slice over the whole row (the remainders stay in v), so that one sum per slice is reduced
+    for (int s = 0; s < k; ++s) {
+        int tsum = 0;
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) {
+            const int64_t l = 4 * t + 1024 * g;
+            if (l < Npad) {
+                int sm;
+                *reinterpret_cast<uint32_t*>(SA + s * slice_stride + packed_offset(R, l, KT)) =
+                    slice_word4<MASK>(v[g], c, two_beta, &sm);
+                tsum += sm;
+            }
+        }
+        tsum = wave_sum_i32(tsum);
+        if ((t & 63) == 0) wsum[t >> 6][s] = tsum;
+    }
+    __syncthreads();
+    if (t == 0) {
+        int run = 0;
+        for (int s = 0; s < k; ++s) {
+            run += wsum[0][s] + wsum[1][s] + wsum[2][s] + wsum[3][s];
+            P[(int64_t)s * Rpad + R] = run;
+        }
     }
 }
 
@@ -253,6 +311,18 @@ __global__ void k_decode_keys(int64_t count, int32_t* e)
     if (i < count) e[i] = key_to_exp<MASK>((uint32_t)e[i]);
 }
 
+// per-slice sums of a stack (k arrays of Rpad entries) -> prefix sums over the slices, in place
+__global__ void k_prefix_sums(int64_t Rpad, int k, int32_t* P)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= Rpad) return;
+    int run = 0;
+    for (int s = 0; s < k; ++s) {
+        run += P[(int64_t)s * Rpad + i];
+        P[(int64_t)s * Rpad + i] = run;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // B, pass 2: slices, transposed so that the inner index becomes contiguous.
 // A workgroup handles 128 inner rows x 64 columns.  Reads: lane = column
@@ -267,63 +337,70 @@ constexpr int PITCH = 33;  // dwords per column row in LDS (32 data + 1 pad)
 
 template <bool MASK>
 __global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const double* __restrict__ B, int64_t ldb,
-                                                 int k, int beta, int8_t* __restrict__ SB,
-                                                 const int32_t* __restrict__ eB, int64_t Npad, int64_t slice_stride)
+                                                 int k, int beta, int c, int8_t* __restrict__ SB,
+                                                 const int32_t* __restrict__ eB, int32_t* __restrict__ P,
+                                                 int32_t* __restrict__ trailer, int64_t Npad, int64_t Rpad,
+                                                 int64_t slice_stride, int blocks_per_wg)
 {
     __shared__ uint32_t tile[SBATCH][64 * PITCH];
+    __shared__ int colsum[OZIMMU_MAX_SLICES_DEV][64];  // sums of the stored bytes per slice and column
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-    const int64_t l0 = (int64_t)blockIdx.x * 128;  // inner offset of this block (128 inner rows)
     const int64_t j0 = (int64_t)blockIdx.y * 64;      // first column (= packed row)
     const int64_t j = j0 + lane;
     const int64_t KT = Npad / TILE_K;
     const double two_beta = (double)(1 << beta);
-
-    double y[32];
-    {
-        const bool col_ok = j < p;
-        const int sc = beta - 1 - (col_ok ? eB[j] : 0);
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            int64_t l = l0 + w * 32 + i;
-            double v = (col_ok && l < n) ? B[l * ldb + j] : 0.0;
-            y[i] = ldexp(v, sc);
-        }
-    }
+    const bool col_ok = j < p;
+    const int sc = beta - 1 - (col_ok ? eB[j] : 0);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && t == 0) trailer[0] = c;
+    for (int i = t; i < k * 64; i += 256) colsum[i / 64][i % 64] = 0;
     // write-out mapping: 8 lanes per column row, 32 column rows per pass
     const int oc = t & 7, orow = t >> 3;
+    __syncthreads();
 
-    for (int sb = 0; sb < k; sb += SBATCH) {
-        const int ns = (k - sb) < SBATCH ? (k - sb) : SBATCH;
-        for (int s = 0; s < ns; ++s) {
+    // blocks_per_wg consecutive blocks of 128 inner rows (fewer atomics on the sums than one block each)
+    for (int blk = 0; blk < blocks_per_wg; ++blk) {
+        const int64_t l0 = ((int64_t)blockIdx.x * blocks_per_wg + blk) * 128;  // inner offset of this block
+        if (l0 >= Npad) break;
+        double y[32];
 #pragma unroll
-            for (int ii = 0; ii < 8; ++ii) {
-                uint32_t wv = 0;
+        for (int i = 0; i < 32; ++i) {
+            const int64_t l = l0 + w * 32 + i;
+            const double v = (col_ok && l < n) ? B[l * ldb + j] : 0.0;
+            y[i] = ldexp(v, sc);
+        }
+        for (int sb = 0; sb < k; sb += SBATCH) {
+            const int ns = (k - sb) < SBATCH ? (k - sb) : SBATCH;
+            for (int s = 0; s < ns; ++s) {
+                int tsum = 0;
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    double q = digit<MASK>(y[4 * ii + b]);
-                    wv |= ((uint32_t)(int)q & 0xffu) << (8 * b);
-                    y[4 * ii + b] = (y[4 * ii + b] - q) * two_beta;
+                for (int ii = 0; ii < 8; ++ii) {
+                    int sm;
+                    tile[s][lane * PITCH + w * 8 + ii] = slice_word4<MASK>(&y[4 * ii], c, two_beta, &sm);
+                    tsum += sm;
                 }
-                tile[s][lane * PITCH + w * 8 + ii] = wv;
+                atomicAdd(&colsum[sb + s][lane], tsum);
             }
-        }
-        __syncthreads();
-        for (int s = 0; s < ns; ++s) {
+            __syncthreads();
+            for (int s = 0; s < ns; ++s) {
 #pragma unroll
-            for (int pass = 0; pass < 2; ++pass) {
-                int jr = orow + 32 * pass;
-                const uint32_t* src = &tile[s][jr * PITCH + oc * 4];
-                uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
-                int8_t* dst = SB + (int64_t)(sb + s) * slice_stride + packed_offset(j0 + jr, l0 + oc * CHUNK, KT);
-                // whole 128-byte lines that nobody reads before the GEMM: non-temporal (4 % on this kernel; the
-                // 64-byte row segments of the A kernels need the L2 to merge them and stay temporal)
-                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-                const u32x4 vv = {v.x, v.y, v.z, v.w};
-                __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>(dst));
+                for (int pass = 0; pass < 2; ++pass) {
+                    int jr = orow + 32 * pass;
+                    const uint32_t* src = &tile[s][jr * PITCH + oc * 4];
+                    uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
+                    int8_t* dst = SB + (int64_t)(sb + s) * slice_stride + packed_offset(j0 + jr, l0 + oc * CHUNK, KT);
+                    // whole 128-byte lines that nobody reads before the GEMM: non-temporal (4 % on this kernel; the
+                    // 64-byte row segments of the A kernels need the L2 to merge them and stay temporal)
+                    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                    const u32x4 vv = {v.x, v.y, v.z, v.w};
+                    __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>(dst));
+                }
             }
+            __syncthreads();
         }
-        __syncthreads();
     }
+    // integer sums: order-free, hence deterministic (P was zeroed; k_prefix_sums finishes)
+    for (int i = t; i < k * 64; i += 256)
+        if (colsum[i / 64][i % 64] != 0) atomicAdd(&P[(int64_t)(i / 64) * Rpad + j0 + (i % 64)], colsum[i / 64][i % 64]);
 }
 
 // ---------------------------------------------------------------------------
@@ -338,12 +415,14 @@ __global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const dou
 template <bool VEC>
 __global__ __launch_bounds__(256) void k_split_A_ps(int64_t m, int64_t n, const double* __restrict__ A, int64_t lda,
                                                     int k, int beta, int8_t* __restrict__ SA,
-                                                    int32_t* __restrict__ eA, double* __restrict__ rem, int64_t Npad,
+                                                    int32_t* __restrict__ eA, double* __restrict__ rem,
+                                                    int32_t* __restrict__ trailer, int64_t Npad,
                                                     int64_t slice_stride)
 {
     const int lane = threadIdx.x & 63;
     const int64_t R = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t KT = Npad / TILE_K;
+    if (blockIdx.x == 0 && threadIdx.x == 0) trailer[0] = 0;  // slices with a scale each are stored without offset
 
     if (R >= m) {  // padding row: zeros in every slice
         for (int64_t l = 4 * lane; l < Npad; l += 256)
@@ -479,30 +558,41 @@ __global__ __launch_bounds__(256) void k_split_B_ps(int64_t n, int64_t p, const 
 
 // Unpack: one thread per output byte, out[s][row][l].
 __global__ __launch_bounds__(256) void k_export(int64_t rows, int64_t n, int k, const int8_t* __restrict__ packed,
-                                                int8_t* __restrict__ out, int64_t KT, int64_t slice_stride)
+                                                const int32_t* __restrict__ trailer, int8_t* __restrict__ out,
+                                                int64_t KT, int64_t slice_stride)
 {
     int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     int64_t total = (int64_t)k * rows * n;
     if (idx >= total) return;
     int64_t l = idx % n, R = (idx / n) % rows, s = idx / (n * rows);
-    out[idx] = packed[s * slice_stride + packed_offset(R, l, KT)];
+    out[idx] = (int8_t)(packed[s * slice_stride + packed_offset(R, l, KT)] - trailer[0]);  // stored byte = q + c
 }
 
 }  // namespace
 
 namespace ozk {
 
+// k_set_i32: one INT32 (the offset in the trailer of a stack whose split kernels do not write it themselves)
+}  // namespace ozk
+namespace {
+__global__ void k_set_i32(int32_t* x, int32_t v) { x[0] = v; }
+}  // namespace
+namespace ozk {
+
 hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int split_mode,
-                          int8_t* SA, int32_t* eA, hipStream_t st)
+                          int offset, int8_t* SA, int32_t* eA, hipStream_t st)
 {
     const int64_t Rpad = ozl::rows_padded(m), Npad = ozl::inner_padded(n);
     const int64_t stride = ozl::slice_bytes(m, n);
+    int32_t* P = reinterpret_cast<int32_t*>(SA + ozl::sums_offset(m, n, k));
+    int32_t* trailer = reinterpret_cast<int32_t*>(SA + ozl::trailer_offset(m, n, k));
     const bool vec = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 2 == 0);
     const bool mask = split_mode != 0;
     if (Npad <= 16384) {  // the row fits the registers of one workgroup: single pass over A
         dim3 grid((unsigned)Rpad), block(256);
-#define OZ_LAUNCH_ROW(G, V, M)                                                                                  \
-    hipLaunchKernelGGL((k_split_A_row<G, V, M>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride)
+#define OZ_LAUNCH_ROW(G, V, M)                                                                                    \
+    hipLaunchKernelGGL((k_split_A_row<G, V, M>), grid, block, 0, st, m, n, A, lda, k, beta, offset, SA, eA, P, trailer, \
+                       Npad, Rpad, stride)
 #define OZ_PICK_ROW(G)                         \
     do {                                       \
         if (vec && !mask) OZ_LAUNCH_ROW(G, true, false);       \
@@ -519,34 +609,49 @@ hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, in
         return hipGetLastError();
     }
     dim3 grid((unsigned)(Rpad / 4)), block(256);
+#define OZ_LAUNCH_A(V, M)                                                                                          \
+    hipLaunchKernelGGL((k_split_A<V, M>), grid, block, 0, st, m, n, A, lda, k, beta, offset, SA, eA, P, trailer, Npad, \
+                       Rpad, stride)
     if (vec && !mask)
-        hipLaunchKernelGGL((k_split_A<true, false>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
+        OZ_LAUNCH_A(true, false);
     else if (!vec && !mask)
-        hipLaunchKernelGGL((k_split_A<false, false>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
+        OZ_LAUNCH_A(false, false);
     else if (vec)
-        hipLaunchKernelGGL((k_split_A<true, true>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
+        OZ_LAUNCH_A(true, true);
     else
-        hipLaunchKernelGGL((k_split_A<false, true>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, Npad, stride);
+        OZ_LAUNCH_A(false, true);
+#undef OZ_LAUNCH_A
     return hipGetLastError();
 }
 
 hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int split_mode,
-                          int8_t* SB, int32_t* eB, hipStream_t st)
+                          int offset, int8_t* SB, int32_t* eB, hipStream_t st)
 {
     const int64_t Rpad = ozl::rows_padded(p), Npad = ozl::inner_padded(n);
     const int64_t stride = ozl::slice_bytes(p, n);
+    int32_t* P = reinterpret_cast<int32_t*>(SB + ozl::sums_offset(p, n, k));
+    int32_t* trailer = reinterpret_cast<int32_t*>(SB + ozl::trailer_offset(p, n, k));
     hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p,
                        reinterpret_cast<uint32_t*>(eB), 0u);
+    const int64_t nsums = (int64_t)k * Rpad;
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nsums + 255) / 256)), dim3(256), 0, st, nsums,
+                       reinterpret_cast<uint32_t*>(P), 0u);
     dim3 gmax((unsigned)((n + LCH - 1) / LCH), (unsigned)((p + 63) / 64));
     hipLaunchKernelGGL(k_colmax_B, gmax, dim3(256), 0, st, n, p, B, ldb, reinterpret_cast<uint32_t*>(eB));
-    dim3 grid((unsigned)(Npad / 128), (unsigned)(Rpad / 64));
+    // a workgroup takes 4 consecutive blocks of 128 inner rows once there are enough blocks to fill the chip anyway
+    const int64_t blocks = Npad / 128;
+    const int per_wg = blocks >= 32 ? 4 : 1;
+    dim3 grid((unsigned)((blocks + per_wg - 1) / per_wg), (unsigned)(Rpad / 64));
     if (split_mode == 0) {
         hipLaunchKernelGGL(k_decode_keys<false>, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
-        hipLaunchKernelGGL(k_split_B<false>, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, SB, eB, Npad, stride);
+        hipLaunchKernelGGL(k_split_B<false>, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, offset, SB, eB, P, trailer,
+                           Npad, Rpad, stride, per_wg);
     } else {
         hipLaunchKernelGGL(k_decode_keys<true>, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
-        hipLaunchKernelGGL(k_split_B<true>, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, SB, eB, Npad, stride);
+        hipLaunchKernelGGL(k_split_B<true>, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, offset, SB, eB, P, trailer,
+                           Npad, Rpad, stride, per_wg);
     }
+    hipLaunchKernelGGL(k_prefix_sums, dim3((unsigned)((Rpad + 255) / 256)), dim3(256), 0, st, Rpad, k, P);
     return hipGetLastError();
 }
 
@@ -555,12 +660,15 @@ hipError_t launch_split_A_per_slice(int64_t m, int64_t n, const double* A, int64
 {
     const int64_t Rpad = ozl::rows_padded(m), Npad = ozl::inner_padded(n);
     const int64_t stride = ozl::slice_bytes(m, n);
+    int32_t* trailer = reinterpret_cast<int32_t*>(SA + ozl::trailer_offset(m, n, k));
     const bool vec = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 2 == 0);
     dim3 grid((unsigned)(Rpad / 4)), block(256);
     if (vec)
-        hipLaunchKernelGGL((k_split_A_ps<true>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, rem, Npad, stride);
+        hipLaunchKernelGGL((k_split_A_ps<true>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, rem, trailer, Npad,
+                           stride);
     else
-        hipLaunchKernelGGL((k_split_A_ps<false>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, rem, Npad, stride);
+        hipLaunchKernelGGL((k_split_A_ps<false>), grid, block, 0, st, m, n, A, lda, k, beta, SA, eA, rem, trailer, Npad,
+                           stride);
     return hipGetLastError();
 }
 
@@ -569,6 +677,8 @@ hipError_t launch_split_B_per_slice(int64_t n, int64_t p, const double* B, int64
 {
     const int64_t Rpad = ozl::rows_padded(p), Npad = ozl::inner_padded(n);
     const int64_t stride = ozl::slice_bytes(p, n);
+    hipLaunchKernelGGL(k_set_i32, dim3(1), dim3(1), 0, st,
+                       reinterpret_cast<int32_t*>(SB + ozl::trailer_offset(p, n, k)), 0);
     uint32_t* keys = reinterpret_cast<uint32_t*>(eB);  // k arrays of p keys, decoded in place at the end
     const int64_t nk = (int64_t)k * p;
     hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, st, nk, keys, 0u);
@@ -588,7 +698,8 @@ hipError_t launch_export(int64_t rows, int64_t n, int k, const int8_t* packed, i
     const int64_t Npad = ozl::inner_padded(n);
     const int64_t total = (int64_t)k * rows * n;
     if (total == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_export, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, rows, n, k, packed, out,
+    hipLaunchKernelGGL(k_export, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, rows, n, k, packed,
+                       reinterpret_cast<const int32_t*>(packed + ozl::trailer_offset(rows, n, k)), out,
                        Npad / ozl::TILE_K, ozl::slice_bytes(rows, n));
     return hipGetLastError();
 }

@@ -66,14 +66,18 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 8, fake, 16, None) == -4           # workspace too small
     assert lib.ozimmu_dgemm(4, 2 ** 29 + 1, 4, fake, 2 ** 30, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -2
     assert lib.ozimmu_dgemm(0, 4, 4, None, 4, None, 4, None, 4, 8, None, 0, None) == 0             # empty: nothing to do
-    # workspace = scratch + exponents + k padded slices of A and of B (rows padded to 256, inner index to 256)
-    # + one INT32 block of 256 x 256 per output tile, for at most 128 tiles
+    # workspace = scratch + exponents + the two slice stacks + one INT32 block of 256 x 256 per output tile, for at
+    # most 128 tiles.  A stack = k padded slices (rows padded to 256, inner index to 256) + k arrays of padded-rows
+    # INT32 row sums (rounded up to 256 bytes) + a 256-byte trailer
     blk = 4 * 256 * 256
-    assert lib.ozimmu_workspace_bytes(256, 128, 256, 8) == 512 + 2 * 1024 + 2 * 8 * 256 * 256 + blk
-    assert lib.ozimmu_workspace_bytes(257, 257, 1, 3) == 512 + 1280 + 256 + 3 * 512 * 512 + 3 * 256 * 512 + 2 * blk
-    big = lib.ozimmu_workspace_bytes(4096, 256, 4096, 1)       # 256 tiles: blocks for 128 of them
-    assert big == 512 + 2 * 4 * 4096 + 2 * 4096 * 256 + 128 * blk
 
+    def stack(rows_padded, inner_padded, k):
+        return k * rows_padded * inner_padded + -(-4 * k * rows_padded // 256) * 256 + 256
+
+    assert lib.ozimmu_workspace_bytes(256, 128, 256, 8) == 512 + 2 * 1024 + 2 * stack(256, 256, 8) + blk
+    assert lib.ozimmu_workspace_bytes(257, 257, 1, 3) == 512 + 1280 + 256 + stack(512, 512, 3) + stack(256, 512, 3) + 2 * blk
+    big = lib.ozimmu_workspace_bytes(4096, 256, 4096, 1)       # 256 tiles: blocks for 128 of them
+    assert big == 512 + 2 * 4 * 4096 + 2 * stack(4096, 256, 1) + 128 * blk
 
 def test_limits_are_reported_as_dimension_errors(lib):
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int

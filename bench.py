@@ -21,8 +21,9 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA peak, 5.0 POP/s
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch of the GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script, scaled by the same counters on a plain copy (see profiles/k_gemm_16384_k8_traffic.md)
+# Bytes per launch of the GEMM kernel at the L2 / fabric boundary, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this script, each scaled by the same counter on a plain copy (profiles/k_gemm_16384_k8_traffic.md).
+# Counters cannot be read from inside this process: the figure exists for the shapes profiled, else null.
 MEASURED_TRAFFIC_BYTES = {(16384, 16384, 16384, 8): 247.1e9 + 17.2e9}
 
 
@@ -74,6 +75,7 @@ def main() -> int:
     ap.add_argument("--no-accuracy", action="store_true")
     ap.add_argument("--no-native", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the register-only MFMA rate measurement")
+    ap.add_argument("--no-small", action="store_true", help="skip the single-call latency of the 256^3 case")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of A (known size) so that a rocprofv3 --pmc run "
                          "can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -180,6 +182,11 @@ def main() -> int:
             "avg_launch_ms": round(gemm_ms, 4),
             "ops_per_launch": int_ops,
             "traffic": MEASURED_TRAFFIC_BYTES.get((m, n, p, k)),
+            "traffic_note": ("FETCH_SIZE + WRITE_SIZE of one launch, rocprofv3 --pmc, copy-calibrated "
+                             "(profiles/k_gemm_16384_k8_traffic.md)" if (m, n, p, k) in MEASURED_TRAFFIC_BYTES else
+                             "null: no rocprofv3 --pmc run of this shape is on file (hardware counters cannot be "
+                             "read from inside the benchmark process)"),
+            "algorithmic_bytes": float(pairs) * (m * n + n * p) + 8.0 * m * p,
         },
         "split_hbm": {"algorithmic_GBps": round(split_bytes / split_ms / 1e6, 1), "peak_GBps": PEAK_HBM_GBS,
                       "frac": round(split_bytes / split_ms / 1e6 / PEAK_HBM_GBS, 4)},
@@ -223,6 +230,28 @@ def main() -> int:
             del qa, qb, qc
         except Exception as ex:  # not every build of torch carries it for every shape
             log(f"torch._int_mm not usable here: {ex!r}")
+
+    if not args.no_small:
+        # configuration 1 of the benchmark list: m = n = p = 256, k = 8, a single call (median of 100 after a warm-up)
+        As, Bs = inputs.phi_pair(256, 256, 256, 0.5, seed=0)
+        dAs, dBs = torch.from_numpy(As).cuda(), torch.from_numpy(Bs).cuda()
+        Ds = torch.empty((256, 256), dtype=torch.float64, device="cuda")
+        wss = ozimmu.alloc_workspace(256, 256, 256, 8)
+        ozimmu.dgemm(dAs, dBs, 8, D=Ds, workspace=wss)
+        torch.cuda.synchronize()
+        lat = []
+        for _ in range(100):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ozimmu.dgemm(dAs, dBs, 8, D=Ds, workspace=wss)
+            e1.record()
+            torch.cuda.synchronize()
+            lat.append(e0.elapsed_time(e1))
+        lat.sort()
+        result["single_call_256_k8"] = {"median_us": round(lat[50] * 1e3, 1), "min_us": round(lat[0] * 1e3, 1),
+                                        "what": "one ozimmu_dgemm, m=n=p=256, phi=0.5, seed 0, k=8; HIP events, 100 calls"}
+        log(f"256^3 k=8 single call: median {lat[50] * 1e3:.1f} us")
+        del dAs, dBs, Ds, wss
 
     per_k = {str(k): round(value, 3)}
     for kk in extra_ks:

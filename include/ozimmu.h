@@ -79,7 +79,8 @@ int64_t ozimmu_num_chunks(int64_t n, int k);
 size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k);
 
 /* Bytes of device workspace ozimmu_dgemm needs (scheduling scratch, exponents, the two slice stacks and
- * INT32 blocks of 256 x 256 for the partial sums of up to 128 output tiles); host. */
+ * INT32 blocks of 256 x 256: one per output tile for up to 128 tiles, or, for outputs of few tiles, one per
+ * tile and chunk of the schedule, at most 512); host. */
 size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k);
 
 /* D <- A B with k slices: steps (i)-(iv) of the scheme (Section 1) as
@@ -135,7 +136,14 @@ enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 
  *                                with integer atomics, then one accumulation kernel.  Chosen by default when
  *                                the inner dimension is long enough to pay for the extra launches; the flag
  *                                forces it wherever the inner dimension can be cut at all. */
-enum { OZIMMU_SCHEDULE_ONE_LAUNCH = 0x100, OZIMMU_SCHEDULE_SPLIT_INNER = 0x200 };
+/*   OZIMMU_SCHEDULE_CHUNK_PARALLEL  for outputs of few tiles (tiles x chunks <= 512): one launch whose workgroups
+ *                                take (chunk, inner part, tile) work items, every chunk leaving its INT32 sums in
+ *                                a block of its own, and one kernel that adds the chunks of each element in the
+ *                                order of Algorithm 6.  All chunks run side by side (a 1024^3 product occupies
+ *                                128 compute units instead of 16).  Chosen by default for small outputs when the
+ *                                workspace has room for the blocks (ozimmu_workspace_bytes includes them); the
+ *                                flag forces it wherever it fits and is ignored elsewhere. */
+enum { OZIMMU_SCHEDULE_ONE_LAUNCH = 0x100, OZIMMU_SCHEDULE_SPLIT_INNER = 0x200, OZIMMU_SCHEDULE_CHUNK_PARALLEL = 0x400 };
 int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p,
                          const double *A, int64_t lda, const double *B, int64_t ldb,
                          double *D, int64_t ldd, int k, int split_mode, int accumulate_mode,
@@ -256,8 +264,10 @@ int ozimmu_export_slices(int64_t rows, int64_t n, int k, const int8_t *packed,
  * a static device array of OZIMMU_STATIC_WORKSPACE_BYTES inside the library, one copy on every GPU the
  * library is loaded on, held until the process ends.  The call allocates nothing and frees nothing.
  * Arguments and results as for ozimmu_dgemm (bit-identical D).
- *   Returns OZIMMU_ERR_WORKSPACE when ozimmu_workspace_bytes(m, n, p, k) exceeds
- *   OZIMMU_STATIC_WORKSPACE_BYTES (1024^3 with k <= 20 and 2048^3 with k <= 5 fit).
+ *   Returns OZIMMU_ERR_WORKSPACE when the call does not fit the array: the two slice stacks
+ *   (ozimmu_slices_bytes), 4 (m + p) bytes of exponents and one 256 KiB block per output tile (at most 128)
+ *   must stay within OZIMMU_STATIC_WORKSPACE_BYTES (1024^3 with k <= 20 and 2048^3 with k <= 5 fit).
+ *   The schedules that need more room than that are simply not chosen.
  * All calls on one GPU share that GPU's array: two calls that may run at the same time on one GPU (different
  * streams, or different host threads) race and give undefined results; calls on one stream are ordered and
  * safe.  What a call needs cleared it clears itself; nothing carries over from the previous call.  Before

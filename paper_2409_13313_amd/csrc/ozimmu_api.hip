@@ -81,7 +81,7 @@ int64_t r_wide_of(int64_t n, int beta)
 
 int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
                double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
-               size_t workspace_bytes, void* stream, void* const* events);
+               size_t workspace_bytes, void* stream, void* const* events, bool minimal_workspace_ok = false);
 
 // The split-inner way of running the schedule (see run_schedule) works on at most this many 256 x 256 tiles
 // at a time: outputs that small as a whole, or the last, partly filled round of tiles of a larger output
@@ -92,11 +92,37 @@ inline int64_t output_tiles(int64_t m, int64_t p)
 {
     return (ozl::rows_padded(m) / ozl::TILE_R) * (ozl::rows_padded(p) / ozl::TILE_R);
 }
-// INT32 partial sums: one dense 256 x 256 block per tile handled that way
-inline int64_t partial_sums_bytes(int64_t m, int64_t p)
+// The chunk-parallel way (see run_schedule) keeps one block per (chunk, tile): used for outputs of few tiles whose
+// tiles times chunks stay within this many blocks (128 MiB).
+constexpr int64_t CHUNK_PARALLEL_MAX_BLOCKS = 512;
+inline int64_t chunks_of(int k, int64_t r)
+{
+    int64_t w = 0;
+    for (int g = 2; g <= k + 1; ++g) w += ((g - 1) + r - 1) / r;
+    return w;
+}
+// INT32 blocks of 256 x 256 behind the slice stacks: what the split-inner way needs at least ...
+inline int64_t min_partial_blocks(int64_t m, int64_t p)
 {
     const int64_t T = output_tiles(m, p);
-    return (T < SPLIT_INNER_MAX_TILES ? T : SPLIT_INNER_MAX_TILES) * (4 * 256 * 256);
+    return T < SPLIT_INNER_MAX_TILES ? T : SPLIT_INNER_MAX_TILES;
+}
+// ... and what ozimmu_workspace_bytes asks for, so that the chunk-parallel way can be used where it applies
+inline int64_t partial_blocks(int64_t m, int64_t n, int64_t p, int k)
+{
+    const int64_t base = min_partial_blocks(m, p);
+    if (n < 1 || n > MAX_INNER || k < 1) return base;
+    const int64_t items = output_tiles(m, p) * chunks_of(k, r_of(n, beta_of(n)));
+    return (items <= CHUNK_PARALLEL_MAX_BLOCKS && items > base) ? items : base;
+}
+constexpr int64_t BLOCK_BYTES = 4 * 256 * 256;
+
+// the least a call of ozimmu_dgemm can run in (no room for the chunk-parallel blocks)
+inline size_t min_workspace_bytes(int64_t m, int64_t n, int64_t p, int k)
+{
+    return (size_t)(align256(OZIMMU_SCRATCH_BYTES) + align256(4 * m) + align256(4 * p)) +
+           (size_t)ozl::stack_bytes(m, n, k) + (size_t)ozl::stack_bytes(p, n, k) +
+           (size_t)(min_partial_blocks(m, p) * BLOCK_BYTES);
 }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? OZIMMU_OK : OZIMMU_ERR_HIP; }
@@ -177,16 +203,73 @@ struct Finish {
 // schedule: 0 = choose, OZIMMU_SCHEDULE_ONE_LAUNCH, OZIMMU_SCHEDULE_SPLIT_INNER (honoured when possible).
 int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, const int32_t* eA,
                  const int32_t* eB, int k, int64_t r, bool per_slice, int schedule, double* D, int64_t ldd,
-                 const Finish& fin, int32_t* partial, void* scratch, int num_cu, hipStream_t st)
+                 const Finish& fin, int32_t* partial, int64_t partial_capacity, void* scratch, int num_cu, hipStream_t st)
 {
     const int beta = beta_of(n);
     const int r_eff = (int)(r < k ? r : k);
     const int KT = (int)(ozl::inner_padded(n) / ozl::TILE_K);
     const int64_t T = output_tiles(m, p);
+    const int64_t w = chunks_of(k, r_eff);
+
+    // Third way, for outputs of few tiles: ONE launch whose work items are (chunk, inner part, tile), every chunk
+    // writing (or, when cut, atomically adding) its INT32 sums to a block of its own per tile, and one kernel that
+    // adds the chunks of every element in the order of Algorithm 6.  All chunks of all tiles run side by side, so a
+    // 1024^3 product occupies 128 compute units instead of 16; the price is 4 bytes of workspace per element and
+    // chunk.  Times in microseconds as in the model below; a work item pays about 15 us of prologue and epilogue.
+    if (!per_slice && partial && T * w <= CHUNK_PARALLEL_MAX_BLOCKS && T * w <= partial_capacity && T < num_cu &&
+        schedule != OZIMMU_SCHEDULE_ONE_LAUNCH && schedule != OZIMMU_SCHEDULE_SPLIT_INNER) {
+        const double stage_us = 0.68, item_us = 15.0;
+        const double pairs = (double)k * (k + 1) / 2;
+        const int longest = r_eff < k ? r_eff : k;  // pairs of the longest chunk
+        const double one_launch_us = stage_us * pairs * KT + 35.0 * (double)w;  // every tile at once, chunks in sequence
+        double best = 0.0;
+        int best_z = 0;
+        const int zmax = KT / 4 > 0 ? KT / 4 : 1;
+        for (int z = 1; z <= zmax; z *= 2) {
+            const double total = (double)T * (stage_us * pairs * KT + item_us * (double)w * z);
+            const double longest_item = stage_us * longest * KT / z + item_us;
+            double t = total / (double)num_cu * 1.25;  // static assignment of unequal items
+            if (t < longest_item) t = longest_item;
+            t += 25.0;  // one more launch, the accumulation kernel, clearing the blocks
+            if (best_z == 0 || t < best) {
+                best = t;
+                best_z = z;
+            }
+        }
+        if (schedule == OZIMMU_SCHEDULE_CHUNK_PARALLEL || best < 0.8 * one_launch_us) {
+            hipError_t e = hipSuccess;
+            if (best_z > 1) e = ozk::launch_fill_zero_i32(T * w * 256 * 256, partial, st);
+            if (e != hipSuccess) return OZIMMU_ERR_HIP;
+            ozk::GemmArgs a = make_args(m, n, p, SA, k, SB, k, 2, k + 1, r_eff, 0, 0, scratch, num_cu);
+            a.C = partial;
+            a.zsplit = best_z;
+            a.nchunks = (int)w;
+            a.spin_limit = 0;  // the items of a team are different chunks: nothing to line up
+            e = ozk::launch_gemm(a, 3, st);
+            if (e != hipSuccess) return OZIMMU_ERR_HIP;
+            ozk::TileAccArgs t{};
+            t.tile_begin = 0;
+            t.tile_count = (int)T;
+            t.m = m;
+            t.p = p;
+            t.Ct = partial;
+            t.eA = eA;
+            t.eB = eB;
+            t.D = D;
+            t.ldd = ldd;
+            t.finish = fin.on ? 1 : 0;
+            t.alpha = fin.alpha;
+            t.cbeta = fin.cbeta;
+            t.Cout = fin.Cout;
+            t.ldco = fin.ldco;
+            return hip_status(ozk::launch_accumulate_chunks(t, k, r_eff, beta, st));
+        }
+    }
+
     // tiles [0, T - tail) go to the persistent launch, the last `tail` tiles (band order) are cut Z ways
     int64_t tail = 0;
     int Z = 1;
-    if (!per_slice && partial && schedule != OZIMMU_SCHEDULE_ONE_LAUNCH) {
+    if (!per_slice && partial && schedule != OZIMMU_SCHEDULE_ONE_LAUNCH && schedule != OZIMMU_SCHEDULE_CHUNK_PARALLEL) {
         const int64_t ncu = num_cu;
         const int64_t cand = ncu > 0 ? (T < ncu ? T : T % ncu) : 0;  // tiles of the partly filled round
         const int64_t zmax = KT / 4;  // every part gets at least one group of 4 stages of the shortest chunk
@@ -195,8 +278,6 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             // 0.68 us; the fused path pays about 35 us per chunk and tile for epilogue and prologue, a part of
             // the cut path about 15 us (atomic epilogue, prologue), and every chunk of the cut path about 15 us
             // of launches plus the accumulation pass over the tail tiles (20 bytes per element at 4.5 TB/s).
-            int64_t w = 0;
-            for (int g = 2; g <= k + 1; ++g) w += ((g - 1) + r_eff - 1) / r_eff;
             const double chunk_us = 0.68 * (double)k * (k + 1) / 2 * KT / (double)w;  // average chunk of one tile
             const double fused_us = chunk_us + 35.0;  // one more round of the persistent launch
             const double fixed_us = 15.0 + 0.29 * (double)cand;
@@ -321,7 +402,7 @@ size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k)
 {
     if (m < 0 || n < 0 || p < 0 || k < 0) return 0;
     return (size_t)(align256(OZIMMU_SCRATCH_BYTES) + align256(4 * m) + align256(4 * p)) +
-           ozimmu_slices_bytes(m, n, k) + ozimmu_slices_bytes(p, n, k) + (size_t)partial_sums_bytes(m, p);
+           ozimmu_slices_bytes(m, n, k) + ozimmu_slices_bytes(p, n, k) + (size_t)(partial_blocks(m, n, p, k) * BLOCK_BYTES);
 }
 
 int ozimmu_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int8_t* SA, int32_t* eA, void* stream)
@@ -455,7 +536,8 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
     int8_t* SB = reinterpret_cast<int8_t*>(ws);
     ws += ozimmu_slices_bytes(p, n, k);
     int32_t* partial = reinterpret_cast<int32_t*>(ws);
-    ws += partial_sums_bytes(m, p);
+    const int64_t blocks = partial_blocks(m, n, p, k);
+    ws += blocks * BLOCK_BYTES;
     double* Dw = reinterpret_cast<double*>(ws);  // beta != 0 only
 
     // op(A): one scale per row of op(A).  Stored transposed (n x m), those rows are the columns of the
@@ -473,7 +555,7 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
     const bool in_place = beta == 0.0;
     const Finish fin = {!(alpha == 1.0 && beta == 0.0), alpha, beta, C, ldc};
     return run_schedule(m, n, p, SA, SB, eA, eB, k, r, false, 0, in_place ? C : Dw, in_place ? ldc : p, fin, partial,
-                        scratch, ds.num_cu, st);
+                        blocks, scratch, ds.num_cu, st);
 }
 
 int ozimmu_dgemm(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
@@ -537,7 +619,8 @@ int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p, const double* A, int64
     const int flags = accumulate_mode & ~0xff, amode = accumulate_mode & 0xff;
     if (split_mode < OZIMMU_SPLIT_NEAREST || split_mode > OZIMMU_SPLIT_NEAREST_PER_SLICE) return OZIMMU_ERR_SLICES;
     if (amode < OZIMMU_ACCUM_GROUPED || amode > OZIMMU_ACCUM_WIDE) return OZIMMU_ERR_SLICES;
-    if (flags != 0 && flags != OZIMMU_SCHEDULE_ONE_LAUNCH && flags != OZIMMU_SCHEDULE_SPLIT_INNER)
+    if (flags != 0 && flags != OZIMMU_SCHEDULE_ONE_LAUNCH && flags != OZIMMU_SCHEDULE_SPLIT_INNER &&
+        flags != OZIMMU_SCHEDULE_CHUNK_PARALLEL)
         return OZIMMU_ERR_SLICES;
     if (amode == OZIMMU_ACCUM_WIDE && split_mode != OZIMMU_SPLIT_NEAREST) return OZIMMU_ERR_SLICES;
     if (split_mode == OZIMMU_SPLIT_NEAREST_PER_SLICE && amode != OZIMMU_ACCUM_PER_PAIR) return OZIMMU_ERR_SLICES;
@@ -580,13 +663,13 @@ int ozimmu_dgemm_static(int64_t m, int64_t n, int64_t p, const double* A, int64_
 {
     if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
     if (k < 1 || k > OZIMMU_MAX_SLICES) return OZIMMU_ERR_SLICES;
-    if (ozimmu_workspace_bytes(m, n, p, k) > (size_t)OZIMMU_STATIC_WORKSPACE_BYTES) return OZIMMU_ERR_WORKSPACE;
+    if (min_workspace_bytes(m, n, p, k) > (size_t)OZIMMU_STATIC_WORKSPACE_BYTES) return OZIMMU_ERR_WORKSPACE;
     if (m == 0 || p == 0) return OZIMMU_OK;
     DeviceState ds;
     const int rc = device_state(&ds);
     if (rc != OZIMMU_OK) return rc;
     return dgemm_impl(m, n, p, A, lda, B, ldb, D, ldd, k, OZIMMU_SPLIT_NEAREST, OZIMMU_ACCUM_GROUPED, ds.static_ws,
-                      (size_t)OZIMMU_STATIC_WORKSPACE_BYTES, stream, nullptr);
+                      (size_t)OZIMMU_STATIC_WORKSPACE_BYTES, stream, nullptr, true);
 }
 
 int64_t ozimmu_r_wide(int64_t n)
@@ -601,7 +684,7 @@ namespace {
 
 int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
                double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
-               size_t workspace_bytes, void* stream, void* const* events)
+               size_t workspace_bytes, void* stream, void* const* events, bool minimal_workspace_ok)
 {
     if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
     if (lda < n || ldb < p || ldd < p || lda > MAX_LD || ldb > MAX_LD || ldd > MAX_LD) return OZIMMU_ERR_DIM;
@@ -612,13 +695,15 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     if (n == 0) return hip_status(ozk::launch_fill_zero_f64(m, p, D, ldd, st));
     if (!A || !B || !workspace) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(workspace) % 256 ||
-        workspace_bytes < ozimmu_workspace_bytes_variant(m, n, p, k, split_mode))
+        workspace_bytes < (minimal_workspace_ok ? min_workspace_bytes(m, n, p, k)
+                                                : ozimmu_workspace_bytes_variant(m, n, p, k, split_mode)))
         return OZIMMU_ERR_WORKSPACE;
     DeviceState ds;
     const int drc = device_state(&ds);
     if (drc != OZIMMU_OK) return drc;
 
-    const int schedule = accumulate_mode & (OZIMMU_SCHEDULE_ONE_LAUNCH | OZIMMU_SCHEDULE_SPLIT_INNER);
+    const int schedule =
+        accumulate_mode & (OZIMMU_SCHEDULE_ONE_LAUNCH | OZIMMU_SCHEDULE_SPLIT_INNER | OZIMMU_SCHEDULE_CHUNK_PARALLEL);
     accumulate_mode &= 0xff;
     const int beta = beta_of(n);
     const bool per_slice = split_mode == OZIMMU_SPLIT_NEAREST_PER_SLICE;
@@ -658,8 +743,13 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     int32_t* partial = nullptr;  // INT32 partial sums of few-tile outputs, behind the slices
     if (!per_slice) partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(SB) + ozimmu_slices_bytes(p, n, k));
     const Finish no_finish = {false, 1.0, 0.0, D, ldd};
+    // blocks of 256 x 256 INT32 the rest of the workspace holds (decides whether the chunk-parallel way fits)
+    int64_t capacity = 0;
+    if (partial)
+        capacity = (int64_t)((static_cast<char*>(workspace) + workspace_bytes - reinterpret_cast<char*>(partial)) /
+                             BLOCK_BYTES);
     const int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, per_slice, schedule, D, ldd, no_finish, partial,
-                                scratch, ds.num_cu, st);
+                                capacity, scratch, ds.num_cu, st);
     if (rc != OZIMMU_OK) return rc;
     return hip_status(mark(2));
 }

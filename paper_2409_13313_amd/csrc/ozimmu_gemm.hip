@@ -11,7 +11,10 @@
 // is one pair (s, t) and the factor is 2^(2 - 2 beta) diag(2^eA_s) . diag(2^eB_t).
 // MODE 3 is MODE 0 for tiles too few to fill the chip: the inner range of the chunk
 // is cut into Z parts that run on different workgroups and add their INT32 partial
-// sums to zeroed per-tile blocks with integer atomics (exact in any order).
+// sums to zeroed per-tile blocks with integer atomics (exact in any order).  With
+// a.nchunks > 0 one MODE 3 launch covers ALL chunks of the schedule at once: a work
+// item is (chunk, part, tile), every chunk has a block per tile of its own, and a
+// separate kernel adds the chunks up in FP64 in the order of Algorithm 6.
 // A launch covers a range of tiles (tile_begin, tile_count) of the band order.
 //
 // The stored bytes are the slice integers plus the offset of their stack (cA for A, cB for B, see
@@ -206,9 +209,11 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     const int nwg = gridDim.x, bid = blockIdx.x;
     const int xcd = bid % NXCD, member = bid / NXCD;
     const int team = nwg / NXCD + (xcd < nwg % NXCD ? 1 : 0);
-    // MODE 3 cuts the inner range of every chunk into Z parts; a work item is (part, tile)
+    // MODE 3 cuts the inner range of every chunk into Z parts; a work item is (part, tile), or, when the launch
+    // covers all chunks of the schedule (a.nchunks > 0), (chunk, part, tile)
     const int Z = (MODE == 3) ? a.zsplit : 1;
-    const int T = a.tile_count * Z;
+    const bool all_chunks = (MODE == 3) && a.nchunks > 0;
+    const int T = a.tile_count * Z * (all_chunks ? a.nchunks : 1);
     const int tiles_base = T / NXCD, tiles_rem = T % NXCD;
     const int range_off = xcd * tiles_base + (xcd < tiles_rem ? xcd : tiles_rem);
     const int range_cnt = tiles_base + (xcd < tiles_rem ? 1 : 0);
@@ -240,8 +245,29 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
         const int item = range_off + local;
         // MODE 3: part-major order, so that the 32 work items of a team are 32 tiles cut at the same place of
         // the inner dimension and share operand tiles in L2 like the tiles of the un-cut kernel
-        const int zpart = (MODE == 3) ? item / a.tile_count : 0;
-        const int ztile = (MODE == 3) ? item % a.tile_count : item;
+        // (integer divisions run on the vector unit: readfirstlane tells the compiler the results are uniform)
+        const int zpart = (MODE == 3) ? __builtin_amdgcn_readfirstlane((item / a.tile_count) % Z) : 0;
+        const int ztile = (MODE == 3) ? __builtin_amdgcn_readfirstlane(item % a.tile_count) : item;
+        // the chunks this work item runs: all of the schedule, or the one chunk given by the launch, or (all_chunks)
+        // chunk number `chunk_no` of the schedule, found by walking it.  Long chunks (late groups) come first in
+        // the item order, so that the short ones fill the gaps at the end.
+        int it_g_lo = a.g_lo, it_g_hi = a.g_hi, it_s0 = a.s0, it_s1 = a.s1, chunk_no = 0;
+        if (all_chunks) {
+            chunk_no = __builtin_amdgcn_readfirstlane(a.nchunks - 1 - item / (a.tile_count * Z));
+            int q = 0;
+            for (int g = a.g_lo; g <= a.g_hi; ++g)
+                for (int c0 = 1; c0 <= g - 1; c0 += a.r, ++q)
+                    if (q == chunk_no) {
+                        it_g_lo = it_g_hi = g;
+                        it_s0 = c0;
+                        it_s1 = (c0 + a.r - 1 < g - 1) ? c0 + a.r - 1 : g - 1;
+                    }
+            // the same in every lane: say so (operand addresses built from these go into scalar registers)
+            it_g_lo = it_g_hi = __builtin_amdgcn_readfirstlane(it_g_lo);
+            it_s0 = __builtin_amdgcn_readfirstlane(it_s0);
+            it_s1 = __builtin_amdgcn_readfirstlane(it_s1);
+            chunk_no = __builtin_amdgcn_readfirstlane(chunk_no);
+        }
         if (MODE != 3 && TM % 16 == 0 && TP % 16 == 0 && nwg == 32 * NXCD && a.tile_count == TM * TP) {
             // Tile grid made of 16 x 16 blocks and a full grid of workgroups: in round q the 8 x 4 patches of
             // the eight XCDs tile block q (2 x 4 patches), so that all XCDs together stream 16 A and 16 B
@@ -271,9 +297,9 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
             lds_exp[256 + t] = gc < a.p ? a.eB[gc] : 0;
         }
 
-        for (int g = a.g_lo; g <= a.g_hi; ++g) {
-            const int s_lo = a.s0 > 0 ? a.s0 : 1;
-            const int s_hi = a.s0 > 0 ? a.s1 : g - 1;
+        for (int g = it_g_lo; g <= it_g_hi; ++g) {
+            const int s_lo = it_s0 > 0 ? it_s0 : 1;
+            const int s_hi = it_s0 > 0 ? it_s1 : g - 1;
             for (int c0 = s_lo; c0 <= s_hi; c0 += a.r) {
                 const int c1 = (c0 + a.r - 1 < s_hi) ? c0 + a.r - 1 : s_hi;  // chunk: s = c0..c1
                 int nstage = (c1 - c0 + 1) * KT;
@@ -483,13 +509,13 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 const int64_t urow = er0 + rt;
                                 // MODE 3: the tile's own dense 256 x 256 block, addressed by the row / column in the tile
                                 int32_t* base = (MODE == 3)
-                                                    ? a.C + (int64_t)ztile * (256 * 256) + (int64_t)(wm * 128 + rt) * 256 +
-                                                          wn * 128 + j * 32
+                                                    ? a.C + ((int64_t)chunk_no * a.tile_count + ztile) * (256 * 256) +
+                                                          (int64_t)(wm * 128 + rt) * 256 + wn * 128 + j * 32
                                                     : a.C + urow * a.ldc + ec0 + j * 32;
                                 const uint32_t off =
                                     (uint32_t)(4 * lhe) * ((MODE == 3) ? 256u : (uint32_t)a.ldc) + (uint32_t)lre;
                                 if (lane_col_ok[j] && urow + 4 * lhe < a.m) {
-                                    if (MODE == 3)  // partial sum of one part: integer adds commute, C'' starts at zero
+                                    if (MODE == 3 && Z > 1)  // partial sum of one part: integer adds commute, C'' starts at zero
                                         __hip_atomic_fetch_add(&base[off], acc[i][j][r], __ATOMIC_RELAXED,
                                                                __HIP_MEMORY_SCOPE_AGENT);
                                     else
@@ -692,6 +718,41 @@ __global__ __launch_bounds__(256) void k_accumulate_tiles(ozk::TileAccArgs t)
     }
 }
 
+// Step (iv) over all chunks of the schedule for a range of tiles: chunk q's INT32 sums lie in blocks
+// Ct[q * tile_count + tile]; D = fl(...fl(fl(T_1 + T_2) + T_3)...) in schedule order (g ascending, chunks of r
+// ascending), T_q = 2^(2 - beta g) diag(2^eA) FP64(C''_q) diag(2^eB), the first addend taken as it is.
+__global__ __launch_bounds__(256) void k_accumulate_chunks(ozk::TileAccArgs t, int k, int r, int beta)
+{
+    const int local = blockIdx.x / 32, rows8 = blockIdx.x % 32;
+    int tm, tp;
+    tile_of_linear(t.tile_begin + local, t.TM, t.TP, tm, tp);
+    const int64_t j = (int64_t)tp * 256 + threadIdx.x;
+    if (j >= t.p) return;
+    const int eb = t.eB[j];
+    const int64_t chunk_stride = (int64_t)t.tile_count * (256 * 256);
+    for (int q = 0; q < 8; ++q) {
+        const int64_t i = (int64_t)tm * 256 + rows8 * 8 + q;
+        if (i >= t.m) break;
+        const int32_t* c = t.Ct + (int64_t)local * (256 * 256) + (int64_t)(rows8 * 8 + q) * 256 + threadIdx.x;
+        const int e = t.eA[i] + eb;
+        double d = 0.0;
+        bool first = true;
+        for (int g = 2; g <= k + 1; ++g)
+            for (int c0 = 1; c0 <= g - 1; c0 += r, c += chunk_stride) {
+                const double term = ldexp((double)*c, e + 2 - beta * g);
+                d = first ? term : d + term;
+                first = false;
+            }
+        double* out = t.D + i * t.ldd + j;
+        if (t.finish) {
+            d = t.alpha * d;
+            out = t.Cout + i * t.ldco + j;
+            if (t.cbeta != 0.0) d = d + t.cbeta * *out;
+        }
+        *out = d;
+    }
+}
+
 __global__ __launch_bounds__(256) void k_zero_f64(int64_t m, int64_t p, double* __restrict__ D, int64_t ldd)
 {
     const int64_t j = (int64_t)blockIdx.y * 256 + threadIdx.x;
@@ -752,7 +813,7 @@ hipError_t launch_gemm(const GemmArgs& a_in, int fused, hipStream_t st)
     const int TM = (int)(ozl::rows_padded(a.m) / ozl::TILE_R), TP = (int)(ozl::rows_padded(a.p) / ozl::TILE_R);
     const size_t smem = (size_t)NSTAGES * STAGE_BYTES + EXP_BYTES;
     // one workgroup per CU (the LDS ring allows no second one), never more workgroups than tiles
-    const int64_t tiles = (int64_t)a.tile_count * (fused == 3 ? a.zsplit : 1);
+    const int64_t tiles = (int64_t)a.tile_count * (fused == 3 ? a.zsplit : 1) * (fused == 3 && a.nchunks > 0 ? a.nchunks : 1);
     if (a.tile_count <= 0 || a.tile_begin < 0 || (int64_t)a.tile_begin + a.tile_count > (int64_t)TM * TP)
         return hipErrorInvalidValue;
     int nwg = a.num_cu > 0 ? a.num_cu : 1;
@@ -816,6 +877,16 @@ hipError_t launch_accumulate_tiles(const TileAccArgs& t_in, hipStream_t st)
     t.TM = (int)(ozl::rows_padded(t.m) / ozl::TILE_R);
     t.TP = (int)(ozl::rows_padded(t.p) / ozl::TILE_R);
     hipLaunchKernelGGL(k_accumulate_tiles, dim3((unsigned)t.tile_count * 32u), dim3(256), 0, st, t);
+    return hipGetLastError();
+}
+
+hipError_t launch_accumulate_chunks(const TileAccArgs& t_in, int k, int r, int beta, hipStream_t st)
+{
+    if (t_in.tile_count <= 0) return hipSuccess;
+    TileAccArgs t = t_in;
+    t.TM = (int)(ozl::rows_padded(t.m) / ozl::TILE_R);
+    t.TP = (int)(ozl::rows_padded(t.p) / ozl::TILE_R);
+    hipLaunchKernelGGL(k_accumulate_chunks, dim3((unsigned)t.tile_count * 32u), dim3(256), 0, st, t, k, r, beta);
     return hipGetLastError();
 }
 

@@ -48,6 +48,8 @@ struct GemmArgs {
     const int32_t* eB;
     int64_t estrideA, estrideB;  // fused == 2 only: elements from the exponents of slice s to those of slice s+1
     int zsplit;            // fused == 3 only: parts the inner range of a chunk is cut into (<= KT / 4)
+    int nchunks;           // fused == 3 only: 0, or the number of chunks of the full schedule g_lo..g_hi: the launch
+                           // then runs every chunk, C holding nchunks x tile_count blocks (chunk-major)
     int tile_begin, tile_count;  // the launch covers tiles tile_begin .. tile_begin + tile_count - 1 of the band order
     int dma_ok;            // D is 16-byte aligned and ldd even: rows of D can be copied 16 bytes per lane
     int beta;              // shift of group g is 2 - beta * g
@@ -93,6 +95,10 @@ struct TileAccArgs {
     int64_t ldco;
 };
 hipError_t launch_accumulate_tiles(const TileAccArgs& t, hipStream_t st);
+// Step (iv) for ALL chunks of the schedule (groups 2..k+1, chunks of r) at once: the chunk sums of chunk q lie in
+// blocks Ct[q][tile]; they are added in schedule order, one rounded FP64 addition each.  Uses t.tile_*, m, p, Ct,
+// eA, eB, D, ldd and the finish fields; shift / first are ignored.
+hipError_t launch_accumulate_chunks(const TileAccArgs& t, int k, int r, int beta, hipStream_t st);
 // Step (v): C <- alpha D + beta C (beta == 0: C not read).
 hipError_t launch_axpby(int64_t m, int64_t p, double alpha, const double* D, int64_t ldd, double beta, double* C,
                         int64_t ldc, hipStream_t st);

@@ -15,6 +15,9 @@
 
   --sizes      m=n=p in {1024 .. 16384}, k in {4, 8, 12}: time of ozimmu_dgemm against native FP64   [Section 4.2]
 
+  --small      m=n=p in {256, 1024}, k=8: single-call latency (median of 100) next to native FP64, and the time of
+               the CPU oracle for the same product run in full
+
   --schedules  outputs of few tiles: the one-launch schedule against the split-inner one and native FP64
 
   --breakdown  time shares of split / INT8 GEMMs / FP64 accumulation with the phases run as separate kernels,
@@ -273,6 +276,35 @@ def sizes(ns=(1024, 2048, 3072, 4096, 5120, 6144, 7168, 8192, 9216, 10240, 12288
     print()
 
 
+def small(reps=100):
+    """Configurations 1 and 2 of the benchmark list as single calls: latency of one ozimmu_dgemm (median of `reps`,
+    after one warm-up) next to native FP64, and the CPU oracle's time for the same product, run in full."""
+    import time
+    import torch
+    import oracle
+    from paper_2409_13313_amd import inputs, ozimmu
+    print(f"### single-call latency of small products, phi=0.5, k=8; median of {reps} calls after one warm-up\n")
+    print("| m=n=p | ozimmu_dgemm (us) | effective TFLOP/s | native FP64 torch.mm (us) | CPU oracle, full product (s) "
+          "| oracle threads | D identical to the oracle's |")
+    print("|---|---|---|---|---|---|---|")
+    for n in (256, 1024):
+        A, B = inputs.phi_pair(n, n, n, 0.5, seed=0)
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        D = torch.empty((n, n), dtype=torch.float64, device="cuda")
+        ws = ozimmu.alloc_workspace(n, n, n, 8)
+        ozimmu.dgemm(dA, dB, 8, D=D, workspace=ws)
+        t = _median_ms(lambda: ozimmu.dgemm(dA, dB, 8, D=D, workspace=ws), reps)
+        got = D.cpu().numpy()
+        torch.mm(dA, dB, out=D)
+        t_nat = _median_ms(lambda: torch.mm(dA, dB, out=D), reps)
+        t0 = time.perf_counter()
+        want = oracle.dgemm(A, B, 8)
+        t_cpu = time.perf_counter() - t0
+        print(f"| {n} | {t * 1e3:.1f} | {2.0 * n ** 3 / t / 1e9:.2f} | {t_nat * 1e3:.1f} | {t_cpu:.2f} | "
+              f"{oracle.num_threads()} | {bool((got == want).all())} |")
+    print()
+
+
 def schedules(k=8, reps=5):
     import torch
     from paper_2409_13313_amd import inputs, ozimmu
@@ -353,6 +385,7 @@ def main():
     ap.add_argument("--small-beta", action="store_true")
     ap.add_argument("--sizes", action="store_true")
     ap.add_argument("--schedules", action="store_true")
+    ap.add_argument("--small", action="store_true")
     ap.add_argument("--breakdown", action="store_true")
     args = ap.parse_args()
     import torch
@@ -375,6 +408,8 @@ def main():
         sizes()
     if args.schedules:
         schedules()
+    if args.small:
+        small()
     if args.breakdown:
         breakdown()
     return 0

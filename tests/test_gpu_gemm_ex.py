@@ -48,6 +48,32 @@ def test_gemm_ex_matches_oracle_bit_for_bit(oz, transA, transB, alpha, beta):
     assert (got[m:, :] == -3.0).all() and (got[:, p:] == -3.0).all()
 
 
+def test_gemm_ex_without_old_c_needs_no_extra_buffer(oz):
+    # beta == 0: the sum is formed in C itself and fl(alpha d) is applied by the last chunk's epilogue, so the
+    # workspace of ozimmu_dgemm is enough; beta != 0 needs the m x p buffer on top
+    m, n, p, k = 520, 300, 270, 5
+    A, B = inputs.phi_pair(m, n, p, 0.5, seed=61)
+    want = oracle.gemm_ex(False, False, -0.375, A, B, 0.0, np.zeros((m, p)), k)
+    small = torch.empty(oz.workspace_bytes(m, n, p, k), dtype=torch.uint8, device="cuda")
+    C = torch.full((m, p), float("nan"), dtype=torch.float64, device="cuda")
+    oz.gemm_ex(False, False, -0.375, dev(A), dev(B), 0.0, C, k, workspace=small)
+    assert np.array_equal(C.cpu().numpy(), want)
+    with pytest.raises(oz.OzimmuError):
+        oz.gemm_ex(False, False, -0.375, dev(A), dev(B), 0.5, C, k, workspace=small)
+
+
+def test_gemm_ex_single_slice_first_chunk_is_also_the_last(oz):
+    # k = 1: one chunk, which is first (D not read) and last (step (v) applied) at once
+    m, n, p = 300, 260, 280
+    A, B = inputs.phi_pair(m, n, p, 1.0, seed=62)
+    C0 = np.random.Generator(np.random.PCG64(63)).standard_normal((m, p))
+    for alpha, beta in ((2.5, 0.0), (-0.3, 1.25)):
+        want = oracle.gemm_ex(False, False, alpha, A, B, beta, C0, 1)
+        C = dev(C0)
+        oz.gemm_ex(False, False, alpha, dev(A), dev(B), beta, C, 1)
+        assert np.array_equal(C.cpu().numpy(), want)
+
+
 def test_gemm_ex_empty_inner_dimension_scales_c(oz):
     C0 = np.random.Generator(np.random.PCG64(53)).standard_normal((5, 7))
     C = dev(C0)

@@ -1,6 +1,7 @@
-"""GPU parity of the two ways the schedule is run: one persistent launch with the fused epilogue, and the
-split-inner way for outputs of few tiles (partial INT32 sums by integer atomics + accumulation kernel).
-Both must give the oracle's D bit for bit."""
+"""GPU parity of the ways the schedule is run: one persistent launch with the fused epilogue; the split-inner
+way for tiles too few to fill the chip (per chunk: partial INT32 sums by integer atomics + accumulation kernel);
+the chunk-parallel way for outputs of few tiles (all chunks in one launch, each with INT32 blocks of its own,
+then one kernel that adds them in the order of Algorithm 6).  All must give the oracle's D bit for bit."""
 import numpy as np
 import pytest
 
@@ -33,7 +34,7 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("schedule", ["one_launch", "split_inner", "auto"])
+@pytest.mark.parametrize("schedule", ["one_launch", "split_inner", "chunk_parallel", "auto"])
 @pytest.mark.parametrize("m,n,p,k,phi", SHAPES)
 def test_both_schedules_match_the_oracle_bit_for_bit(oz, m, n, p, k, phi, schedule):
     A, B = inputs.phi_pair(m, n, p, phi, seed=91)
@@ -68,12 +69,53 @@ def test_split_inner_with_strided_output_and_reused_workspace(oz):
     assert np.array_equal(got[:, :p], want) and (got[:, p:] == -1.0).all()
 
 
+@pytest.mark.parametrize("split,accumulate", [("bitmask", "grouped"), ("bitmask", "per_pair"), ("rn", "wide"),
+                                              ("rn", "per_pair")])
+def test_chunk_parallel_schedule_with_the_comparison_variants(oz, split, accumulate):
+    m, n, p, k = 300, 2000, 270, 9
+    A, B = inputs.phi_pair(m, n, p, 2.0, seed=94)
+    want = oracle.dgemm_variant(A, B, k, split, accumulate)
+    got = oz.dgemm_variant(dev(A), dev(B), k, split, accumulate, schedule="chunk_parallel").cpu().numpy()
+    assert np.array_equal(got, want)
+
+
+def test_chunk_parallel_with_strided_output_reused_workspace_and_step_v(oz):
+    m, n, p, k = 700, 1100, 300, 7
+    A, B = inputs.phi_pair(m, n, p, 1.0, seed=95)
+    want = oracle.dgemm(A, B, k)
+    Dbig = torch.full((m, p + 3), -1.0, dtype=torch.float64, device="cuda")
+    ws = oz.alloc_workspace(m, n, p, k)
+    ws.fill_(0x5A)                       # stale bytes in the blocks must not leak
+    for _ in range(2):
+        oz.dgemm_variant(dev(A), dev(B), k, "rn", "grouped", D=Dbig[:, :p], workspace=ws, schedule="chunk_parallel")
+    got = Dbig.cpu().numpy()
+    assert np.array_equal(got[:, :p], want) and (got[:, p:] == -1.0).all()
+    # the GEMM-routine form takes the same way by default at this size: step (v) in the accumulation kernel
+    C0 = np.random.Generator(np.random.PCG64(96)).standard_normal((m, p))
+    for alpha, beta in ((-1.5, 0.0), (0.75, -0.25)):
+        C = dev(C0)
+        oz.gemm_ex(False, False, alpha, dev(A), dev(B), beta, C, k)
+        assert np.array_equal(C.cpu().numpy(), oracle.gemm_ex(False, False, alpha, A, B, beta, C0, k))
+
+
+def test_small_workspace_falls_back_to_the_other_schedules(oz):
+    # a workspace without room for the chunk-parallel blocks is still enough for the static-workspace entry
+    # point; ozimmu_dgemm itself insists on ozimmu_workspace_bytes
+    m, n, p, k = 1024, 1024, 1024, 20
+    assert oz.workspace_bytes(m, n, p, k) > oz.STATIC_WORKSPACE_BYTES
+    A, B = inputs.phi_pair(m, n, p, 0.5, seed=97)
+    dA, dB = dev(A), dev(B)
+    D = torch.empty((m, p), dtype=torch.float64, device="cuda")
+    oz.dgemm_static(dA, dB, k, D)
+    assert torch.equal(D, oz.dgemm(dA, dB, k))
+
+
 def test_schedule_flags_are_validated(oz):
     A = torch.zeros((4, 4), dtype=torch.float64, device="cuda")
     ws = oz.alloc_workspace(4, 4, 4, 4)
     st = torch.cuda.current_stream().cuda_stream
     D = torch.empty((4, 4), dtype=torch.float64, device="cuda")
-    for bad in (0x300, 0x400, 0x103 | 0x200):
+    for bad in (0x300, 0x800, 0x500, 0x103 | 0x200):
         rc = oz._lib.ozimmu_dgemm_variant(4, 4, 4, A.data_ptr(), 4, A.data_ptr(), 4, D.data_ptr(), 4, 4, 0, bad,
                                           ws.data_ptr(), ws.numel(), st)
         assert rc == -3

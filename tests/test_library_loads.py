@@ -66,18 +66,21 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 8, fake, 16, None) == -4           # workspace too small
     assert lib.ozimmu_dgemm(4, 2 ** 29 + 1, 4, fake, 2 ** 30, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -2
     assert lib.ozimmu_dgemm(0, 4, 4, None, 4, None, 4, None, 4, 8, None, 0, None) == 0             # empty: nothing to do
-    # workspace = scratch + exponents + the two slice stacks + one INT32 block of 256 x 256 per output tile, for at
-    # most 128 tiles.  A stack = k padded slices (rows padded to 256, inner index to 256) + k arrays of padded-rows
-    # INT32 row sums (rounded up to 256 bytes) + a 256-byte trailer
+    # workspace = scratch + exponents + the two slice stacks + INT32 blocks of 256 x 256: one per output tile for at
+    # most 128 tiles, or one per tile and chunk of the schedule when that stays within 512 blocks.  A stack = k
+    # padded slices (rows padded to 256, inner index to 256) + k arrays of padded-rows INT32 row sums (rounded up to
+    # 256 bytes) + a 256-byte trailer
     blk = 4 * 256 * 256
 
     def stack(rows_padded, inner_padded, k):
         return k * rows_padded * inner_padded + -(-4 * k * rows_padded // 256) * 256 + 256
 
-    assert lib.ozimmu_workspace_bytes(256, 128, 256, 8) == 512 + 2 * 1024 + 2 * stack(256, 256, 8) + blk
-    assert lib.ozimmu_workspace_bytes(257, 257, 1, 3) == 512 + 1280 + 256 + stack(512, 512, 3) + stack(256, 512, 3) + 2 * blk
-    big = lib.ozimmu_workspace_bytes(4096, 256, 4096, 1)       # 256 tiles: blocks for 128 of them
-    assert big == 512 + 2 * 4 * 4096 + 2 * stack(4096, 256, 1) + 128 * blk
+    # 1 tile x 8 chunks (r >= k: one chunk per group)
+    assert lib.ozimmu_workspace_bytes(256, 128, 256, 8) == 512 + 2 * 1024 + 2 * stack(256, 256, 8) + 8 * blk
+    # 2 tiles x 3 chunks
+    assert lib.ozimmu_workspace_bytes(257, 257, 1, 3) == 512 + 1280 + 256 + stack(512, 512, 3) + stack(256, 512, 3) + 6 * blk
+    big = lib.ozimmu_workspace_bytes(4096, 256, 4096, 8)       # 256 tiles x 8 chunks > 512: blocks for 128 tiles
+    assert big == 512 + 2 * 4 * 4096 + 2 * stack(4096, 256, 8) + 128 * blk
 
 def test_limits_are_reported_as_dimension_errors(lib):
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -109,7 +112,10 @@ def test_static_workspace_size_check_needs_no_gpu(lib):
     lib.ozimmu_workspace_bytes.argtypes = [i64, i64, i64, ci]
     lib.ozimmu_workspace_bytes.restype = ctypes.c_size_t
     fake = 4096
-    assert lib.ozimmu_workspace_bytes(1024, 1024, 1024, 20) <= 64 << 20 < lib.ozimmu_workspace_bytes(4096, 4096, 4096, 8)
+    assert 64 << 20 < lib.ozimmu_workspace_bytes(4096, 4096, 4096, 8)
     assert lib.ozimmu_dgemm_static(4096, 4096, 4096, fake, 4096, fake, 4096, fake, 4096, 8, None) == -4
+    # 2048^3 with k = 6: the two slice stacks alone are 6 x 8 MiB: too much; with k = 5 the call fits (and would go
+    # on to the device set-up, which needs a GPU: not called here)
+    assert lib.ozimmu_dgemm_static(2048, 2048, 2048, fake, 2048, fake, 2048, fake, 2048, 6, None) == -4
     assert lib.ozimmu_dgemm_static(4, 4, 4, fake, 4, fake, 4, fake, 4, 21, None) == -3
     assert lib.ozimmu_dgemm_static(0, 4, 4, None, 4, None, 4, None, 4, 8, None) == 0   # empty: nothing to do

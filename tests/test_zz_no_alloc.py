@@ -47,7 +47,7 @@ def test_static_workspace_entry_point_matches_dgemm_twice_in_a_row(oz):
 
 def test_static_workspace_entry_point_rejects_what_does_not_fit(oz):
     # 4096^3 with k = 8 needs 268 MB of slices alone: more than the 64 MiB the library holds
-    assert oz.workspace_bytes(4096, 4096, 4096, 8) > oz.STATIC_WORKSPACE_BYTES
+    assert oz.slices_bytes(4096, 4096, 8) > oz.STATIC_WORKSPACE_BYTES
     fake = 4096   # never dereferenced: the size check comes first
     rc = oz._lib.ozimmu_dgemm_static(4096, 4096, 4096, fake, 4096, fake, 4096, fake, 4096, 8, None)
     assert rc == -4

@@ -109,7 +109,7 @@ def main() -> int:
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     D = torch.empty((m, p), dtype=torch.float64, device="cuda")
     extra_ks = [int(x) for x in args.extra_k.split(",") if x.strip()] if args.extra_k else []
-    ws = ozimmu.alloc_workspace(m, n, p, max([k] + extra_ks))
+    ws = ozimmu.alloc_workspace(m, n, p, [k] + extra_ks)
     torch.cuda.synchronize()
     log(f"inputs {m}x{n}x{p} phi={args.phi} generated and uploaded in {time.perf_counter() - t0:.1f}s; "
         f"beta={beta} r={r} chunks={w} pairs={pairs}")

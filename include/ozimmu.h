@@ -78,16 +78,23 @@ int64_t ozimmu_num_chunks(int64_t n, int k);
  * valid for the k it was made with: pass that k as kA / kB below. */
 size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k);
 
-/* Bytes of device workspace ozimmu_dgemm needs (scheduling scratch, exponents, the two slice stacks and
- * INT32 blocks of 256 x 256: one per output tile for up to 128 tiles, or, for outputs of few tiles, one per
- * tile and chunk of the schedule, at most 512); host. */
+/* Bytes of device workspace ozimmu_dgemm makes the best use of (scheduling scratch, exponents, the two slice
+ * stacks and INT32 blocks of 256 x 256: one per output tile for up to 128 tiles, or, for outputs of few tiles,
+ * one per tile and chunk of the schedule, at most 512); host.  Not monotone in k (the per-chunk blocks are only
+ * counted while tiles x chunks <= 512). */
 size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k);
+
+/* The least ozimmu_dgemm accepts (one block per output tile, at most 128): with less than
+ * ozimmu_workspace_bytes the call gives the same D, but small outputs cannot take the chunk-parallel
+ * schedule (see OZIMMU_SCHEDULE_CHUNK_PARALLEL below).  Monotone in m, n, p and k.  Host. */
+size_t ozimmu_workspace_bytes_min(int64_t m, int64_t n, int64_t p, int k);
 
 /* D <- A B with k slices: steps (i)-(iv) of the scheme (Section 1) as
  * Algorithm 8 (split) followed by Algorithm 6 (grouped accumulation).
  *   A, B, D      device, FP64, row-major (see above); D is overwritten.
  *   k            number of slices, 1..OZIMMU_MAX_SLICES.
- *   workspace    device, >= ozimmu_workspace_bytes(m,n,p,k) bytes, 256-byte aligned.
+ *   workspace    device, 256-byte aligned, >= ozimmu_workspace_bytes_min(m,n,p,k) bytes
+ *                (ozimmu_workspace_bytes(m,n,p,k) to let small outputs run their fastest schedule).
  * m, n or p equal to 0 is valid: nothing is computed, and for n == 0 (m, p > 0)
  * D is set to +0. */
 int ozimmu_dgemm(int64_t m, int64_t n, int64_t p,
@@ -141,8 +148,9 @@ enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 
  *                                a block of its own, and one kernel that adds the chunks of each element in the
  *                                order of Algorithm 6.  All chunks run side by side (a 1024^3 product occupies
  *                                128 compute units instead of 16).  Chosen by default for small outputs when the
- *                                workspace has room for the blocks (ozimmu_workspace_bytes includes them); the
- *                                flag forces it wherever it fits and is ignored elsewhere. */
+ *                                workspace has room for the blocks (ozimmu_workspace_bytes includes them,
+ *                                ozimmu_workspace_bytes_min does not); the flag forces it wherever it fits and
+ *                                is ignored elsewhere. */
 enum { OZIMMU_SCHEDULE_ONE_LAUNCH = 0x100, OZIMMU_SCHEDULE_SPLIT_INNER = 0x200, OZIMMU_SCHEDULE_CHUNK_PARALLEL = 0x400 };
 int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p,
                          const double *A, int64_t lda, const double *B, int64_t ldb,
@@ -162,8 +170,9 @@ int64_t ozimmu_r_wide(int64_t n);
  *   op(A) is m x n: A is stored row-major m x n (lda >= n) or, transposed, n x m (lda >= m).
  *   op(B) is n x p: B is stored row-major n x p (ldb >= p) or, transposed, p x n (ldb >= n).
  *   C       device, m x p row-major, ldc >= p; read unless beta == 0, then overwritten.
- *   workspace  device, 256-byte aligned; >= ozimmu_workspace_bytes_ex(m,n,p,k) bytes, or, when
- *              beta == 0, only >= ozimmu_workspace_bytes(m,n,p,k) (the sum is then formed in C itself).
+ *   workspace  device, 256-byte aligned; at least ozimmu_workspace_bytes_min(m,n,p,k) bytes when beta == 0
+ *              (the sum is then formed in C itself), plus 8 m p bytes (rounded up to 256) when beta != 0;
+ *              ozimmu_workspace_bytes_ex(m,n,p,k) covers both and the fastest schedule.
  * The product D is formed exactly as by ozimmu_dgemm; then, per element, t1 = fl(alpha d),
  * t2 = fl(beta c), c = fl(t1 + t2) (three rounded FP64 operations, no fused multiply-add); with
  * beta == 0 the old C is not read and c = fl(alpha d).  Step (v) costs no pass of its own: the last

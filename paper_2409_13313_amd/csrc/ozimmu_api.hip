@@ -81,7 +81,7 @@ int64_t r_wide_of(int64_t n, int beta)
 
 int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
                double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
-               size_t workspace_bytes, void* stream, void* const* events, bool minimal_workspace_ok = false);
+               size_t workspace_bytes, void* stream, void* const* events);
 
 // The split-inner way of running the schedule (see run_schedule) works on at most this many 256 x 256 tiles
 // at a time: outputs that small as a whole, or the last, partly filled round of tiles of a larger output
@@ -405,6 +405,12 @@ size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k)
            ozimmu_slices_bytes(m, n, k) + ozimmu_slices_bytes(p, n, k) + (size_t)(partial_blocks(m, n, p, k) * BLOCK_BYTES);
 }
 
+size_t ozimmu_workspace_bytes_min(int64_t m, int64_t n, int64_t p, int k)
+{
+    if (m < 0 || n < 0 || p < 0 || k < 0) return 0;
+    return min_workspace_bytes(m, n, p, k);
+}
+
 int ozimmu_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int8_t* SA, int32_t* eA, void* stream)
 {
     if (m < 0 || n < 0 || m > MAX_OUTER || n > MAX_INNER || lda < n || lda > MAX_LD) return OZIMMU_ERR_DIM;
@@ -516,7 +522,7 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
     }
     if (!A || !B || !workspace) return OZIMMU_ERR_NULL;
     // beta == 0: the sum is formed in C itself, no m x p buffer
-    const size_t need = beta == 0.0 ? ozimmu_workspace_bytes(m, n, p, k) : ozimmu_workspace_bytes_ex(m, n, p, k);
+    const size_t need = min_workspace_bytes(m, n, p, k) + (beta == 0.0 ? (size_t)0 : (size_t)align256(8 * m * p));
     if (reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < need) return OZIMMU_ERR_WORKSPACE;
 
     DeviceState ds;
@@ -535,10 +541,10 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
     ws += ozimmu_slices_bytes(m, n, k);
     int8_t* SB = reinterpret_cast<int8_t*>(ws);
     ws += ozimmu_slices_bytes(p, n, k);
-    int32_t* partial = reinterpret_cast<int32_t*>(ws);
-    const int64_t blocks = partial_blocks(m, n, p, k);
-    ws += blocks * BLOCK_BYTES;
     double* Dw = reinterpret_cast<double*>(ws);  // beta != 0 only
+    if (beta != 0.0) ws += align256(8 * m * p);
+    int32_t* partial = reinterpret_cast<int32_t*>(ws);  // the rest: INT32 blocks, as many as there is room for
+    const int64_t blocks = (int64_t)((static_cast<char*>(workspace) + workspace_bytes - ws) / BLOCK_BYTES);
 
     // op(A): one scale per row of op(A).  Stored transposed (n x m), those rows are the columns of the
     // stored matrix, which is what the column-wise split kernel handles; likewise for op(B).
@@ -669,7 +675,7 @@ int ozimmu_dgemm_static(int64_t m, int64_t n, int64_t p, const double* A, int64_
     const int rc = device_state(&ds);
     if (rc != OZIMMU_OK) return rc;
     return dgemm_impl(m, n, p, A, lda, B, ldb, D, ldd, k, OZIMMU_SPLIT_NEAREST, OZIMMU_ACCUM_GROUPED, ds.static_ws,
-                      (size_t)OZIMMU_STATIC_WORKSPACE_BYTES, stream, nullptr, true);
+                      (size_t)OZIMMU_STATIC_WORKSPACE_BYTES, stream, nullptr);
 }
 
 int64_t ozimmu_r_wide(int64_t n)
@@ -684,7 +690,7 @@ namespace {
 
 int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
                double* D, int64_t ldd, int k, int split_mode, int accumulate_mode, void* workspace,
-               size_t workspace_bytes, void* stream, void* const* events, bool minimal_workspace_ok)
+               size_t workspace_bytes, void* stream, void* const* events)
 {
     if (m < 0 || n < 0 || p < 0 || m > MAX_OUTER || p > MAX_OUTER || n > MAX_INNER) return OZIMMU_ERR_DIM;
     if (lda < n || ldb < p || ldd < p || lda > MAX_LD || ldb > MAX_LD || ldd > MAX_LD) return OZIMMU_ERR_DIM;
@@ -695,8 +701,9 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     if (n == 0) return hip_status(ozk::launch_fill_zero_f64(m, p, D, ldd, st));
     if (!A || !B || !workspace) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(workspace) % 256 ||
-        workspace_bytes < (minimal_workspace_ok ? min_workspace_bytes(m, n, p, k)
-                                                : ozimmu_workspace_bytes_variant(m, n, p, k, split_mode)))
+        workspace_bytes < (split_mode == OZIMMU_SPLIT_NEAREST_PER_SLICE
+                               ? ozimmu_workspace_bytes_variant(m, n, p, k, split_mode)
+                               : min_workspace_bytes(m, n, p, k)))
         return OZIMMU_ERR_WORKSPACE;
     DeviceState ds;
     const int drc = device_state(&ds);

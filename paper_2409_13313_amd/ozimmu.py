@@ -34,6 +34,8 @@ _lib.ozimmu_slices_bytes.argtypes = [_i64, _i64, _int]
 _lib.ozimmu_slices_bytes.restype = _sz
 _lib.ozimmu_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
 _lib.ozimmu_workspace_bytes.restype = _sz
+_lib.ozimmu_workspace_bytes_min.argtypes = [_i64, _i64, _i64, _int]
+_lib.ozimmu_workspace_bytes_min.restype = _sz
 _lib.ozimmu_dgemm.argtypes = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _vp, _sz, _vp]
 _lib.ozimmu_dgemm.restype = _int
 _lib.ozimmu_dgemm_profiled.argtypes = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _vp, _sz, _vp,
@@ -83,7 +85,7 @@ EXPORTS = ["ozimmu_status_string", "ozimmu_params", "ozimmu_num_chunks", "ozimmu
            "ozimmu_r_wide", "ozimmu_split_A_variant", "ozimmu_split_B_variant", "ozimmu_split_A", "ozimmu_split_B", "ozimmu_gemm_group",
            "ozimmu_accumulate", "ozimmu_gemm_group_accumulate", "ozimmu_export_slices",
            "ozimmu_workspace_bytes_variant", "ozimmu_remainder_bytes", "ozimmu_split_A_per_slice",
-           "ozimmu_split_B_per_slice", "ozimmu_init", "ozimmu_dgemm_static"]
+           "ozimmu_split_B_per_slice", "ozimmu_init", "ozimmu_dgemm_static", "ozimmu_workspace_bytes_min"]
 
 
 SPLIT_MODES = {"rn": 0, "bitmask": 1, "per_slice": 2}
@@ -143,8 +145,15 @@ def workspace_bytes(m: int, n: int, p: int, k: int) -> int:
     return int(_lib.ozimmu_workspace_bytes(m, n, p, k))
 
 
-def alloc_workspace(m: int, n: int, p: int, k: int, device="cuda", split: str = "rn") -> torch.Tensor:
-    nbytes = int(_lib.ozimmu_workspace_bytes_variant(m, n, p, k, SPLIT_MODES[split]))
+def workspace_bytes_min(m: int, n: int, p: int, k: int) -> int:
+    return int(_lib.ozimmu_workspace_bytes_min(m, n, p, k))
+
+
+def alloc_workspace(m: int, n: int, p: int, k, device="cuda", split: str = "rn") -> torch.Tensor:
+    """Workspace for calls with k slices; k may be a sequence of slice counts the workspace is to serve
+    (the requirement is not monotone in k, so the largest k alone would not do)."""
+    ks = [k] if isinstance(k, int) else list(k)
+    nbytes = max(int(_lib.ozimmu_workspace_bytes_variant(m, n, p, kk, SPLIT_MODES[split])) for kk in ks)
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 

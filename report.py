@@ -202,7 +202,7 @@ def perf_vs_accuracy(n=4096, phi=0.0, sample=256, reps=5):
     print(f"native FP64 (torch.mm): {flops / t / 1e9:.1f} TFLOP/s, e1 = {e1:.2e}, e2 = {e2:.2e}\n")
     print("| k | " + " | ".join(f"{name}: TFLOP/s, e1, e2" for _, _, name in methods) + " |")
     print("|---|" + "---|" * len(methods))
-    ws = ozimmu.alloc_workspace(n, n, n, 12, split="per_slice")
+    ws = ozimmu.alloc_workspace(n, n, n, list(range(3, 13)), split="per_slice")
     for k in range(3, 13):
         cells = []
         for split, acc, name in methods:
@@ -234,7 +234,7 @@ def small_beta(m=2048, p=2048, phi=0.5, sample=64, reps=3):
         tI, tJ = torch.from_numpy(I).cuda(), torch.from_numpy(J).cuda()
         D = torch.empty((m, p), dtype=torch.float64, device="cuda")
         beta, r = ozimmu.params(n)
-        ws = ozimmu.alloc_workspace(m, n, p, 12)
+        ws = ozimmu.alloc_workspace(m, n, p, list(range(3, 13)))
         cells = []
         for k in (8, 9, 10, 11, 12):
             ozimmu.dgemm(dA, dB, k, D=D, workspace=ws)
@@ -260,7 +260,7 @@ def sizes(ns=(1024, 2048, 3072, 4096, 5120, 6144, 7168, 8192, 9216, 10240, 12288
         A, B = inputs.phi_pair(n, n, n, 0.5, seed=0)
         dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
         D = torch.empty((n, n), dtype=torch.float64, device="cuda")
-        ws = ozimmu.alloc_workspace(n, n, n, max(ks))
+        ws = ozimmu.alloc_workspace(n, n, n, list(ks))
         torch.mm(dA, dB, out=D)
         t_nat = _median_ms(lambda: torch.mm(dA, dB, out=D), reps)
         cells = []

@@ -50,11 +50,11 @@ def test_gemm_ex_matches_oracle_bit_for_bit(oz, transA, transB, alpha, beta):
 
 def test_gemm_ex_without_old_c_needs_no_extra_buffer(oz):
     # beta == 0: the sum is formed in C itself and fl(alpha d) is applied by the last chunk's epilogue, so the
-    # workspace of ozimmu_dgemm is enough; beta != 0 needs the m x p buffer on top
+    # least workspace of ozimmu_dgemm is enough; beta != 0 needs the m x p buffer on top
     m, n, p, k = 520, 300, 270, 5
     A, B = inputs.phi_pair(m, n, p, 0.5, seed=61)
     want = oracle.gemm_ex(False, False, -0.375, A, B, 0.0, np.zeros((m, p)), k)
-    small = torch.empty(oz.workspace_bytes(m, n, p, k), dtype=torch.uint8, device="cuda")
+    small = torch.empty(oz.workspace_bytes_min(m, n, p, k), dtype=torch.uint8, device="cuda")
     C = torch.full((m, p), float("nan"), dtype=torch.float64, device="cuda")
     oz.gemm_ex(False, False, -0.375, dev(A), dev(B), 0.0, C, k, workspace=small)
     assert np.array_equal(C.cpu().numpy(), want)

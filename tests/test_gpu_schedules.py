@@ -99,15 +99,22 @@ def test_chunk_parallel_with_strided_output_reused_workspace_and_step_v(oz):
 
 
 def test_small_workspace_falls_back_to_the_other_schedules(oz):
-    # a workspace without room for the chunk-parallel blocks is still enough for the static-workspace entry
-    # point; ozimmu_dgemm itself insists on ozimmu_workspace_bytes
+    # a workspace without room for the chunk-parallel blocks (the least one, or the library's static array)
+    # gives the same D through the other schedules; the requirement is not monotone in k, the least one is
     m, n, p, k = 1024, 1024, 1024, 20
-    assert oz.workspace_bytes(m, n, p, k) > oz.STATIC_WORKSPACE_BYTES
+    assert oz.workspace_bytes(m, n, p, k) > oz.STATIC_WORKSPACE_BYTES >= oz.workspace_bytes_min(m, n, p, k)
+    assert oz.workspace_bytes(2048, 2048, 2048, 8) > oz.workspace_bytes(2048, 2048, 2048, 12)
+    assert oz.workspace_bytes_min(2048, 2048, 2048, 8) < oz.workspace_bytes_min(2048, 2048, 2048, 12)
     A, B = inputs.phi_pair(m, n, p, 0.5, seed=97)
     dA, dB = dev(A), dev(B)
+    want = oz.dgemm(dA, dB, k)
     D = torch.empty((m, p), dtype=torch.float64, device="cuda")
     oz.dgemm_static(dA, dB, k, D)
-    assert torch.equal(D, oz.dgemm(dA, dB, k))
+    assert torch.equal(D, want)
+    least = torch.empty(oz.workspace_bytes_min(m, n, p, k), dtype=torch.uint8, device="cuda")
+    assert torch.equal(oz.dgemm(dA, dB, k, workspace=least), want)
+    with pytest.raises(oz.OzimmuError):
+        oz.dgemm(dA, dB, k, workspace=least[:-256])
 
 
 def test_schedule_flags_are_validated(oz):

@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256) void k_split_A(int64_t m, int64_t n, const dou
 }
 
 // ---------------------------------------------------------------------------
-// A, single pass (rows of at most 1024 * GROUPS padded elements): one workgroup
+// A, single pass (rows of at most 1024 * GROUPS padded elements; GROUPS = 4, 8 or 16): one workgroup
 // per padded row keeps the whole row in registers (4 * GROUPS doubles per
 // thread), reduces max |a_ij| through LDS and writes the k slices, so A is read
 // from HBM exactly once.  Thread t holds elements 4t + 1024 g .. + 3.
@@ -602,6 +602,8 @@ hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, in
     } while (0)
         if (Npad <= 4096)
             OZ_PICK_ROW(4);
+        else if (Npad <= 8192)
+            OZ_PICK_ROW(8);
         else
             OZ_PICK_ROW(16);
 #undef OZ_PICK_ROW

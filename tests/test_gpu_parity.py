@@ -317,3 +317,47 @@ def test_dgemm_captured_in_a_hip_graph_replays_bit_identically(oz):
         del other
     want = oracle.dgemm(A, B, k)
     assert (np.abs(eager.cpu().numpy() - want) <= 2 * np.spacing(np.abs(want))).all()
+
+
+def test_first_library_call_of_a_process_inside_a_graph_capture_after_init(oz):
+    # the per-device set-up (kernel attributes, symbol address) is not legal inside a stream capture: a process whose
+    # very first library call is a captured one must call ozimmu_init before.  Run in a child process, so that the
+    # library is really fresh there.
+    import subprocess
+    import sys
+    code = r"""
+import sys
+import numpy as np
+import torch
+sys.path.insert(0, %r)
+from paper_2409_13313_amd import inputs, ozimmu
+m, n, p, k = 300, 520, 270, 6
+A, B = inputs.phi_pair(m, n, p, 0.5, seed=43)
+dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+ws = ozimmu.alloc_workspace(m, n, p, k)
+D = torch.zeros((m, p), dtype=torch.float64, device="cuda")
+ozimmu.init()                                  # the only library call before the capture
+side = torch.cuda.Stream()
+side.wait_stream(torch.cuda.current_stream())
+torch.cuda.synchronize()
+graph = torch.cuda.CUDAGraph()
+with torch.cuda.graph(graph):
+    ozimmu.dgemm(dA, dB, k, D=D, workspace=ws)
+outs = []
+for rep in range(3):
+    D.fill_(float(rep))
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    outs.append(D.clone())
+eager = ozimmu.dgemm(dA, dB, k)
+torch.cuda.synchronize()
+assert all(torch.equal(o, eager) for o in outs)
+import oracle
+assert np.array_equal(eager.cpu().numpy(), oracle.dgemm(A, B, k))
+print("CAPTURE_OK")
+""" % (str(__import__("os").path.dirname(__import__("os").path.dirname(__import__("os").path.abspath(__file__)))),)
+    pr = subprocess.run([sys.executable, "-c", code], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True,
+                        timeout=240)
+    assert pr.returncode == 0 and "CAPTURE_OK" in pr.stdout, pr.stdout[-3000:]
+

@@ -96,7 +96,8 @@ def test_mode_errors_and_workspace_size(oz):
     for acc in ("grouped", "wide"):
         with pytest.raises(oz.OzimmuError):
             oz.dgemm_variant(A, A, 4, "per_slice", acc)       # per-slice scales share no shift inside a group
-    small = oz.alloc_workspace(300, 520, 270, 8)              # sized for the shared-scale splits
+    # the least workspace of the shared-scale splits has no room for the remainders of the per-slice split
+    small = torch.empty(oz.workspace_bytes_min(300, 520, 270, 8), dtype=torch.uint8, device="cuda")
     A, B = inputs.phi_pair(300, 520, 270, 0.5, seed=74)
     with pytest.raises(oz.OzimmuError):
         oz.dgemm_variant(dev(A), dev(B), 8, "per_slice", "per_pair", workspace=small)

@@ -76,6 +76,8 @@ def main() -> int:
     ap.add_argument("--no-native", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the register-only MFMA rate measurement")
     ap.add_argument("--no-small", action="store_true", help="skip the single-call latency of the 256^3 case")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the phase times of the 8192^3 and 4096 x 65536 x 4096 configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of A (known size) so that a rocprofv3 --pmc run "
                          "can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -328,6 +330,30 @@ def main() -> int:
             result["accuracy_phi%g" % args.extra_phi] = {"sample": f"{S}x{S} entries vs Dot2", **acc4}
             log(f"accuracy phi={args.extra_phi}:", acc4)
         del A4, B4
+
+    if not args.no_secondary:
+        # configurations 3 and 5 of the benchmark list, timed like the headline (phase times from HIP events)
+        del dA, dB, D, ws
+        torch.cuda.empty_cache()
+        sec = {}
+        for (m2, n2, p2, phi2, k2) in ((8192, 8192, 8192, 0.5, 8), (4096, 65536, 4096, 1.0, 10)):
+            A2, B2 = inputs.phi_pair(m2, n2, p2, phi2, seed=0)
+            dA, dB = torch.from_numpy(A2).cuda(), torch.from_numpy(B2).cuda()
+            del A2, B2
+            D = torch.empty((m2, p2), dtype=torch.float64, device="cuda")
+            ws = ozimmu.alloc_workspace(m2, n2, p2, k2)
+            wms, sms, gms = timed(k2, 3, 1)
+            fl2 = 2.0 * m2 * n2 * p2
+            b2, r2 = ozimmu.params(n2)
+            sec[f"{m2}x{n2}x{p2}_phi{phi2:g}_k{k2}"] = {
+                "ms_per_call": round(wms, 4), "tflops": round(fl2 / wms / 1e9, 2), "split_ms": round(sms, 4),
+                "gemm_ms": round(gms, 4), "gemm_tops": round(fl2 * k2 * (k2 + 1) / 2 / gms / 1e9, 1),
+                "beta": b2, "r": r2, "fp64_addends": ozimmu.num_chunks(n2, k2)}
+            log(f"{m2}x{n2}x{p2} phi={phi2} k={k2}: {wms:.2f} ms -> {fl2 / wms / 1e9:.1f} TFLOP/s "
+                f"(split {sms:.2f} ms, GEMMs {gms:.2f} ms)")
+            del dA, dB, D, ws
+            torch.cuda.empty_cache()
+        result["secondary_configs"] = sec
 
     if not args.no_cpu_baseline:
         # the oracle, untuned, on a bounded sample of the same workload: rows I and columns J of D

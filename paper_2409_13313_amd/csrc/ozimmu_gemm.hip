@@ -47,6 +47,12 @@
 //   MFMAs issued before the barrier) | k-step 1 math.
 // The LDS-writing loads are issued from inline assembly, so the compiler does
 // not track them; the vmcnt waits that order them are written out below.
+// The compiler's own memory waits use the same counter: an ordinary load (or
+// a spill reload) still pending when the loop is entered would make it put a
+// vmcnt wait into the loop that also waits for the copies in flight.  Hence
+// every ordinary load of a chunk prologue is consumed before the loop, and the
+// accumulators are pinned to their registers when they are initialised (see
+// there); tests/test_kernel_codegen.py checks the generated loop for it.
 // The fused epilogue of later chunks uses the same copies to bring the old values
 // of D through the then idle ring (see there).
 #include "ozimmu_kernels.h"

@@ -298,9 +298,11 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
             // exponents of this tile's rows and columns go to LDS once (every wave is past the previous
             // tile's epilogue; the chunk prologue's barrier publishes them)
             __builtin_amdgcn_s_barrier();
-            const int64_t gr = (int64_t)tm * 256 + t, gc = (int64_t)tp * 256 + t;
-            lds_exp[t] = gr < a.m ? a.eA[gr] : 0;
-            lds_exp[256 + t] = gc < a.p ? a.eB[gc] : 0;
+            // (row / column indices fit 32 bits: outer sizes are at most 2^22; a uniform base plus a 32-bit lane
+            // offset needs no 64-bit address arithmetic per lane)
+            const uint32_t gr = (uint32_t)tm * 256u + (uint32_t)t, gc = (uint32_t)tp * 256u + (uint32_t)t;
+            lds_exp[t] = (int64_t)gr < a.m ? a.eA[gr] : 0;
+            lds_exp[256 + t] = (int64_t)gc < a.p ? a.eB[gc] : 0;
         }
 
         for (int g = it_g_lo; g <= it_g_hi; ++g) {
@@ -349,19 +351,28 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 if (MODE == 2) {
                     // one scale per slice: this chunk is the single pair (c0, g - c0); every wave is past the
                     // previous epilogue, and the barriers of the main loop publish the new exponents
-                    const int64_t gr = (int64_t)tm * 256 + t, gc = (int64_t)tp * 256 + t;
-                    lds_exp[t] = gr < a.m ? a.eA[(int64_t)(c0 - 1) * a.estrideA + gr] : 0;
-                    lds_exp[256 + t] = gc < a.p ? a.eB[(int64_t)(g - c0 - 1) * a.estrideB + gc] : 0;
+                    const uint32_t gr = (uint32_t)tm * 256u + (uint32_t)t, gc = (uint32_t)tp * 256u + (uint32_t)t;
+                    const int32_t* ea_s = a.eA + (int64_t)(c0 - 1) * a.estrideA;       // uniform
+                    const int32_t* eb_t = a.eB + (int64_t)(g - c0 - 1) * a.estrideB;
+                    lds_exp[t] = (int64_t)gr < a.m ? ea_s[gr] : 0;
+                    lds_exp[256 + t] = (int64_t)gc < a.p ? eb_t[gc] : 0;
                 }
                 // sums of the stored bytes over the chunk's slices (A: c0 .. c1, B: g - c1 .. g - c0) for this
                 // thread's row and column of the tile, as differences of prefix sums; the loads are in flight
                 // while the first stages are issued and the team lines up, the corrections go to LDS after that
                 int sumA = 0, sumB = 0;
                 if (offsets) {
-                    const int64_t gr = (int64_t)tm * 256 + t, gc = (int64_t)tp * 256 + t;  // inside the padded stacks
-                    sumA = a.PA[(int64_t)(c1 - 1) * a.pstrideA + gr] - (c0 > 1 ? a.PA[(int64_t)(c0 - 2) * a.pstrideA + gr] : 0);
+                    // row / column inside the padded stacks; uniform slice bases plus a 32-bit lane offset (opaque, so
+                    // that no per-lane 64-bit address is formed once per tile and kept alive through the chunks)
+                    uint32_t gr = (uint32_t)tm * 256u + (uint32_t)t, gc = (uint32_t)tp * 256u + (uint32_t)t;
+                    asm volatile("" : "+v"(gr), "+v"(gc));
                     const int t_lo = g - c1, t_hi = g - c0;
-                    sumB = a.PB[(int64_t)(t_hi - 1) * a.pstrideB + gc] - (t_lo > 1 ? a.PB[(int64_t)(t_lo - 2) * a.pstrideB + gc] : 0);
+                    const int32_t* pa_hi = a.PA + (int64_t)(c1 - 1) * a.pstrideA;
+                    const int32_t* pa_lo = a.PA + (int64_t)(c0 > 1 ? c0 - 2 : 0) * a.pstrideA;
+                    const int32_t* pb_hi = a.PB + (int64_t)(t_hi - 1) * a.pstrideB;
+                    const int32_t* pb_lo = a.PB + (int64_t)(t_lo > 1 ? t_lo - 2 : 0) * a.pstrideB;
+                    sumA = pa_hi[gr] - (c0 > 1 ? pa_lo[gr] : 0);
+                    sumB = pb_hi[gc] - (t_lo > 1 ? pb_lo[gc] : 0);
                 }
                 static_for<0, NS - 1>([&](auto S) {
                     constexpr int sidx = decltype(S)::value;
@@ -398,15 +409,19 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 // accumulators start at -(ra[row] + cb[column]) (see the head of this file); of a chunk that is cut
                 // into parts (MODE 3) only part 0 carries the start value, the others start at zero
                 {
+                    // lane parts of the LDS addresses made opaque here: otherwise the sixteen addresses are formed
+                    // at kernel entry, live through everything and get spilled
+                    int lhi = lh, lri = lr;
+                    asm volatile("" : "+v"(lhi), "+v"(lri));
                     int ncb[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) ncb[j] = lds_corr[256 + wn * 128 + j * 32 + lr];
+                    for (int j = 0; j < 4; ++j) ncb[j] = lds_corr[256 + wn * 128 + j * 32 + lri];
                     const bool carries = (MODE != 3) || zpart == 0;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         int nra[16];
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) nra[r] = lds_corr[wm * 128 + i * 32 + 8 * (r / 4) + (r % 4) + 4 * lh];
+                        for (int r = 0; r < 16; ++r) nra[r] = lds_corr[wm * 128 + i * 32 + 8 * (r / 4) + (r % 4) + 4 * lhi];
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
 #pragma unroll

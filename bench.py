@@ -68,7 +68,7 @@ def main() -> int:
     ap.add_argument("--size", type=int, nargs="*", default=[16384], help="m n p (one value = square)")
     ap.add_argument("--k", type=int, default=8)
     ap.add_argument("--phi", type=float, default=0.5)
-    ap.add_argument("--extra-k", type=str, default="12,14", help="further slice counts timed with 2 steps each")
+    ap.add_argument("--extra-k", type=str, default="6,7,12,14", help="further slice counts timed with 2 steps each")
     ap.add_argument("--extra-phi", type=float, default=4.0,
                     help="also time the same shape with this phi (0 = skip); the headline value stays --phi's")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -139,13 +139,12 @@ int check_gemm_args(int64_t m, int64_t n, int64_t p, const void* SA, int kA, con
     return OZIMMU_OK;
 }
 
-// Offset of the stored bytes (see ozimmu_layout.h): 63 moves round-to-nearest slices (|q| <= 64) into [-1, 127];
-// bit-mask slices (|q| <= 127) have no room for one, and neither have the wide chunks, whose length is derived
-// from |q| <= 64.
-#ifndef OZIMMU_RN_OFFSET
-#define OZIMMU_RN_OFFSET 63
-#endif
-constexpr int RN_OFFSET = OZIMMU_RN_OFFSET;
+// Offset of the stored bytes (see ozimmu_layout.h): round-to-nearest slices obey |q| <= 2^(beta-1), so the offset
+// 2^(beta-1) - 1 (63 for beta = 7) moves them into [-1, 2^beta - 1]: inside the magnitude 2^beta - 1 for which the
+// paper derives the chunk length r, so no INT32 sum of a chunk can overflow with the stored bytes either.  Bit-mask
+// slices (|q| <= 2^beta - 1) have no room for an offset, and neither have the wide chunks, whose length is derived
+// from |q| <= 2^(beta-1).
+inline int rn_offset(int beta) { return (1 << (beta - 1)) - 1; }
 
 // single chunk (s0 > 0): g, s = s0..s1; full schedule (s0 == 0): g = g_lo..g_hi, chunks of r.
 // SA / SB are whole stacks of kA / kB slices (slices, prefix row sums, trailer).
@@ -418,7 +417,7 @@ int ozimmu_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, in
     if (m == 0 || n == 0) return OZIMMU_OK;
     if (!A || !SA || !eA) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(SA) % 256) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), 0, RN_OFFSET, SA, eA, (hipStream_t)stream));
+    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), 0, rn_offset(beta_of(n)), SA, eA, (hipStream_t)stream));
 }
 
 int ozimmu_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int8_t* SB, int32_t* eB, void* stream)
@@ -428,7 +427,7 @@ int ozimmu_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, in
     if (p == 0 || n == 0) return OZIMMU_OK;
     if (!B || !SB || !eB) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(SB) % 256) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), 0, RN_OFFSET, SB, eB, (hipStream_t)stream));
+    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), 0, rn_offset(beta_of(n)), SB, eB, (hipStream_t)stream));
 }
 
 int ozimmu_gemm_group(int64_t m, int64_t n, int64_t p, const int8_t* SA, int kA, const int8_t* SB, int kB, int g,
@@ -548,11 +547,11 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
 
     // op(A): one scale per row of op(A).  Stored transposed (n x m), those rows are the columns of the
     // stored matrix, which is what the column-wise split kernel handles; likewise for op(B).
-    hipError_t e = transA ? ozk::launch_split_B(n, m, A, lda, k, bt, 0, RN_OFFSET, SA, eA, st)
-                          : ozk::launch_split_A(m, n, A, lda, k, bt, 0, RN_OFFSET, SA, eA, st);
+    hipError_t e = transA ? ozk::launch_split_B(n, m, A, lda, k, bt, 0, rn_offset(bt), SA, eA, st)
+                          : ozk::launch_split_A(m, n, A, lda, k, bt, 0, rn_offset(bt), SA, eA, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
-    e = transB ? ozk::launch_split_A(p, n, B, ldb, k, bt, 0, RN_OFFSET, SB, eB, st)
-               : ozk::launch_split_B(n, p, B, ldb, k, bt, 0, RN_OFFSET, SB, eB, st);
+    e = transB ? ozk::launch_split_A(p, n, B, ldb, k, bt, 0, rn_offset(bt), SB, eB, st)
+               : ozk::launch_split_B(n, p, B, ldb, k, bt, 0, rn_offset(bt), SB, eB, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
     // Step (v) rides on the epilogue of every tile's last chunk.  beta == 0: the running sum lives in C and the
@@ -642,7 +641,7 @@ int ozimmu_split_A_variant(int64_t m, int64_t n, const double* A, int64_t lda, i
     if (m == 0 || n == 0) return OZIMMU_OK;
     if (!A || !SA || !eA) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(SA) % 256) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), split_mode, split_mode == 0 ? RN_OFFSET : 0, SA, eA,
+    return hip_status(ozk::launch_split_A(m, n, A, lda, k, beta_of(n), split_mode, split_mode == 0 ? rn_offset(beta_of(n)) : 0, SA, eA,
                                           (hipStream_t)stream));
 }
 
@@ -654,7 +653,7 @@ int ozimmu_split_B_variant(int64_t n, int64_t p, const double* B, int64_t ldb, i
     if (p == 0 || n == 0) return OZIMMU_OK;
     if (!B || !SB || !eB) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(SB) % 256) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), split_mode, split_mode == 0 ? RN_OFFSET : 0, SB, eB,
+    return hip_status(ozk::launch_split_B(n, p, B, ldb, k, beta_of(n), split_mode, split_mode == 0 ? rn_offset(beta_of(n)) : 0, SB, eB,
                                           (hipStream_t)stream));
 }
 
@@ -737,7 +736,7 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
     };
     hipError_t e = mark(0);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
-    const int offset = (split_mode == OZIMMU_SPLIT_NEAREST && accumulate_mode != OZIMMU_ACCUM_WIDE) ? RN_OFFSET : 0;
+    const int offset = (split_mode == OZIMMU_SPLIT_NEAREST && accumulate_mode != OZIMMU_ACCUM_WIDE) ? rn_offset(beta) : 0;
     e = per_slice ? ozk::launch_split_A_per_slice(m, n, A, lda, k, beta, SA, eA, remA, st)
                   : ozk::launch_split_A(m, n, A, lda, k, beta, split_mode, offset, SA, eA, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;

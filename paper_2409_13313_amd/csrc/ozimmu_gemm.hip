@@ -23,8 +23,9 @@
 //     ra[i] = cB SA'[i] - pairs N cA cB,   cb[j] = cA SB'[j],
 // SA' / SB' being the sums of the stored bytes of row i / column j over the chunk's slices (differences of
 // the prefix sums the split kernels left behind the slices) and N the padded inner length: what the
-// epilogue finds in the accumulators is then C'' itself.  Every partial sum on the way lies in
-// [-12033, 4096] x (inner length of the chunk), inside INT32 under the paper's bound on the chunk length.
+// epilogue finds in the accumulators is then C'' itself.  With h = 2^(beta-1) and the offsets h - 1 every partial
+// sum on the way is a sum of terms q_a q_b in [-h^2, h^2] and -(h-1)(q_a + q_b + h - 1) in (-3 h^2, h^2): below
+// 0.75 x 4^beta x (inner length of the chunk) in magnitude, inside INT32 by the paper's choice of the chunk length.
 // With `finish` set the last chunk of a tile also applies step (v) of the scheme in its epilogue:
 //     out = fl(fl(alpha d) + fl(cbeta c_old))   (cbeta == 0: c_old is not read),  d the finished sum.
 //

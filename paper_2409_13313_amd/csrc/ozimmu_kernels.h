@@ -9,7 +9,7 @@ namespace ozk {
 
 // Step (i): row exponents + slices of A.  split_mode 0: round to nearest, ceil exponent (Algorithm 8);
 // 1: bit-mask digits, floor exponent (Algorithm 3).  SA is a whole stack (ozl::stack_bytes): slices, prefix row
-// sums, trailer; `offset` is the stack's offset c (stored byte = slice integer + c; 63 needs |q| <= 64).
+// sums, trailer; `offset` is the stack's offset c (stored byte = slice integer + c; needs |q + c| <= 127).
 hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int split_mode,
                           int offset, int8_t* SA, int32_t* eA, hipStream_t st);
 // Step (ii): column exponents + slices of B (the same applied to B^T).

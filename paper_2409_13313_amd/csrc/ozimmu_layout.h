@@ -15,23 +15,24 @@
 // 16-byte operand fetches of v_mfma_i32_32x32x32_i8 (consecutive rows, one
 // logical chunk) of any 16 consecutive lanes cover all 64 LDS banks once.
 //
-// Stored bytes are OFFSET-ENCODED: a stack carries one offset c (0 or 63) and
-// the byte of an element is q + c, q being the slice integer of the method
-// (inner padding is q = 0 like any zero; padding ROWS may hold anything that is
-// consistent with their row sums: their results are never stored).  Round-to-nearest
-// slices obey -64 <= q <= 64, so with c = 63 every byte lies in [-1, 127] and
-// practically all are non-negative: the matrix cores draw measurably less
-// power on operands of one sign (their sustained clock is higher), and
+// Stored bytes are OFFSET-ENCODED: a stack carries one offset c and the byte of
+// an element is q + c, q being the slice integer of the method (inner padding
+// is q = 0 like any zero; padding ROWS may hold anything that is consistent
+// with their row sums: their results are never stored).  Round-to-nearest
+// slices obey |q| <= 2^(beta-1) and are stored with c = 2^(beta-1) - 1 (63 for
+// beta = 7: bytes in [-1, 127], practically all non-negative); other slices
+// with c = 0.  Why: the matrix cores draw measurably less power on operands of
+// one sign (their sustained clock is higher), and
 //   sum_l (a'_l - cA)(b'_l - cB) = sum_l a'_l b'_l - cB sum_l a'_l - cA sum_l b'_l + N cA cB
-// (l over the N = inner_padded(n) stored positions)
-// gives the product of the slice integers back exactly from the product of the
-// stored bytes and the row sums of the stored bytes (INT32, wrap-around exact:
-// |a'|, |b'| <= 127 keeps even the uncorrected sums of a chunk below 2^31 under
-// the paper's bound on the chunk length).  Behind the k slices a stack therefore
-// holds, for every padded row R, the PREFIX sums P[s][R] = sum over slices
-// 1..s+1 and all inner l of the stored bytes (k arrays of rows_padded INT32; the
-// sum over any range of consecutive slices is a difference of two entries), and
-// a 256-byte trailer whose first INT32 is c.
+// (l over the N = inner_padded(n) stored positions) gives the product of the
+// slice integers back exactly from the product of the stored bytes and the row
+// sums of the stored bytes, in INT32: |a'|, |b'| <= 2^beta - 1 is the magnitude
+// the paper's bound on the chunk length is derived for, so the sums of stored
+// bytes fit as the sums of slice integers do.  Behind the k slices a stack
+// therefore holds, for every padded row R, the PREFIX sums P[s][R] = sum over
+// slices 1..s+1 and all inner l of the stored bytes (k arrays of rows_padded
+// INT32; the sum over any range of consecutive slices is a difference of two
+// entries), and a 256-byte trailer whose first INT32 is c.
 #pragma once
 #include <cstdint>
 #include <cstddef>

@@ -158,6 +158,33 @@ def test_extreme_slice_values_long_inner_dimension(oz):
     assert not oz.gemm_group(3, n, 2, SA, k, SB, k, 3, 1, 2).cpu().numpy().any()
 
 
+@pytest.mark.parametrize("n,k", [(16384, 8), (2 ** 17 + 128, 6), (2 ** 17, 5)])
+def test_near_maximal_slices_everywhere_stay_inside_int32(oz, n, k):
+    # every entry is the same x = 2^e (h - 1/2 - 2^-20) / h, h = 2^(beta-1): its first slice is h - 1, its second
+    # h (the largest magnitudes), in every row and column, so every chunk sum is as large as the data can make
+    # it; with the sign pattern below the products keep one sign along the whole inner dimension.  Pair
+    # products, chunk sums over r pairs and D must still be the oracle's.
+    beta, r = oracle.params(n)
+    h = 2.0 ** (beta - 1)
+    x = (h - 0.5 - 2.0 ** -20) / h
+    m, p = 5, 3
+    A = np.full((m, n), x)
+    B = np.full((n, p), x)
+    A[1] = -x                      # a row of the other sign
+    B[:, 2] = -x
+    SAo, _ = oracle.split_rows(A, k, beta)
+    SBo, _ = oracle.split_cols(B, k, beta)
+    assert SAo[0].max() == h - 1 and SAo[1].max() == h
+    SA, eA = oz.split_A(dev(A), k)
+    SB, eB = oz.split_B(dev(B), k)
+    assert np.array_equal(oz.export_slices(m, n, k, SA).cpu().numpy(), SAo)
+    assert np.array_equal(oz.export_slices(p, n, k, SB).cpu().numpy().transpose(0, 2, 1), SBo)
+    for (g, s0, s1) in [(2, 1, 1), (4, 2, 2), (3, 1, min(2, r)), (k + 1, 1, min(k, r))]:
+        C = oz.gemm_group(m, n, p, SA, k, SB, k, g, s0, s1).cpu().numpy()
+        assert np.array_equal(C, oracle.group_chunk(SAo, SBo, g, s0, s1)), (g, s0, s1)
+    assert np.array_equal(oz.dgemm(dev(A), dev(B), k).cpu().numpy(), oracle.dgemm(A, B, k))
+
+
 # --------------------------------------------------------------------------- accumulation
 def test_accumulate_matches_oracle_bit_exact(oz):
     rng = np.random.Generator(np.random.PCG64(3))

@@ -95,6 +95,8 @@ inline int64_t output_tiles(int64_t m, int64_t p)
 // The chunk-parallel way (see run_schedule) keeps one block per (chunk, tile): used for outputs of few tiles whose
 // tiles times chunks stay within this many blocks (128 MiB).
 constexpr int64_t CHUNK_PARALLEL_MAX_BLOCKS = 512;
+// Inner dimensions above this make the persistent kernel wait for the whole grid at chunk starts.
+constexpr int64_t GRID_WAIT_MIN_INNER = 8192 + 512;
 inline int64_t chunks_of(int k, int64_t r)
 {
     int64_t w = 0;
@@ -177,6 +179,8 @@ ozk::GemmArgs make_args(int64_t m, int64_t n, int64_t p, const int8_t* SA, int k
     a.zsplit = 1;
     a.sync = static_cast<unsigned*>(scratch);
     a.spin_limit = 64;  // polls (about 0.1 us each) before a workgroup stops waiting for its team
+    // the grid-wide wait pays only when the operand panels are long (see arrive_and_wait2)
+    a.grid_spin_limit = n > GRID_WAIT_MIN_INNER ? 64 : 0;
     a.sync_epoch = 0;
     a.alpha = 1.0;
     return a;
@@ -244,6 +248,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             a.zsplit = best_z;
             a.nchunks = (int)w;
             a.spin_limit = 0;  // the items of a team are different chunks: nothing to line up
+            a.grid_spin_limit = 0;
             e = ozk::launch_gemm(a, 3, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;
             ozk::TileAccArgs t{};

@@ -61,7 +61,8 @@ struct GemmArgs {
     double* Cout;
     int64_t ldco;
     unsigned* sync;        // 8 x 16 counters, zeroed by launch_gemm: [16 x] per-XCD soft barrier, [1] whole grid
-    int spin_limit;        // polls before a soft barrier gives up
+    int spin_limit;        // polls before the soft barrier of an XCD's team gives up
+    int grid_spin_limit;   // the same for the soft barrier of the whole grid (0: workgroups arrive, none waits)
     int num_cu;            // compute units of the device: the persistent grid has one workgroup on each
     int sync_epoch;        // 0: launch_gemm zeroes the counters; e > 0: e single-chunk launches of this very geometry
                            // have used them since (the split-inner schedule: one reset for all its chunks)

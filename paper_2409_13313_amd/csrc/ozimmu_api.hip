@@ -206,8 +206,16 @@ struct Finish {
 // schedule: 0 = choose, OZIMMU_SCHEDULE_ONE_LAUNCH, OZIMMU_SCHEDULE_SPLIT_INNER (honoured when possible).
 int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, const int32_t* eA,
                  const int32_t* eB, int k, int64_t r, bool per_slice, int schedule, double* D, int64_t ldd,
-                 const Finish& fin, int32_t* partial, int64_t partial_capacity, void* scratch, int num_cu, hipStream_t st)
+                 const Finish& fin, int32_t* partial, int64_t partial_capacity, void* scratch, int num_cu, hipStream_t st,
+                 bool sync_clean = false)
 {
+    // sync_clean: the caller has already zeroed the soft-barrier counters in `scratch` (the first GEMM launch
+    // then need not; later ones of the same call find them used and do)
+    auto take_clean = [&]() -> int {
+        const int c = sync_clean ? 1 : 0;
+        sync_clean = false;
+        return c;
+    };
     const int beta = beta_of(n);
     const int r_eff = (int)(r < k ? r : k);
     const int KT = (int)(ozl::inner_padded(n) / ozl::TILE_K);
@@ -249,6 +257,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             a.nchunks = (int)w;
             a.spin_limit = 0;  // the items of a team are different chunks: nothing to line up
             a.grid_spin_limit = 0;
+            a.sync_zeroed = take_clean();
             e = ozk::launch_gemm(a, 3, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;
             ozk::TileAccArgs t{};
@@ -317,6 +326,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         a.cbeta = fin.cbeta;
         a.Cout = fin.Cout;
         a.ldco = fin.ldco;
+        a.sync_zeroed = take_clean();
         const hipError_t e = ozk::launch_gemm(a, per_slice ? 2 : 1, st);
         if (e != hipSuccess) return OZIMMU_ERR_HIP;
     }
@@ -334,6 +344,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             a.C = partial;
             a.zsplit = Z;
             a.sync_epoch = epoch++;
+            a.sync_zeroed = take_clean();
             e = ozk::launch_gemm(a, 3, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;
             ozk::TileAccArgs t{};
@@ -556,7 +567,8 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
                           : ozk::launch_split_A(m, n, A, lda, k, bt, 0, rn_offset(bt), SA, eA, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     e = transB ? ozk::launch_split_A(p, n, B, ldb, k, bt, 0, rn_offset(bt), SB, eB, st)
-               : ozk::launch_split_B(n, p, B, ldb, k, bt, 0, rn_offset(bt), SB, eB, st);
+               : ozk::launch_split_B(n, p, B, ldb, k, bt, 0, rn_offset(bt), SB, eB, st, static_cast<uint32_t*>(scratch),
+                                     ozk::SYNC_WORDS);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
     // Step (v) rides on the epilogue of every tile's last chunk.  beta == 0: the running sum lives in C and the
@@ -565,7 +577,7 @@ int ozimmu_gemm_ex(int transA, int transB, int64_t m, int64_t n, int64_t p, doub
     const bool in_place = beta == 0.0;
     const Finish fin = {!(alpha == 1.0 && beta == 0.0), alpha, beta, C, ldc};
     return run_schedule(m, n, p, SA, SB, eA, eB, k, r, false, 0, in_place ? C : Dw, in_place ? ldc : p, fin, partial,
-                        blocks, scratch, ds.num_cu, st);
+                        blocks, scratch, ds.num_cu, st, !transB);
 }
 
 int ozimmu_dgemm(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, const double* B, int64_t ldb,
@@ -746,7 +758,8 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
                   : ozk::launch_split_A(m, n, A, lda, k, beta, split_mode, offset, SA, eA, st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     e = per_slice ? ozk::launch_split_B_per_slice(n, p, B, ldb, k, beta, SB, eB, remB, st)
-                  : ozk::launch_split_B(n, p, B, ldb, k, beta, split_mode, offset, SB, eB, st);
+                  : ozk::launch_split_B(n, p, B, ldb, k, beta, split_mode, offset, SB, eB, st,
+                                        static_cast<uint32_t*>(scratch), ozk::SYNC_WORDS);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
     e = mark(1);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
@@ -760,7 +773,7 @@ int dgemm_impl(int64_t m, int64_t n, int64_t p, const double* A, int64_t lda, co
         capacity = (int64_t)((static_cast<char*>(workspace) + workspace_bytes - reinterpret_cast<char*>(partial)) /
                              BLOCK_BYTES);
     const int rc = run_schedule(m, n, p, SA, SB, eA, eB, k, r, per_slice, schedule, D, ldd, no_finish, partial,
-                                capacity, scratch, ds.num_cu, st);
+                                capacity, scratch, ds.num_cu, st, !per_slice);
     if (rc != OZIMMU_OK) return rc;
     return hip_status(mark(2));
 }

@@ -846,7 +846,9 @@ hipError_t launch_gemm(const GemmArgs& a_in, int fused, hipStream_t st)
         return hipErrorInvalidValue;
     int nwg = a.num_cu > 0 ? a.num_cu : 1;
     if (tiles < nwg) nwg = (int)tiles;
-    if (a.sync_epoch == 0) hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(NXCD * 16), 0, st, a.sync);
+    static_assert(NXCD * 16 == SYNC_WORDS, "soft-barrier counters: 16 words per XCD");
+    if (a.sync_epoch == 0 && !a.sync_zeroed)
+        hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(SYNC_WORDS), 0, st, a.sync);
     dim3 grid((unsigned)nwg), block(256);
     if (fused == 3)
         hipLaunchKernelGGL((k_gemm<3, NSTAGES>), grid, block, smem, st, a, TM, TP);

@@ -13,8 +13,11 @@ namespace ozk {
 hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int split_mode,
                           int offset, int8_t* SA, int32_t* eA, hipStream_t st);
 // Step (ii): column exponents + slices of B (the same applied to B^T).
+// also_zero: optional array of also_zero_count 32-bit words that the first kernel of the split clears on the way
+// (the soft-barrier counters of the GEMM that follows: one launch less per call)
 hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int split_mode,
-                          int offset, int8_t* SB, int32_t* eB, hipStream_t st);
+                          int offset, int8_t* SB, int32_t* eB, hipStream_t st, uint32_t* also_zero = nullptr,
+                          int also_zero_count = 0);
 // Algorithm 5: round-to-nearest slices with one scale per slice.  e holds k arrays of exponents (slice-major);
 // rem is scratch for the remainders: m x inner_padded(n) doubles for A, n x p doubles for B.
 hipError_t launch_split_A_per_slice(int64_t m, int64_t n, const double* A, int64_t lda, int k, int beta, int8_t* SA,
@@ -22,6 +25,8 @@ hipError_t launch_split_A_per_slice(int64_t m, int64_t n, const double* A, int64
 hipError_t launch_split_B_per_slice(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int8_t* SB,
                                     int32_t* eB, double* rem, hipStream_t st);
 hipError_t launch_export(int64_t rows, int64_t n, int k, const int8_t* packed, int8_t* out, hipStream_t st);
+
+constexpr int SYNC_WORDS = 128;  // 32-bit soft-barrier counters at the start of the GEMM scratch (16 per XCD)
 
 struct GemmArgs {
     const int8_t* SA;      // packed stack of A slices
@@ -65,6 +70,7 @@ struct GemmArgs {
     int grid_spin_limit;   // the same for the soft barrier of the whole grid (0: workgroups arrive, none waits)
     int num_cu;            // compute units of the device: the persistent grid has one workgroup on each
     int sync_epoch;        // 0: launch_gemm zeroes the counters; e > 0: e single-chunk launches of this very geometry
+    int sync_zeroed;       // the caller has zeroed the counters already (with sync_epoch 0: no fill launch)
                            // have used them since (the split-inner schedule: one reset for all its chunks)
 };
 // Steps (iii) (+ (iv) when fused is 1 or 2) for the chunks of the schedule (Algorithm 6).  fused == 2: one scale

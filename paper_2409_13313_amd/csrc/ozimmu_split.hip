@@ -272,15 +272,18 @@ __global__ __launch_bounds__(256) void k_split_A_row(int64_t m, int64_t n, const
 // per-column maximum is merged into keys[] with a 32-bit atomic max (order
 // free, hence deterministic).
 // ---------------------------------------------------------------------------
-constexpr int LCH = 512;
+constexpr int LCH = 512;  // rows of B per workgroup of the column-maximum kernel (fewer for small B)
+// Marks a column entry of eB that still holds the key of the column maximum rather than the exponent decoded
+// from it (k_split_B decodes on the fly and stores the exponents): exponents are small, keys carry this bit.
+constexpr uint32_t RAW_KEY_TAG = 0x40000000u;
 
 __global__ __launch_bounds__(256) void k_colmax_B(int64_t n, int64_t p, const double* __restrict__ B, int64_t ldb,
-                                                  uint32_t* __restrict__ keys)
+                                                  uint32_t* __restrict__ keys, int lch, uint32_t tag)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t j = (int64_t)blockIdx.y * 64 + lane;
-    const int64_t l0 = (int64_t)blockIdx.x * LCH;
-    const int64_t l1 = l0 + LCH < n ? l0 + LCH : n;
+    const int64_t l0 = (int64_t)blockIdx.x * lch;
+    const int64_t l1 = l0 + lch < n ? l0 + lch : n;
     __shared__ uint64_t part[4][64];
     uint64_t mx = 0;
     if (j < p) {
@@ -294,8 +297,26 @@ __global__ __launch_bounds__(256) void k_colmax_B(int64_t n, int64_t p, const do
     if (w == 0 && j < p) {
         for (int q = 1; q < 4; ++q) mx = part[q][lane] > mx ? part[q][lane] : mx;
         uint32_t key = exp_key(mx);
-        if (key) atomicMax(keys + j, key);
+        if (key) atomicMax(keys + j, tag | key);
     }
+}
+
+// rows per workgroup of k_colmax_B: LCH, halved while that leaves the chip short of workgroups
+inline int colmax_rows(int64_t n, int64_t p)
+{
+    int lch = LCH;
+    while (lch > 16 && ((n + lch - 1) / lch) * ((p + 63) / 64) < 1024) lch /= 2;
+    return lch;
+}
+
+// two fills in one launch: x[0, cx) = vx and y[0, cy) = vy, then z[0, cz) = 0 (any count may be 0)
+__global__ void k_fill3_u32(int64_t cx, uint32_t* x, uint32_t vx, int64_t cy, uint32_t* y, uint32_t vy, int64_t cz,
+                            uint32_t* z)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < cx) x[i] = vx;
+    if (i < cy) y[i] = vy;
+    if (i < cz) z[i] = 0u;
 }
 
 __global__ void k_fill_u32(int64_t count, uint32_t* x, uint32_t v)
@@ -338,7 +359,7 @@ constexpr int PITCH = 33;  // dwords per column row in LDS (32 data + 1 pad)
 template <bool MASK>
 __global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const double* __restrict__ B, int64_t ldb,
                                                  int k, int beta, int c, int8_t* __restrict__ SB,
-                                                 const int32_t* __restrict__ eB, int32_t* __restrict__ P,
+                                                 int32_t* eB, int32_t* __restrict__ P,
                                                  int32_t* __restrict__ trailer, int64_t Npad, int64_t Rpad,
                                                  int64_t slice_stride, int blocks_per_wg)
 {
@@ -350,7 +371,16 @@ __global__ __launch_bounds__(256) void k_split_B(int64_t n, int64_t p, const dou
     const int64_t KT = Npad / TILE_K;
     const double two_beta = (double)(1 << beta);
     const bool col_ok = j < p;
-    const int sc = beta - 1 - (col_ok ? eB[j] : 0);
+    // eB[j] holds the tagged key of the column maximum until the workgroups of the first inner block have
+    // replaced it by the exponent; a workgroup that reads it meanwhile gets one or the other, and both give e
+    int e = 0;
+    if (col_ok) {
+        const uint32_t v = __hip_atomic_load(reinterpret_cast<uint32_t*>(eB) + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        e = (v & 0xc0000000u) == RAW_KEY_TAG ? key_to_exp<MASK>(v - RAW_KEY_TAG) : (int)v;
+        if (blockIdx.x == 0 && w == 0)
+            __hip_atomic_store(reinterpret_cast<uint32_t*>(eB) + j, (uint32_t)e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const int sc = beta - 1 - e;
     if (blockIdx.x == 0 && blockIdx.y == 0 && t == 0) trailer[0] = c;
     for (int i = t; i < k * 64; i += 256) colsum[i / 64][i % 64] = 0;
     // write-out mapping: 8 lanes per column row, 32 column rows per pass
@@ -627,29 +657,31 @@ hipError_t launch_split_A(int64_t m, int64_t n, const double* A, int64_t lda, in
 }
 
 hipError_t launch_split_B(int64_t n, int64_t p, const double* B, int64_t ldb, int k, int beta, int split_mode,
-                          int offset, int8_t* SB, int32_t* eB, hipStream_t st)
+                          int offset, int8_t* SB, int32_t* eB, hipStream_t st, uint32_t* also_zero,
+                          int also_zero_count)
 {
     const int64_t Rpad = ozl::rows_padded(p), Npad = ozl::inner_padded(n);
     const int64_t stride = ozl::slice_bytes(p, n);
     int32_t* P = reinterpret_cast<int32_t*>(SB + ozl::sums_offset(p, n, k));
     int32_t* trailer = reinterpret_cast<int32_t*>(SB + ozl::trailer_offset(p, n, k));
-    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p,
-                       reinterpret_cast<uint32_t*>(eB), 0u);
     const int64_t nsums = (int64_t)k * Rpad;
-    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nsums + 255) / 256)), dim3(256), 0, st, nsums,
-                       reinterpret_cast<uint32_t*>(P), 0u);
-    dim3 gmax((unsigned)((n + LCH - 1) / LCH), (unsigned)((p + 63) / 64));
-    hipLaunchKernelGGL(k_colmax_B, gmax, dim3(256), 0, st, n, p, B, ldb, reinterpret_cast<uint32_t*>(eB));
+    const int64_t nfill = nsums > p ? (nsums > also_zero_count ? nsums : also_zero_count)
+                                    : (p > also_zero_count ? p : also_zero_count);
+    hipLaunchKernelGGL(k_fill3_u32, dim3((unsigned)((nfill + 255) / 256)), dim3(256), 0, st, p,
+                       reinterpret_cast<uint32_t*>(eB), RAW_KEY_TAG, nsums, reinterpret_cast<uint32_t*>(P), 0u,
+                       also_zero ? also_zero_count : 0, also_zero);
+    const int lch = colmax_rows(n, p);
+    dim3 gmax((unsigned)((n + lch - 1) / lch), (unsigned)((p + 63) / 64));
+    hipLaunchKernelGGL(k_colmax_B, gmax, dim3(256), 0, st, n, p, B, ldb, reinterpret_cast<uint32_t*>(eB), lch,
+                       RAW_KEY_TAG);
     // a workgroup takes 4 consecutive blocks of 128 inner rows once there are enough blocks to fill the chip anyway
     const int64_t blocks = Npad / 128;
     const int per_wg = blocks >= 32 ? 4 : 1;
     dim3 grid((unsigned)((blocks + per_wg - 1) / per_wg), (unsigned)(Rpad / 64));
     if (split_mode == 0) {
-        hipLaunchKernelGGL(k_decode_keys<false>, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
         hipLaunchKernelGGL(k_split_B<false>, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, offset, SB, eB, P, trailer,
                            Npad, Rpad, stride, per_wg);
     } else {
-        hipLaunchKernelGGL(k_decode_keys<true>, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, st, p, eB);
         hipLaunchKernelGGL(k_split_B<true>, grid, dim3(256), 0, st, n, p, B, ldb, k, beta, offset, SB, eB, P, trailer,
                            Npad, Rpad, stride, per_wg);
     }
@@ -685,7 +717,7 @@ hipError_t launch_split_B_per_slice(int64_t n, int64_t p, const double* B, int64
     const int64_t nk = (int64_t)k * p;
     hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, st, nk, keys, 0u);
     dim3 gmax((unsigned)((n + LCH - 1) / LCH), (unsigned)((p + 63) / 64));
-    hipLaunchKernelGGL(k_colmax_B, gmax, dim3(256), 0, st, n, p, B, ldb, keys);
+    hipLaunchKernelGGL(k_colmax_B, gmax, dim3(256), 0, st, n, p, B, ldb, keys, LCH, 0u);
     dim3 grid((unsigned)(Npad / 128), (unsigned)(Rpad / 64));
     for (int s = 0; s < k; ++s)
         hipLaunchKernelGGL(k_split_B_ps, grid, dim3(256), 0, st, n, p, s == 0 ? B : rem, s == 0 ? ldb : p, beta,

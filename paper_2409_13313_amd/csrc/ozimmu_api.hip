@@ -92,9 +92,9 @@ inline int64_t output_tiles(int64_t m, int64_t p)
 {
     return (ozl::rows_padded(m) / ozl::TILE_R) * (ozl::rows_padded(p) / ozl::TILE_R);
 }
-// The chunk-parallel way (see run_schedule) keeps one block per (chunk, tile): used for outputs of few tiles whose
-// tiles times chunks stay within this many blocks (128 MiB).
-constexpr int64_t CHUNK_PARALLEL_MAX_BLOCKS = 512;
+// The chunk-parallel way (see run_schedule) keeps one block per (chunk, tile): used for outputs of fewer tiles than
+// the chip has compute units whose tiles times chunks stay within this many blocks (1 GiB).
+constexpr int64_t CHUNK_PARALLEL_MAX_BLOCKS = 4096;
 // Inner dimensions above this make the persistent kernel wait for the whole grid at chunk starts.
 constexpr int64_t GRID_WAIT_MIN_INNER = 8192 + 512;
 inline int64_t chunks_of(int k, int64_t r)
@@ -114,8 +114,10 @@ inline int64_t partial_blocks(int64_t m, int64_t n, int64_t p, int k)
 {
     const int64_t base = min_partial_blocks(m, p);
     if (n < 1 || n > MAX_INNER || k < 1) return base;
-    const int64_t items = output_tiles(m, p) * chunks_of(k, r_of(n, beta_of(n)));
-    return (items <= CHUNK_PARALLEL_MAX_BLOCKS && items > base) ? items : base;
+    const int64_t T = output_tiles(m, p);
+    const int64_t items = T * chunks_of(k, r_of(n, beta_of(n)));
+    // (the chunk-parallel way is for fewer tiles than compute units: 256 on the chip this is written for)
+    return (T < 256 && items <= CHUNK_PARALLEL_MAX_BLOCKS && items > base) ? items : base;
 }
 constexpr int64_t BLOCK_BYTES = 4 * 256 * 256;
 
@@ -229,25 +231,32 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     // chunk.  Times in microseconds as in the model below; a work item pays about 15 us of prologue and epilogue.
     if (!per_slice && partial && T * w <= CHUNK_PARALLEL_MAX_BLOCKS && T * w <= partial_capacity && T < num_cu &&
         schedule != OZIMMU_SCHEDULE_ONE_LAUNCH && schedule != OZIMMU_SCHEDULE_SPLIT_INNER) {
-        const double stage_us = 0.68, item_us = 15.0;
+        // (measured on MI355X: a stage 0.68 us; prologue + epilogue of an item 15 us, 22 us when the epilogue adds
+        // with atomics; clearing the blocks 5 us + 0.065 us per block; the accumulation kernel 15 us + 0.058 us
+        // per block)
+        const double stage_us = 0.68;
         const double pairs = (double)k * (k + 1) / 2;
         const int longest = r_eff < k ? r_eff : k;  // pairs of the longest chunk
+        const double blocks = (double)(T * w);
         const double one_launch_us = stage_us * pairs * KT + 35.0 * (double)w;  // every tile at once, chunks in sequence
         double best = 0.0;
         int best_z = 0;
         const int zmax = KT / 4 > 0 ? KT / 4 : 1;
         for (int z = 1; z <= zmax; z *= 2) {
+            const double item_us = z > 1 ? 22.0 : 15.0;
             const double total = (double)T * (stage_us * pairs * KT + item_us * (double)w * z);
             const double longest_item = stage_us * longest * KT / z + item_us;
-            double t = total / (double)num_cu * 1.25;  // static assignment of unequal items
+            // items are handed out longest first to whichever workgroup is free: the last ones end unevenly
+            double t = total / (double)num_cu + 0.25 * longest_item;
             if (t < longest_item) t = longest_item;
-            t += 25.0;  // one more launch, the accumulation kernel, clearing the blocks
+            t += 15.0 + 0.058 * blocks;               // the accumulation kernel
+            if (z > 1) t += 5.0 + 0.065 * blocks;     // clearing the blocks for the atomic adds
             if (best_z == 0 || t < best) {
                 best = t;
                 best_z = z;
             }
         }
-        if (schedule == OZIMMU_SCHEDULE_CHUNK_PARALLEL || best < 0.8 * one_launch_us) {
+        if (schedule == OZIMMU_SCHEDULE_CHUNK_PARALLEL || best < 0.9 * one_launch_us) {
             hipError_t e = hipSuccess;
             if (best_z > 1) e = ozk::launch_fill_zero_i32(T * w * 256 * 256, partial, st);
             if (e != hipSuccess) return OZIMMU_ERR_HIP;

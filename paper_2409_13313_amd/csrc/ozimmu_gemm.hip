@@ -70,7 +70,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // A tile + B tile = 32 KiB
 constexpr int NLOAD = TILE_BYTES / (256 * 16);    // 16-byte copies per thread and operand tile = 4
 constexpr int EPI_ROWS = 2;                       // 32 x 32 tiles per batch of the plain epilogue (16 D loads in flight per lane each)
-constexpr int EXP_BYTES = 2 * 256 * 8;            // (exponent, offset correction) of the tile's 256 rows and 256 columns, kept in LDS
+constexpr int EXP_BYTES = 2 * 256 * 8 + 64;       // (exponent, offset correction) of the tile's 256 rows and 256 columns, kept in LDS; work-item ticket
 
 // Linear tile order: bands of GROUP tile rows, each walked column by column, so
 // that 32 consecutive tiles form an 8 x 4 patch (8 A tiles + 4 B tiles per stage).
@@ -240,7 +240,22 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     unsigned* const all_ctr = a.sync + 1;
     unsigned all_target = (unsigned)a.sync_epoch * (unsigned)T;
 
-    for (int local = member; local < range_cnt; local += team) {
+    // A launch over all chunks of the schedule hands its work items out through a counter instead: the items
+    // differ in length (1 to r slice pairs), the longest come first, and whoever is free takes the next one.
+    // The static ranges above would give one XCD all the long chunks.  Every workgroup leaves once the counter
+    // has passed the last item.  (The counter is one of the soft-barrier words, zero at the start of a launch.)
+    unsigned* const ticket_ctr = a.sync + 2;
+    volatile int* const lds_ticket = reinterpret_cast<volatile int*>(lds + NS * STAGE_BYTES + 2 * 256 * 8);
+
+    for (int local = member; all_chunks || local < range_cnt; local += team) {
+        int item = range_off + local;
+        if (all_chunks) {
+            if (t == 0)
+                *lds_ticket = (int)__hip_atomic_fetch_add(ticket_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();  // (the next write to the ticket word is a whole work item away)
+            item = __builtin_amdgcn_readfirstlane(*lds_ticket);
+            if (item >= T) break;
+        }
         const int round_first = local - member;
         const unsigned participants = (unsigned)((range_cnt - round_first) < team ? (range_cnt - round_first) : team);
         unsigned all_participants = 0;  // workgroups of all XCDs that work on a tile in this round
@@ -255,7 +270,6 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
             }
         }
         int tm, tp;
-        const int item = range_off + local;
         // MODE 3: part-major order, so that the 32 work items of a team are 32 tiles cut at the same place of
         // the inner dimension and share operand tiles in L2 like the tiles of the un-cut kernel
         // (integer divisions run on the vector unit: readfirstlane tells the compiler the results are uniform)

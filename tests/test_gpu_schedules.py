@@ -31,6 +31,7 @@ SHAPES = [
     (1024, 1024, 1024, 12, 0.5),   # 16 tiles, 4 parts, chunks of up to 12 pairs
     (256, 256, 256, 8, 0.5),       # one group of stages per pair: nothing to cut, falls back to one launch
     (40, 2 ** 17 + 128, 64, 4, 0.5),   # beta = 6
+    (1536, 512, 1792, 8, 0.5),     # 42 tiles x 8 chunks: more work items than workgroups in the chunk-parallel launch
 ]
 
 
@@ -103,8 +104,9 @@ def test_small_workspace_falls_back_to_the_other_schedules(oz):
     # gives the same D through the other schedules; the requirement is not monotone in k, the least one is
     m, n, p, k = 1024, 1024, 1024, 20
     assert oz.workspace_bytes(m, n, p, k) > oz.STATIC_WORKSPACE_BYTES >= oz.workspace_bytes_min(m, n, p, k)
-    assert oz.workspace_bytes(2048, 2048, 2048, 8) > oz.workspace_bytes(2048, 2048, 2048, 12)
-    assert oz.workspace_bytes_min(2048, 2048, 2048, 8) < oz.workspace_bytes_min(2048, 2048, 2048, 12)
+    # (240 tiles: 14 chunks each stay within the 4096 blocks of the chunk-parallel way, 20 do not)
+    assert oz.workspace_bytes(3840, 256, 4096, 14) > oz.workspace_bytes(3840, 256, 4096, 20)
+    assert oz.workspace_bytes_min(3840, 256, 4096, 14) < oz.workspace_bytes_min(3840, 256, 4096, 20)
     A, B = inputs.phi_pair(m, n, p, 0.5, seed=97)
     dA, dB = dev(A), dev(B)
     want = oz.dgemm(dA, dB, k)

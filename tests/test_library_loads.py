@@ -67,9 +67,9 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.ozimmu_dgemm(4, 2 ** 29 + 1, 4, fake, 2 ** 30, fake, 4, fake, 4, 8, fake, 1 << 30, None) == -2
     assert lib.ozimmu_dgemm(0, 4, 4, None, 4, None, 4, None, 4, 8, None, 0, None) == 0             # empty: nothing to do
     # workspace = scratch + exponents + the two slice stacks + INT32 blocks of 256 x 256: one per output tile for at
-    # most 128 tiles, or one per tile and chunk of the schedule when that stays within 512 blocks.  A stack = k
-    # padded slices (rows padded to 256, inner index to 256) + k arrays of padded-rows INT32 row sums (rounded up to
-    # 256 bytes) + a 256-byte trailer
+    # most 128 tiles, or one per tile and chunk of the schedule when the output has fewer than 256 tiles and that
+    # stays within 4096 blocks.  A stack = k padded slices (rows padded to 256, inner index to 256) + k arrays of
+    # padded-rows INT32 row sums (rounded up to 256 bytes) + a 256-byte trailer
     blk = 4 * 256 * 256
 
     def stack(rows_padded, inner_padded, k):
@@ -79,8 +79,17 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.ozimmu_workspace_bytes(256, 128, 256, 8) == 512 + 2 * 1024 + 2 * stack(256, 256, 8) + 8 * blk
     # 2 tiles x 3 chunks
     assert lib.ozimmu_workspace_bytes(257, 257, 1, 3) == 512 + 1280 + 256 + stack(512, 512, 3) + stack(256, 512, 3) + 6 * blk
-    big = lib.ozimmu_workspace_bytes(4096, 256, 4096, 8)       # 256 tiles x 8 chunks > 512: blocks for 128 tiles
+    # 144 tiles x 8 chunks
+    assert lib.ozimmu_workspace_bytes(3072, 256, 3072, 8) == 512 + 2 * 4 * 3072 + 2 * stack(3072, 256, 8) + 1152 * blk
+    big = lib.ozimmu_workspace_bytes(4096, 256, 4096, 8)       # 256 tiles: blocks for 128 tiles
     assert big == 512 + 2 * 4 * 4096 + 2 * stack(4096, 256, 8) + 128 * blk
+    # 240 tiles x 20 chunks (n = 65536: r = 2) > 4096 blocks: blocks for 128 tiles
+    assert lib.ozimmu_workspace_bytes(3840, 65536, 4096, 10) == (512 + 4 * 3840 + 4 * 4096 + stack(3840, 65536, 10) +
+                                                                 stack(4096, 65536, 10) + 128 * blk)
+    lib.ozimmu_workspace_bytes_min.argtypes = [i64, i64, i64, ctypes.c_int]
+    lib.ozimmu_workspace_bytes_min.restype = ctypes.c_size_t
+    assert lib.ozimmu_workspace_bytes_min(3072, 256, 3072, 8) == 512 + 2 * 4 * 3072 + 2 * stack(3072, 256, 8) + 128 * blk
+
 
 def test_limits_are_reported_as_dimension_errors(lib):
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int

@@ -114,10 +114,11 @@ inline int64_t partial_blocks(int64_t m, int64_t n, int64_t p, int k)
 {
     const int64_t base = min_partial_blocks(m, p);
     if (n < 1 || n > MAX_INNER || k < 1) return base;
+    // (the chunk-parallel way takes the tiles that do not fill a round of the 256 compute units of the chip this is
+    // written for)
     const int64_t T = output_tiles(m, p);
-    const int64_t items = T * chunks_of(k, r_of(n, beta_of(n)));
-    // (the chunk-parallel way is for fewer tiles than compute units: 256 on the chip this is written for)
-    return (T < 256 && items <= CHUNK_PARALLEL_MAX_BLOCKS && items > base) ? items : base;
+    const int64_t items = (T % 256) * chunks_of(k, r_of(n, beta_of(n)));
+    return (items <= CHUNK_PARALLEL_MAX_BLOCKS && items > base) ? items : base;
 }
 constexpr int64_t BLOCK_BYTES = 4 * 256 * 256;
 
@@ -224,12 +225,15 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     const int64_t T = output_tiles(m, p);
     const int64_t w = chunks_of(k, r_eff);
 
-    // Third way, for outputs of few tiles: ONE launch whose work items are (chunk, inner part, tile), every chunk
-    // writing (or, when cut, atomically adding) its INT32 sums to a block of its own per tile, and one kernel that
-    // adds the chunks of every element in the order of Algorithm 6.  All chunks of all tiles run side by side, so a
-    // 1024^3 product occupies 128 compute units instead of 16; the price is 4 bytes of workspace per element and
-    // chunk.  Times in microseconds as in the model below; a work item pays about 15 us of prologue and epilogue.
-    if (!per_slice && partial && T * w <= CHUNK_PARALLEL_MAX_BLOCKS && T * w <= partial_capacity && T < num_cu &&
+    // Third way, for outputs of few tiles, or the tiles of a partly filled last round (`cand`, the last ones in band
+    // order): ONE launch whose work items are (chunk, inner part, tile), every chunk writing (or, when cut,
+    // atomically adding) its INT32 sums to a block of its own per tile, and one kernel that adds the chunks of every
+    // element in the order of Algorithm 6.  All chunks of all those tiles run side by side, so a 1024^3 product
+    // occupies 128 compute units instead of 16; the price is 4 bytes of workspace per element and chunk.
+    const int64_t cand = num_cu > 0 ? (T < num_cu ? T : T % num_cu) : 0;  // tiles of the partly filled round
+    int64_t cp_tail = 0;  // tiles that go this way
+    int cp_z = 1;
+    if (!per_slice && partial && cand >= 1 && cand * w <= CHUNK_PARALLEL_MAX_BLOCKS && cand * w <= partial_capacity &&
         schedule != OZIMMU_SCHEDULE_ONE_LAUNCH && schedule != OZIMMU_SCHEDULE_SPLIT_INNER) {
         // (measured on MI355X: a stage 0.68 us; prologue + epilogue of an item 15 us, 22 us when the epilogue adds
         // with atomics; clearing the blocks 5 us + 0.065 us per block; the accumulation kernel 15 us + 0.058 us
@@ -237,14 +241,15 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         const double stage_us = 0.68;
         const double pairs = (double)k * (k + 1) / 2;
         const int longest = r_eff < k ? r_eff : k;  // pairs of the longest chunk
-        const double blocks = (double)(T * w);
-        const double one_launch_us = stage_us * pairs * KT + 35.0 * (double)w;  // every tile at once, chunks in sequence
+        const double blocks = (double)(cand * w);
+        // one more round of the persistent launch: every tile at once, chunks in sequence
+        const double one_launch_us = stage_us * pairs * KT + 35.0 * (double)w;
         double best = 0.0;
         int best_z = 0;
         const int zmax = KT / 4 > 0 ? KT / 4 : 1;
         for (int z = 1; z <= zmax; z *= 2) {
             const double item_us = z > 1 ? 22.0 : 15.0;
-            const double total = (double)T * (stage_us * pairs * KT + item_us * (double)w * z);
+            const double total = (double)cand * (stage_us * pairs * KT + item_us * (double)w * z);
             const double longest_item = stage_us * longest * KT / z + item_us;
             // items are handed out longest first to whichever workgroup is free: the last ones end unevenly
             double t = total / (double)num_cu + 0.25 * longest_item;
@@ -257,43 +262,17 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             }
         }
         if (schedule == OZIMMU_SCHEDULE_CHUNK_PARALLEL || best < 0.9 * one_launch_us) {
-            hipError_t e = hipSuccess;
-            if (best_z > 1) e = ozk::launch_fill_zero_i32(T * w * 256 * 256, partial, st);
-            if (e != hipSuccess) return OZIMMU_ERR_HIP;
-            ozk::GemmArgs a = make_args(m, n, p, SA, k, SB, k, 2, k + 1, r_eff, 0, 0, scratch, num_cu);
-            a.C = partial;
-            a.zsplit = best_z;
-            a.nchunks = (int)w;
-            a.spin_limit = 0;  // the items of a team are different chunks: nothing to line up
-            a.grid_spin_limit = 0;
-            a.sync_zeroed = take_clean();
-            e = ozk::launch_gemm(a, 3, st);
-            if (e != hipSuccess) return OZIMMU_ERR_HIP;
-            ozk::TileAccArgs t{};
-            t.tile_begin = 0;
-            t.tile_count = (int)T;
-            t.m = m;
-            t.p = p;
-            t.Ct = partial;
-            t.eA = eA;
-            t.eB = eB;
-            t.D = D;
-            t.ldd = ldd;
-            t.finish = fin.on ? 1 : 0;
-            t.alpha = fin.alpha;
-            t.cbeta = fin.cbeta;
-            t.Cout = fin.Cout;
-            t.ldco = fin.ldco;
-            return hip_status(ozk::launch_accumulate_chunks(t, k, r_eff, beta, st));
+            cp_tail = cand;
+            cp_z = best_z;
         }
     }
 
     // tiles [0, T - tail) go to the persistent launch, the last `tail` tiles (band order) are cut Z ways
     int64_t tail = 0;
     int Z = 1;
-    if (!per_slice && partial && schedule != OZIMMU_SCHEDULE_ONE_LAUNCH && schedule != OZIMMU_SCHEDULE_CHUNK_PARALLEL) {
+    if (!per_slice && partial && cp_tail == 0 && schedule != OZIMMU_SCHEDULE_ONE_LAUNCH &&
+        schedule != OZIMMU_SCHEDULE_CHUNK_PARALLEL) {
         const int64_t ncu = num_cu;
-        const int64_t cand = ncu > 0 ? (T < ncu ? T : T % ncu) : 0;  // tiles of the partly filled round
         const int64_t zmax = KT / 4;  // every part gets at least one group of 4 stages of the shortest chunk
         if (cand >= 1 && cand <= SPLIT_INNER_MAX_TILES && zmax >= 2) {
             // Time per chunk in microseconds, from measurements on MI355X: a stage of the main loop takes
@@ -320,9 +299,9 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             }
         }
     }
-    if (T - tail > 0) {
+    if (T - tail - cp_tail > 0) {
         ozk::GemmArgs a = make_args(m, n, p, SA, k, SB, k, 2, k + 1, r_eff, 0, 0, scratch, num_cu);
-        a.tile_count = (int)(T - tail);
+        a.tile_count = (int)(T - tail - cp_tail);
         a.D = D;
         a.ldd = ldd;
         a.eA = eA;
@@ -338,6 +317,38 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         a.sync_zeroed = take_clean();
         const hipError_t e = ozk::launch_gemm(a, per_slice ? 2 : 1, st);
         if (e != hipSuccess) return OZIMMU_ERR_HIP;
+    }
+    if (cp_tail > 0) {
+        hipError_t e = hipSuccess;
+        if (cp_z > 1) e = ozk::launch_fill_zero_i32(cp_tail * w * 256 * 256, partial, st);
+        if (e != hipSuccess) return OZIMMU_ERR_HIP;
+        ozk::GemmArgs a = make_args(m, n, p, SA, k, SB, k, 2, k + 1, r_eff, 0, 0, scratch, num_cu);
+        a.tile_begin = (int)(T - cp_tail);
+        a.tile_count = (int)cp_tail;
+        a.C = partial;
+        a.zsplit = cp_z;
+        a.nchunks = (int)w;
+        a.spin_limit = 0;  // the items of a team are different chunks: nothing to line up
+        a.grid_spin_limit = 0;
+        a.sync_zeroed = take_clean();
+        e = ozk::launch_gemm(a, 3, st);
+        if (e != hipSuccess) return OZIMMU_ERR_HIP;
+        ozk::TileAccArgs t{};
+        t.tile_begin = (int)(T - cp_tail);
+        t.tile_count = (int)cp_tail;
+        t.m = m;
+        t.p = p;
+        t.Ct = partial;
+        t.eA = eA;
+        t.eB = eB;
+        t.D = D;
+        t.ldd = ldd;
+        t.finish = fin.on ? 1 : 0;
+        t.alpha = fin.alpha;
+        t.cbeta = fin.cbeta;
+        t.Cout = fin.Cout;
+        t.ldco = fin.ldco;
+        return hip_status(ozk::launch_accumulate_chunks(t, k, r_eff, beta, st));
     }
     if (tail == 0) return OZIMMU_OK;
     int first = 1;

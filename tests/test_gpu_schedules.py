@@ -138,12 +138,13 @@ def test_last_partial_round_cut_along_the_inner_dimension(oz, m, n, p, k):
     A, B = inputs.phi_pair(m, n, p, 1.0, seed=94)
     dA, dB = dev(A), dev(B)
     out = {}
-    for schedule in ("one_launch", "split_inner", "auto"):
+    for schedule in ("one_launch", "split_inner", "chunk_parallel", "auto"):
         D = torch.full((m, p), float("nan"), dtype=torch.float64, device="cuda")
         oz.dgemm_variant(dA, dB, k, "rn", "grouped", D=D, schedule=schedule)
         assert torch.isfinite(D).all(), schedule          # every tile written, by one path or the other
         out[schedule] = D
     assert torch.equal(out["one_launch"], out["split_inner"])
+    assert torch.equal(out["one_launch"], out["chunk_parallel"])
     assert torch.equal(out["one_launch"], out["auto"])
     I = inputs.sample_indices(m, 48, seed=1)
     J = inputs.sample_indices(p, 48, seed=2)

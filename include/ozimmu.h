@@ -80,8 +80,8 @@ size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k);
 
 /* Bytes of device workspace ozimmu_dgemm makes the best use of (scheduling scratch, exponents, the two slice
  * stacks and INT32 blocks of 256 x 256: one per output tile for up to 128 tiles, or, for outputs of few tiles,
- * one per tile and chunk of the schedule, at most 4096 = 1 GiB); host.  Not monotone in k (the per-chunk blocks
- * are only counted for outputs of fewer than 256 tiles and while tiles x chunks <= 4096). */
+ * one per chunk and tile of the last round of 256 tiles, at most 4096 = 1 GiB); host.  Not monotone in k (the
+ * per-chunk blocks are only counted while tiles x chunks <= 4096). */
 size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k);
 
 /* The least ozimmu_dgemm accepts (one block per output tile, at most 128): with less than
@@ -143,7 +143,8 @@ enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 
  *                                with integer atomics, then one accumulation kernel.  Chosen by default when
  *                                the inner dimension is long enough to pay for the extra launches; the flag
  *                                forces it wherever the inner dimension can be cut at all. */
-/*   OZIMMU_SCHEDULE_CHUNK_PARALLEL  for outputs of few tiles (< 256, tiles x chunks <= 4096): one launch whose workgroups
+/*   OZIMMU_SCHEDULE_CHUNK_PARALLEL  for outputs of at most 256 tiles, or the tiles of the last, partly filled round of
+ *                                256 of a larger one (tiles x chunks <= 4096): one launch whose workgroups
  *                                take (chunk, inner part, tile) work items, every chunk leaving its INT32 sums in
  *                                a block of its own, and one kernel that adds the chunks of each element in the
  *                                order of Algorithm 6.  All chunks run side by side (a 1024^3 product occupies

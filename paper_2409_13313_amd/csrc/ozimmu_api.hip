@@ -117,7 +117,7 @@ inline int64_t partial_blocks(int64_t m, int64_t n, int64_t p, int k)
     // (the chunk-parallel way takes the tiles that do not fill a round of the 256 compute units of the chip this is
     // written for)
     const int64_t T = output_tiles(m, p);
-    const int64_t items = (T % 256) * chunks_of(k, r_of(n, beta_of(n)));
+    const int64_t items = (T <= 256 ? T : T % 256) * chunks_of(k, r_of(n, beta_of(n)));
     return (items <= CHUNK_PARALLEL_MAX_BLOCKS && items > base) ? items : base;
 }
 constexpr int64_t BLOCK_BYTES = 4 * 256 * 256;
@@ -230,7 +230,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     // atomically adding) its INT32 sums to a block of its own per tile, and one kernel that adds the chunks of every
     // element in the order of Algorithm 6.  All chunks of all those tiles run side by side, so a 1024^3 product
     // occupies 128 compute units instead of 16; the price is 4 bytes of workspace per element and chunk.
-    const int64_t cand = num_cu > 0 ? (T < num_cu ? T : T % num_cu) : 0;  // tiles of the partly filled round
+    const int64_t cand = num_cu > 0 ? (T <= num_cu ? T : T % num_cu) : 0;  // tiles of the last round, if not full or the only one
     int64_t cp_tail = 0;  // tiles that go this way
     int cp_z = 1;
     if (!per_slice && partial && cand >= 1 && cand * w <= CHUNK_PARALLEL_MAX_BLOCKS && cand * w <= partial_capacity &&
@@ -242,8 +242,9 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         const double pairs = (double)k * (k + 1) / 2;
         const int longest = r_eff < k ? r_eff : k;  // pairs of the longest chunk
         const double blocks = (double)(cand * w);
-        // one more round of the persistent launch: every tile at once, chunks in sequence
-        const double one_launch_us = stage_us * pairs * KT + 35.0 * (double)w;
+        // one more round of the persistent launch: every tile at once, chunks in sequence, each with a fused
+        // epilogue in which all workgroups update D at the same time (measured 2.0 ms at 4096^3, k = 8)
+        const double one_launch_us = 0.70 * pairs * KT + 50.0 * (double)w;
         double best = 0.0;
         int best_z = 0;
         const int zmax = KT / 4 > 0 ? KT / 4 : 1;
@@ -261,7 +262,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
                 best_z = z;
             }
         }
-        if (schedule == OZIMMU_SCHEDULE_CHUNK_PARALLEL || best < 0.9 * one_launch_us) {
+        if (schedule == OZIMMU_SCHEDULE_CHUNK_PARALLEL || best < 0.97 * one_launch_us) {
             cp_tail = cand;
             cp_z = best_z;
         }

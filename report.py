@@ -309,10 +309,12 @@ def schedules(k=8, reps=5):
     import torch
     from paper_2409_13313_amd import inputs, ozimmu
     shapes = [(512, 512, 512), (1024, 1024, 1024), (2048, 2048, 2048), (2560, 2560, 2560), (3072, 3072, 3072),
+              (4096, 4096, 4096), (5120, 5120, 5120), (3072, 16384, 3072),
               (1024, 16384, 1024), (1024, 65536, 1024), (2048, 131072, 2048), (512, 131072, 512), (256, 262144, 256)]
-    print(f"### outputs of few 256 x 256 tiles, k={k}, phi=0.5; median of {reps}, ms (effective TFLOP/s)\n")
-    print("| m x n x p | tiles | one launch | split inner | what the library picks | native FP64 |")
-    print("|---|---|---|---|---|---|")
+    print(f"### outputs of few 256 x 256 tiles (or with a partly filled last round), k={k}, phi=0.5; "
+          f"median of {reps}, ms (effective TFLOP/s)\n")
+    print("| m x n x p | tiles | one launch | split inner | chunk parallel | what the library picks | native FP64 |")
+    print("|---|---|---|---|---|---|---|")
     for (m, n, p) in shapes:
         A, B = inputs.phi_pair(m, n, p, 0.5, seed=0)
         dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
@@ -320,7 +322,7 @@ def schedules(k=8, reps=5):
         ws = ozimmu.alloc_workspace(m, n, p, k)
         flops = 2.0 * m * n * p
         cells = []
-        for sched in ("one_launch", "split_inner", "auto"):
+        for sched in ("one_launch", "split_inner", "chunk_parallel", "auto"):
             run = lambda: ozimmu.dgemm_variant(dA, dB, k, "rn", "grouped", D=D, workspace=ws, schedule=sched)
             run()
             t = _median_ms(run, reps)

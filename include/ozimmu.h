@@ -152,7 +152,13 @@ enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 
  *                                workspace has room for the blocks (ozimmu_workspace_bytes includes them,
  *                                ozimmu_workspace_bytes_min does not); the flag forces it wherever it fits and
  *                                is ignored elsewhere. */
-enum { OZIMMU_SCHEDULE_ONE_LAUNCH = 0x100, OZIMMU_SCHEDULE_SPLIT_INNER = 0x200, OZIMMU_SCHEDULE_CHUNK_PARALLEL = 0x400 };
+/*   OZIMMU_SCHEDULE_QUEUE          every (chunk, tile) is a work item of one launch, handed out round by round
+ *                                (256 tiles, all their chunks, longest chunks first) through a counter; an item
+ *                                leaves its INT32 sums in a block, and the workgroup that completes a tile's last
+ *                                block adds the tile's chunks up in the order of Algorithm 6.  The blocks are
+ *                                recycled every few rounds.  Ignored where the workspace has no room for it. */
+enum { OZIMMU_SCHEDULE_ONE_LAUNCH = 0x100, OZIMMU_SCHEDULE_SPLIT_INNER = 0x200, OZIMMU_SCHEDULE_CHUNK_PARALLEL = 0x400,
+       OZIMMU_SCHEDULE_QUEUE = 0x800 };
 int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p,
                          const double *A, int64_t lda, const double *B, int64_t ldb,
                          double *D, int64_t ldd, int k, int split_mode, int accumulate_mode,

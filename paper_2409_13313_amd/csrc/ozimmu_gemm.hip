@@ -70,7 +70,9 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // A tile + B tile = 32 KiB
 constexpr int NLOAD = TILE_BYTES / (256 * 16);    // 16-byte copies per thread and operand tile = 4
 constexpr int EPI_ROWS = 2;                       // 32 x 32 tiles per batch of the plain epilogue (16 D loads in flight per lane each)
-constexpr int EXP_BYTES = 2 * 256 * 8 + 64;       // (exponent, offset correction) of the tile's 256 rows and 256 columns, kept in LDS; work-item ticket
+// behind the ring in LDS: (exponent, offset correction) of the tile's 256 rows and 256 columns; the work-item ticket
+// (64 bytes); the list of completed tiles that the workgroup still has to add up (queue schedule, 256 bytes)
+constexpr int EXP_BYTES = 2 * 256 * 8 + 64 + 256;
 
 // Linear tile order: bands of GROUP tile rows, each walked column by column, so
 // that 32 consecutive tiles form an 8 x 4 patch (8 A tiles + 4 B tiles per stage).
@@ -120,6 +122,132 @@ __device__ inline void static_for(F&& f)
     if constexpr (I < N) {
         f(std::integral_constant<int, I>{});
         static_for<I + 1, N>(f);
+    }
+}
+
+// Steps (iv) and (v) for one tile by one workgroup (the queue schedule): the tile's chunk sums lie in `w` dense
+// 256 x 256 INT32 blocks, `cstride` elements apart, in schedule order; every element gets them added in that order
+// with one rounded FP64 addition each (Algorithm 6), exactly as k_accumulate_chunks does.  Thread t takes columns
+// 4 (t % 64) .. + 3 of rows t / 64 + 4 i.  A step covers 8 rows and up to 8 chunks: 16 loads of 16 bytes per thread,
+// issued two steps ahead of their use, so that the loads of a step fly while the previous one is added up.
+// The loads are buffer loads of agent scope (they see what other XCDs have written through) and streaming (the
+// 2 MiB of a tile must not displace the operand tiles that the XCD's workgroups share in L2: with plain or merely
+// agent-scope loads the whole launch ran 5 % slower); D is stored non-temporally, 16 bytes per store when aligned.
+// lds_rows: 256 ints of LDS for the row exponents.
+__device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* blocks, int64_t cstride, int w, int tm,
+                                       int tp, int* lds_rows)
+{
+    typedef int v4si __attribute__((ext_vector_type(4)));
+    const int t = threadIdx.x, cg = t & 63, sub = t >> 6;
+    const int64_t j0 = (int64_t)tp * 256 + 4 * cg;
+    int eb[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) eb[c] = (j0 + c < a.p) ? a.eB[j0 + c] : 0;
+    {
+        const int64_t gr = (int64_t)tm * 256 + t;
+        lds_rows[t] = gr < a.m ? a.eA[gr] : 0;
+    }
+    __syncthreads();
+    const bool last_c = a.finish && a.cbeta != 0.0;
+    const int nbatch = (w + 7) / 8;
+    const int nstep = 32 * nbatch;
+    v4si v[2][8][2];
+    double d[2][4];
+    int g = a.g_lo, c0 = 1;
+    bool first = true;
+
+    // buffer descriptor over the tile's blocks: offsets are lane part (vector) + chunk part (scalar); the cache
+    // policy bits ask for agent scope (sc1) and streaming (nt)
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(blocks), 0, 0x7fffffff, 0x00020000);
+    constexpr int POLICY = (1 << 4) | (1 << 1);
+    auto issue = [&](auto BUF, int s) {
+        constexpr int buf = decltype(BUF)::value;
+        const int rg = s / nbatch, cq = (s - rg * nbatch) * 8;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const int cb = (cq + b < w) ? cq + b : w - 1;  // (past the last chunk: read it again, unused)
+            const int soff = (int)((int64_t)cb * cstride * 4);
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr) {
+                const int voff = ((rg * 8 + 4 * rr + sub) * 256 + 4 * cg) * 4;
+                v[buf][b][rr] = __builtin_bit_cast(v4si, __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, POLICY));
+            }
+        }
+    };
+    auto consume = [&](auto BUF, int s) {
+        constexpr int buf = decltype(BUF)::value;
+        const int rg = s / nbatch, bq = s - rg * nbatch, cq = bq * 8;
+        if (bq == 0) {
+            g = a.g_lo;
+            c0 = 1;
+            first = true;
+        }
+        int ea[2];
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) ea[rr] = lds_rows[rg * 8 + 4 * rr + sub];
+        const int nb = (w - cq) < 8 ? (w - cq) : 8;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            if (b < nb) {
+                const int shift = 2 - a.beta * g;
+#pragma unroll
+                for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const double term = ldexp((double)v[buf][b][rr][c], ea[rr] + eb[c] + shift);
+                        d[rr][c] = first ? term : d[rr][c] + term;
+                    }
+                first = false;
+                c0 += a.r;
+                if (c0 > g - 1) {
+                    ++g;
+                    c0 = 1;
+                }
+            }
+        }
+    };
+    // output pointer and pitch (step (v) writes to Cout); pairs of columns go out as 16-byte stores when aligned
+    double* const obase = a.finish ? a.Cout : a.D;
+    const int64_t opitch = a.finish ? a.ldco : a.ldd;
+    const bool wide = (reinterpret_cast<uintptr_t>(obase) % 16 == 0) && (opitch % 2 == 0) && (j0 + 3 < a.p);
+    typedef double v2d __attribute__((ext_vector_type(2)));
+    auto store = [&](int s) {
+        const int rg = s / nbatch, bq = s - rg * nbatch;
+        if (bq != nbatch - 1) return;
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) {
+            const int64_t irow = (int64_t)tm * 256 + rg * 8 + 4 * rr + sub;
+            if (irow >= a.m) continue;
+            double val[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                val[c] = d[rr][c];
+                if (a.finish) {
+                    val[c] = a.alpha * val[c];
+                    if (last_c && j0 + c < a.p) val[c] = val[c] + a.cbeta * obase[irow * opitch + j0 + c];
+                }
+            }
+            double* out = obase + irow * opitch + j0;
+            if (wide) {
+                __builtin_nontemporal_store((v2d){val[0], val[1]}, reinterpret_cast<v2d*>(out));
+                __builtin_nontemporal_store((v2d){val[2], val[3]}, reinterpret_cast<v2d*>(out + 2));
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (j0 + c < a.p) __builtin_nontemporal_store(val[c], out + c);
+            }
+        }
+    };
+    issue(std::integral_constant<int, 0>{}, 0);
+    if (nstep > 1) issue(std::integral_constant<int, 1>{}, 1);
+    for (int s = 0; s < nstep; s += 2) {  // nstep is even
+        consume(std::integral_constant<int, 0>{}, s);
+        if (s + 2 < nstep) issue(std::integral_constant<int, 0>{}, s + 2);
+        store(s);
+        consume(std::integral_constant<int, 1>{}, s + 1);
+        if (s + 3 < nstep) issue(std::integral_constant<int, 1>{}, s + 3);
+        store(s + 1);
     }
 }
 
@@ -247,6 +375,14 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     unsigned* const ticket_ctr = a.sync + 2;
     volatile int* const lds_ticket = reinterpret_cast<volatile int*>(lds + NS * STAGE_BYTES + 2 * 256 * 8);
 
+    // Queue schedule: tiles this workgroup has completed (it stored the last of their blocks) and still has to add
+    // up: ring of 16 entries (tile, round) in LDS; [0] head, [1] tail.  They are added up at the top of the next
+    // turn of the loop below, after the next ticket has been drawn.
+    volatile int* const pend = lds_ticket + 16;
+    if (t == 0) {
+        pend[0] = 0;
+        pend[1] = 0;
+    }
     for (int local = member; all_chunks || local < range_cnt; local += team) {
         int item = range_off + local;
         if (all_chunks) {
@@ -254,6 +390,26 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 *lds_ticket = (int)__hip_atomic_fetch_add(ticket_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();  // (the next write to the ticket word is a whole work item away)
             item = __builtin_amdgcn_readfirstlane(*lds_ticket);
+            if (a.queue_sets > 0) {
+                for (;;) {
+                    __syncthreads();
+                    const int head = __builtin_amdgcn_readfirstlane(pend[0]), tail = __builtin_amdgcn_readfirstlane(pend[1]);
+                    if (head == tail) break;
+                    const int slot = 2 + 2 * (head & 15);
+                    const int zt = __builtin_amdgcn_readfirstlane(pend[slot]), qr = __builtin_amdgcn_readfirstlane(pend[slot + 1]);
+                    int ptm, ptp;
+                    tile_of_linear(a.tile_begin + zt, TM, TP, ptm, ptp);
+                    const int first_block = __builtin_amdgcn_readfirstlane(
+                        (qr % a.queue_sets) * a.nchunks * a.queue_stride + (zt - qr * ozk::QUEUE_ROUND_TILES));
+                    accumulate_tile(a, a.C + (int64_t)first_block * (256 * 256), (int64_t)a.queue_stride * (256 * 256),
+                                    a.nchunks, ptm, ptp, reinterpret_cast<int*>(lds + NS * STAGE_BYTES));
+                    __syncthreads();  // every thread has used what it loaded from the blocks
+                    if (t == 0) {
+                        __hip_atomic_fetch_add(a.done + a.tile_count + qr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        pend[0] = head + 1;
+                    }
+                }
+            }
             if (item >= T) break;
         }
         const int round_first = local - member;
@@ -273,14 +429,48 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
         // MODE 3: part-major order, so that the 32 work items of a team are 32 tiles cut at the same place of
         // the inner dimension and share operand tiles in L2 like the tiles of the un-cut kernel
         // (integer divisions run on the vector unit: readfirstlane tells the compiler the results are uniform)
-        const int zpart = (MODE == 3) ? __builtin_amdgcn_readfirstlane((item / a.tile_count) % Z) : 0;
-        const int ztile = (MODE == 3) ? __builtin_amdgcn_readfirstlane(item % a.tile_count) : item;
+        int zpart = (MODE == 3) ? __builtin_amdgcn_readfirstlane((item / a.tile_count) % Z) : 0;
+        int ztile = (MODE == 3) ? __builtin_amdgcn_readfirstlane(item % a.tile_count) : item;
+        // Queue schedule: rounds of QR tiles, inside a round chunk-major (longest chunks first), Z = 1.  Round q puts
+        // its blocks into set q % queue_sets, once round q - queue_sets has been added up (in practice long before:
+        // the items of a round are all handed out before the first of the next one).
+        constexpr int QR = ozk::QUEUE_ROUND_TILES;
+        const bool queued = (MODE == 3) && all_chunks && a.queue_sets > 0;
+        int q_round = 0, q_chunk = 0;
+        if (queued) {
+            const int per_round = QR * a.nchunks;
+            q_round = __builtin_amdgcn_readfirstlane(item / per_round);
+            const int rem = item - q_round * per_round;
+            int rt = a.tile_count - q_round * QR;  // tiles of this round
+            rt = rt > QR ? QR : rt;
+            q_chunk = __builtin_amdgcn_readfirstlane(a.nchunks - 1 - rem / rt);
+            ztile = __builtin_amdgcn_readfirstlane(q_round * QR + rem % rt);
+            zpart = 0;
+            if (q_round >= a.queue_sets) {
+                // (Every lane polls the same word, so that the loop is uniform.  Bounded: some seconds.  Whoever
+                // holds an item of that old round is running and waits for nothing, so the wait ends; if it ever
+                // does not, the flag behind the counters says so.)
+                unsigned* const rd = a.done + a.tile_count + (q_round - a.queue_sets);
+                int polls = 0;
+                while ((unsigned)__builtin_amdgcn_readfirstlane(
+                           (int)__hip_atomic_load(rd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) < (unsigned)QR) {
+                    __builtin_amdgcn_s_sleep(16);
+                    if (++polls > (1 << 23)) {
+                        if (t == 0) a.done[a.tile_count + (a.tile_count + QR - 1) / QR] = 1u;
+                        break;
+                    }
+                }
+            }
+        }
+        // the INT32 block this item's chunk sums go to (MODE 3)
+        const int64_t block_no =
+            queued ? ((int64_t)(q_round % a.queue_sets) * a.nchunks + q_chunk) * a.queue_stride + (ztile - q_round * QR) : 0;
         // the chunks this work item runs: all of the schedule, or the one chunk given by the launch, or (all_chunks)
         // chunk number `chunk_no` of the schedule, found by walking it.  Long chunks (late groups) come first in
         // the item order, so that the short ones fill the gaps at the end.
         int it_g_lo = a.g_lo, it_g_hi = a.g_hi, it_s0 = a.s0, it_s1 = a.s1, chunk_no = 0;
         if (all_chunks) {
-            chunk_no = __builtin_amdgcn_readfirstlane(a.nchunks - 1 - item / (a.tile_count * Z));
+            chunk_no = __builtin_amdgcn_readfirstlane(queued ? q_chunk : a.nchunks - 1 - item / (a.tile_count * Z));
             int q = 0;
             for (int g = a.g_lo; g <= a.g_hi; ++g)
                 for (int c0 = 1; c0 <= g - 1; c0 += a.r, ++q)
@@ -551,7 +741,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 const int64_t urow = er0 + rt;
                                 // MODE 3: the tile's own dense 256 x 256 block, addressed by the row / column in the tile
                                 int32_t* base = (MODE == 3)
-                                                    ? a.C + ((int64_t)chunk_no * a.tile_count + ztile) * (256 * 256) +
+                                                    ? a.C + (queued ? block_no : (int64_t)chunk_no * a.tile_count + ztile) * (256 * 256) +
                                                           (int64_t)(wm * 128 + rt) * 256 + wn * 128 + j * 32
                                                     : a.C + urow * a.ldc + ec0 + j * 32;
                                 const uint32_t off =
@@ -560,6 +750,8 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                     if (MODE == 3 && Z > 1)  // partial sum of one part: integer adds commute, C'' starts at zero
                                         __hip_atomic_fetch_add(&base[off], acc[i][j][r], __ATOMIC_RELAXED,
                                                                __HIP_MEMORY_SCOPE_AGENT);
+                                    else if (queued)  // written through: another XCD's workgroup may add the tile up
+                                        __hip_atomic_store(&base[off], acc[i][j][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                                     else
                                         base[off] = acc[i][j][r];
                                 }
@@ -707,6 +899,24 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     }
                 }
                 first = 0;
+            }
+        }
+        if (queued) {
+            // This item's block is complete.  The workgroup that completes the last block of a tile adds the
+            // tile's chunks up.  No cache-wide fence (its L2 write-back and invalidation would cost every workgroup
+            // of the XCD its operand tiles): the blocks are stored and loaded with agent-scope accesses, which go
+            // through to memory, every thread waits for its stores to be acknowledged before the counter is
+            // touched, and the loads of the adding workgroup are issued after it has seen the count.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (t == 0)
+                lds_ticket[1] = (int)__hip_atomic_fetch_add(a.done + ztile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            if (__builtin_amdgcn_readfirstlane(lds_ticket[1]) == a.nchunks - 1 && t == 0) {
+                const int tail = pend[1];  // (at most one entry is ever waiting: the list is emptied every turn)
+                pend[2 + 2 * (tail & 15)] = ztile;
+                pend[3 + 2 * (tail & 15)] = q_round;
+                pend[1] = tail + 1;
             }
         }
     }

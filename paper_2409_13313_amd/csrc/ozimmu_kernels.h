@@ -26,6 +26,7 @@ hipError_t launch_split_B_per_slice(int64_t n, int64_t p, const double* B, int64
                                     int32_t* eB, double* rem, hipStream_t st);
 hipError_t launch_export(int64_t rows, int64_t n, int k, const int8_t* packed, int8_t* out, hipStream_t st);
 
+constexpr int QUEUE_ROUND_TILES = 256;  // tiles per round of the queue schedule (see GemmArgs::queue_sets)
 constexpr int SYNC_WORDS = 128;  // 32-bit soft-barrier counters at the start of the GEMM scratch (16 per XCD)
 
 struct GemmArgs {
@@ -55,6 +56,14 @@ struct GemmArgs {
     int zsplit;            // fused == 3 only: parts the inner range of a chunk is cut into (<= KT / 4)
     int nchunks;           // fused == 3 only: 0, or the number of chunks of the full schedule g_lo..g_hi: the launch
                            // then runs every chunk, C holding nchunks x tile_count blocks (chunk-major)
+    // fused == 3 with nchunks > 0 and queue_sets > 0 ("queue" schedule): the work items run round by round (256
+    // tiles, all their chunks), C holds queue_sets sets of nchunks x queue_stride blocks that the rounds take in turn, and the
+    // workgroup that finishes the last chunk of a tile adds the tile's chunks up into D (step (iv), and (v) when
+    // finish is set).  done: tile_count + number-of-rounds + 1 counters, zero at launch (the last one is set if a wait for a
+    // set ever ran out of patience: the result is then invalid).  zsplit must be 1.
+    int queue_sets;
+    int queue_stride;      // blocks per chunk in a set: min(tile_count, 256)
+    unsigned* done;
     int tile_begin, tile_count;  // the launch covers tiles tile_begin .. tile_begin + tile_count - 1 of the band order
     int dma_ok;            // D is 16-byte aligned and ldd even: rows of D can be copied 16 bytes per lane
     int beta;              // shift of group g is 2 - beta * g

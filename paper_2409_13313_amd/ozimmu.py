@@ -90,7 +90,7 @@ EXPORTS = ["ozimmu_status_string", "ozimmu_params", "ozimmu_num_chunks", "ozimmu
 
 SPLIT_MODES = {"rn": 0, "bitmask": 1, "per_slice": 2}
 ACCUMULATE_MODES = {"grouped": 0, "per_pair": 1, "wide": 2}
-SCHEDULES = {"auto": 0, "one_launch": 0x100, "split_inner": 0x200, "chunk_parallel": 0x400}
+SCHEDULES = {"auto": 0, "one_launch": 0x100, "split_inner": 0x200, "chunk_parallel": 0x400, "queue": 0x800}
 
 
 class OzimmuError(RuntimeError):

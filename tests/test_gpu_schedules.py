@@ -24,6 +24,14 @@ def dev(x):
     return torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
+def queue_workspace(oz, m, n, p, k, sets=3):
+    """A workspace with room for the blocks of the queue schedule whatever the size (the recommended size holds
+    them only for outputs of more than 256 tiles): `sets` sets of chunks x min(tiles, 256) blocks + counters."""
+    tiles = -(-m // 256) * -(-p // 256)
+    blocks = sets * oz.num_chunks(n, k) * min(tiles, 256) + 2
+    return torch.empty(oz.workspace_bytes_min(m, n, p, k) + blocks * 4 * 256 * 256, dtype=torch.uint8, device="cuda")
+
+
 SHAPES = [
     (300, 520, 270, 8, 0.5),       # 4 tiles, 12 inner tiles: 3 parts
     (513, 1029, 257, 6, 2.0),      # 6 ragged tiles, 20 inner tiles: 5 parts
@@ -35,13 +43,14 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("schedule", ["one_launch", "split_inner", "chunk_parallel", "auto"])
+@pytest.mark.parametrize("schedule", ["one_launch", "split_inner", "chunk_parallel", "queue", "auto"])
 @pytest.mark.parametrize("m,n,p,k,phi", SHAPES)
 def test_both_schedules_match_the_oracle_bit_for_bit(oz, m, n, p, k, phi, schedule):
     A, B = inputs.phi_pair(m, n, p, phi, seed=91)
     want = oracle.dgemm(A, B, k)
     D = torch.full((m, p), float("nan"), dtype=torch.float64, device="cuda")
-    oz.dgemm_variant(dev(A), dev(B), k, "rn", "grouped", D=D, schedule=schedule)
+    ws = queue_workspace(oz, m, n, p, k) if schedule == "queue" else None
+    oz.dgemm_variant(dev(A), dev(B), k, "rn", "grouped", D=D, workspace=ws, schedule=schedule)
     got = D.cpu().numpy()
     assert np.isfinite(got).all()
     assert (np.abs(got - want) <= 2 * np.spacing(np.abs(want))).all()
@@ -124,7 +133,7 @@ def test_schedule_flags_are_validated(oz):
     ws = oz.alloc_workspace(4, 4, 4, 4)
     st = torch.cuda.current_stream().cuda_stream
     D = torch.empty((4, 4), dtype=torch.float64, device="cuda")
-    for bad in (0x300, 0x800, 0x500, 0x103 | 0x200):
+    for bad in (0x300, 0x1000, 0x500, 0xc00, 0x103 | 0x200):
         rc = oz._lib.ozimmu_dgemm_variant(4, 4, 4, A.data_ptr(), 4, A.data_ptr(), 4, D.data_ptr(), 4, 4, 0, bad,
                                           ws.data_ptr(), ws.numel(), st)
         assert rc == -3
@@ -167,3 +176,42 @@ def test_fused_epilogue_with_and_without_the_alignment_for_staging(oz, col_shift
     got = Dbig.cpu().numpy()
     assert np.array_equal(got[:, col_shift:col_shift + p], want)
     assert (got[:, :col_shift] == -7.0).all() and (got[:, col_shift + p:] == -7.0).all()
+
+
+@pytest.mark.parametrize("m,n,p,k,sets", [(4608, 300, 4352, 5, 3),    # 306 tiles: two rounds, the second partly filled
+                                          (8192, 256, 8192, 4, 3),    # 1024 tiles: four rounds on three sets of blocks
+                                          (8192, 256, 8192, 4, 2),    # the same on two sets (the least that is accepted)
+                                          (4100, 1029, 4000, 3, 3),   # ragged edge tiles
+                                          (2304, 40000, 2300, 9, 3)]) # 81 tiles, r = 4: 18 chunks (three batches of 8)
+def test_queue_schedule_matches_the_persistent_launch_and_sampled_oracle_entries(oz, m, n, p, k, sets):
+    A, B = inputs.phi_pair(m, n, p, 1.0, seed=98)
+    dA, dB = dev(A), dev(B)
+    ref = torch.full((m, p), float("nan"), dtype=torch.float64, device="cuda")
+    oz.dgemm_variant(dA, dB, k, "rn", "grouped", D=ref, schedule="one_launch")
+    ws = queue_workspace(oz, m, n, p, k, sets)
+    ws.fill_(0x5A)                       # stale bytes in the blocks and counters must not leak
+    Dbig = torch.full((m, p + 2), -3.0, dtype=torch.float64, device="cuda")
+    for _ in range(2):                   # the second call finds the first one's counters
+        oz.dgemm_variant(dA, dB, k, "rn", "grouped", D=Dbig[:, :p], workspace=ws, schedule="queue")
+    assert torch.equal(Dbig[:, :p], ref) and bool((Dbig[:, p:] == -3.0).all())
+    I = inputs.sample_indices(m, 40, seed=3)
+    J = inputs.sample_indices(p, 40, seed=4)
+    want = oracle.dgemm_sub(A, B, k, I, J)
+    got = ref[torch.from_numpy(I).cuda()][:, torch.from_numpy(J).cuda()].cpu().numpy()
+    assert np.array_equal(got, want)
+
+
+def test_default_schedule_of_a_large_output_is_bit_identical_with_step_v(oz):
+    # 1056 tiles: the default is the queue (full rounds) here; step (v) rides on its tile accumulation
+    m, n, p, k = 8192, 300, 8448, 4
+    A, B = inputs.phi_pair(m, n, p, 0.5, seed=99)
+    dA, dB = dev(A), dev(B)
+    ref = oz.dgemm_variant(dA, dB, k, "rn", "grouped", schedule="one_launch")
+    assert torch.equal(oz.dgemm(dA, dB, k), ref)
+    C0 = torch.from_numpy(np.random.Generator(np.random.PCG64(100)).standard_normal((m, p))).cuda()
+    for alpha, beta in ((-1.5, 0.0), (0.75, -0.25)):
+        C = C0.clone()
+        oz.gemm_ex(False, False, alpha, dA, dB, beta, C, k)
+        t1 = alpha * ref
+        want = t1 if beta == 0.0 else t1 + beta * C0
+        assert torch.equal(C, want)

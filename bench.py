@@ -173,8 +173,8 @@ def main() -> int:
         "phases_ms": {"split_A_and_B": round(split_ms, 4), "chunk_gemm_with_fused_accumulation": round(gemm_ms, 4)},
         "int8_mfma_utilisation_pct": round(100.0 * gemm_tops / PEAK_INT8_TOPS, 2),
         "roofline": {
-            "kernel": "k_gemm<1,4> (persistent INT8 MFMA kernel: every chunk GEMM of the schedule with its "
-                      "fused FP64 accumulation, one launch per step)",
+            "kernel": "k_gemm<3,4> (persistent INT8 MFMA kernel, queue schedule: every chunk GEMM of the schedule is "
+                      "a work item; the workgroup that completes a tile adds its chunks up in FP64; one launch per step)",
             "bound": "mfma",
             "achieved": round(gemm_tops, 2),
             "peak": PEAK_INT8_TOPS,

@@ -118,13 +118,13 @@ inline int64_t partial_blocks(int64_t m, int64_t n, int64_t p, int k)
     const int64_t base = min_partial_blocks(m, p);
     if (n < 1 || n > MAX_INNER || k < 1) return base;
     // (the chunk-parallel way takes the tiles that do not fill a round of the 256 compute units of the chip this is
-    // written for; the queue, which takes the full rounds of larger outputs, wants QUEUE_SETS sets of chunks x 256
+    // written for; the queue, which takes outputs of 256 tiles and more, wants QUEUE_SETS sets of chunks x 256
     // blocks and a counter per tile and round)
     const int64_t T = output_tiles(m, p);
     const int64_t w = chunks_of(k, r_of(n, beta_of(n)));
     const int64_t items = (T <= 256 ? T : T % 256) * w;
     int64_t blocks = (items <= CHUNK_PARALLEL_MAX_BLOCKS && items > base) ? items : base;
-    if (T > 256 && w * 256 * BLOCK_BYTES < ((int64_t)1 << 31) && T * w < ((int64_t)1 << 30)) {
+    if (T >= 256 && w * 256 * BLOCK_BYTES < ((int64_t)1 << 31) && T * w < ((int64_t)1 << 30)) {
         const int64_t rounds = (T + 255) / 256;
         const int64_t queue = (rounds < QUEUE_SETS ? rounds : QUEUE_SETS) * w * 256 +
                               (4 * (T + rounds + 1) + BLOCK_BYTES - 1) / BLOCK_BYTES;
@@ -281,7 +281,9 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         a.sync_zeroed = take_clean();
         return hip_status(ozk::launch_gemm(a, 3, st));
     };
-    if (schedule == OZIMMU_SCHEDULE_QUEUE) {
+    // Asked for, or the output has tiles for every compute unit (measured against queue for the full rounds +
+    // one of the other ways for a short last round: equal or better with everything in the queue).
+    if (schedule == OZIMMU_SCHEDULE_QUEUE || (schedule == 0 && T >= num_cu)) {
         const int64_t sets = queue_sets(T);
         if (sets > 0) return launch_queue(T, sets);
     }
@@ -361,23 +363,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             }
         }
     }
-    // The full rounds before those tiles: the queue when nothing else was asked for and the workspace has the room
-    // (a last round that fills at least half the chip goes with them), else the persistent launch.
-    bool body_done = false;
-    if (schedule == 0 && T > num_cu) {
-        if (cand * 2 >= num_cu || cand == 0) {
-            const int64_t sets = queue_sets(T);
-            if (sets > 0) return launch_queue(T, sets);
-        }
-        const int64_t body = T - tail - cp_tail;
-        const int64_t sets = queue_sets(body);
-        if (body >= num_cu && sets > 0) {
-            const int rc = launch_queue(body, sets);
-            if (rc != OZIMMU_OK) return rc;
-            body_done = true;
-        }
-    }
-    if (!body_done && T - tail - cp_tail > 0) {
+    if (T - tail - cp_tail > 0) {
         ozk::GemmArgs a = make_args(m, n, p, SA, k, SB, k, 2, k + 1, r_eff, 0, 0, scratch, num_cu);
         a.tile_count = (int)(T - tail - cp_tail);
         a.D = D;

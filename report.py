@@ -313,23 +313,25 @@ def schedules(k=8, reps=5):
               (1024, 16384, 1024), (1024, 65536, 1024), (2048, 131072, 2048), (512, 131072, 512), (256, 262144, 256)]
     print(f"### outputs of few 256 x 256 tiles (or with a partly filled last round), k={k}, phi=0.5; "
           f"median of {reps}, ms (effective TFLOP/s)\n")
-    print("| m x n x p | tiles | one launch | split inner | chunk parallel | what the library picks | native FP64 |")
-    print("|---|---|---|---|---|---|---|")
+    print("| m x n x p | tiles | one launch | split inner | chunk parallel | queue | what the library picks | native FP64 |")
+    print("|---|---|---|---|---|---|---|---|")
     for (m, n, p) in shapes:
         A, B = inputs.phi_pair(m, n, p, 0.5, seed=0)
         dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
         D = torch.empty((m, p), dtype=torch.float64, device="cuda")
-        ws = ozimmu.alloc_workspace(m, n, p, k)
+        # room for the blocks of every way, also where the library would not ask for them (the queue below 256 tiles)
+        tiles = ((m + 255) // 256) * ((p + 255) // 256)
+        extra = (3 * ozimmu.num_chunks(n, k) * min(tiles, 256) + 2) * 4 * 256 * 256
+        ws = torch.empty(ozimmu.workspace_bytes(m, n, p, k) + extra, dtype=torch.uint8, device="cuda")
         flops = 2.0 * m * n * p
         cells = []
-        for sched in ("one_launch", "split_inner", "chunk_parallel", "auto"):
+        for sched in ("one_launch", "split_inner", "chunk_parallel", "queue", "auto"):
             run = lambda: ozimmu.dgemm_variant(dA, dB, k, "rn", "grouped", D=D, workspace=ws, schedule=sched)
             run()
             t = _median_ms(run, reps)
             cells.append(f"{t:.3f} ({flops / t / 1e9:.1f})")
         torch.mm(dA, dB, out=D)
         t = _median_ms(lambda: torch.mm(dA, dB, out=D), reps)
-        tiles = ((m + 255) // 256) * ((p + 255) // 256)
         print(f"| {m} x {n} x {p} | {tiles} | " + " | ".join(cells) + f" | {t:.3f} ({flops / t / 1e9:.1f}) |")
         del dA, dB, D, ws
     print()

@@ -266,6 +266,8 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         a.nchunks = (int)w;
         a.queue_sets = (int)sets;
         a.queue_stride = (int)stride;
+        const int64_t TM = ozl::rows_padded(m) / ozl::TILE_R, TP = ozl::rows_padded(p) / ozl::TILE_R;
+        a.queue_block_rounds = (tiles == T && TM % 16 == 0 && TP % 16 == 0) ? 1 : 0;
         a.done = reinterpret_cast<unsigned*>(ctr);
         a.D = D;
         a.ldd = ldd;

@@ -63,6 +63,7 @@ struct GemmArgs {
     // set ever ran out of patience: the result is then invalid).  zsplit must be 1.
     int queue_sets;
     int queue_stride;      // blocks per chunk in a set: min(tile_count, 256)
+    int queue_block_rounds;  // the launch covers a whole tile grid made of 16 x 16 blocks: a round is such a block
     unsigned* done;
     int tile_begin, tile_count;  // the launch covers tiles tile_begin .. tile_begin + tile_count - 1 of the band order
     int dma_ok;            // D is 16-byte aligned and ldd even: rows of D can be copied 16 bytes per lane

@@ -346,6 +346,34 @@ def test_dgemm_captured_in_a_hip_graph_replays_bit_identically(oz):
     assert (np.abs(eager.cpu().numpy() - want) <= 2 * np.spacing(np.abs(want))).all()
 
 
+def test_queue_schedule_captured_in_a_hip_graph_replays_bit_identically(oz):
+    # 320 tiles: the default schedule is the queue (its counters are cleared by a fill kernel, its waits are
+    # bounded); every replay must reproduce the eager result
+    m, n, p, k = 4096, 300, 5120, 4
+    A, B = inputs.phi_pair(m, n, p, 0.5, seed=43)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    ws = oz.alloc_workspace(m, n, p, k)
+    eager = oz.dgemm(dA, dB, k, workspace=ws).clone()
+    assert torch.equal(eager, oz.dgemm_variant(dA, dB, k, "rn", "grouped", schedule="one_launch"))
+    D = torch.zeros((m, p), dtype=torch.float64, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        oz.dgemm(dA, dB, k, D=D, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        oz.dgemm(dA, dB, k, D=D, workspace=ws)
+    for rep in range(3):
+        D.fill_(float(rep))
+        ws[-(1 << 20):].fill_(0x33)                        # stale counters behind the blocks
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(D, eager), f"replay {rep}"
+
+
 def test_first_library_call_of_a_process_inside_a_graph_capture_after_init(oz):
     # the per-device set-up (kernel attributes, symbol address) is not legal inside a stream capture: a process whose
     # very first library call is a captured one must call ozimmu_init before.  Run in a child process, so that the

@@ -190,7 +190,8 @@ def test_queue_schedule_matches_the_persistent_launch_and_sampled_oracle_entries
     oz.dgemm_variant(dA, dB, k, "rn", "grouped", D=ref, schedule="one_launch")
     ws = queue_workspace(oz, m, n, p, k, sets)
     ws.fill_(0x5A)                       # stale bytes in the blocks and counters must not leak
-    Dbig = torch.full((m, p + 2), -3.0, dtype=torch.float64, device="cuda")
+    # (odd k: an odd leading dimension, D then goes out in 8-byte stores instead of 16-byte ones)
+    Dbig = torch.full((m, p + 2 + k % 2), -3.0, dtype=torch.float64, device="cuda")
     for _ in range(2):                   # the second call finds the first one's counters
         oz.dgemm_variant(dA, dB, k, "rn", "grouped", D=Dbig[:, :p], workspace=ws, schedule="queue")
     assert torch.equal(Dbig[:, :p], ref) and bool((Dbig[:, p:] == -3.0).all())

@@ -216,3 +216,18 @@ def test_default_schedule_of_a_large_output_is_bit_identical_with_step_v(oz):
         t1 = alpha * ref
         want = t1 if beta == 0.0 else t1 + beta * C0
         assert torch.equal(C, want)
+
+
+def test_default_schedule_repeated_calls_give_the_same_bits(oz):
+    # 592 tiles in three rounds on recycled blocks: every call of a run must reproduce the persistent launch's D
+    # (the blocks written by one XCD are read by another; a stale value would show as a difference here)
+    m, n, p, k = 4096, 256, 9472, 8
+    A, B = inputs.phi_pair(m, n, p, 1.0, seed=101)
+    dA, dB = dev(A), dev(B)
+    ref = oz.dgemm_variant(dA, dB, k, "rn", "grouped", schedule="one_launch")
+    ws = oz.alloc_workspace(m, n, p, k)
+    D = torch.empty_like(ref)
+    for rep in range(25):
+        D.fill_(float("nan"))
+        oz.dgemm(dA, dB, k, D=D, workspace=ws)
+        assert torch.equal(D, ref), f"call {rep}"

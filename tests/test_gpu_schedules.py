@@ -231,3 +231,19 @@ def test_default_schedule_repeated_calls_give_the_same_bits(oz):
         D.fill_(float("nan"))
         oz.dgemm(dA, dB, k, D=D, workspace=ws)
         assert torch.equal(D, ref), f"call {rep}"
+
+
+@pytest.mark.parametrize("split,accumulate", [("bitmask", "grouped"), ("rn", "wide"), ("bitmask", "per_pair")])
+def test_default_schedule_of_a_large_output_with_the_comparison_variants(oz, split, accumulate):
+    # 272 tiles: the queue by default where its blocks fit (one per chunk: per-pair accumulation has 15 of them at
+    # k = 5), else the persistent launch; either way the bits of the forced persistent launch and of the oracle
+    m, n, p, k = 4096, 300, 4352, 5
+    A, B = inputs.phi_pair(m, n, p, 2.0, seed=102)
+    dA, dB = dev(A), dev(B)
+    ref = oz.dgemm_variant(dA, dB, k, split, accumulate, schedule="one_launch")
+    got = oz.dgemm_variant(dA, dB, k, split, accumulate)
+    assert torch.equal(got, ref)
+    I = inputs.sample_indices(m, 32, seed=5)
+    J = inputs.sample_indices(p, 32, seed=6)
+    want = oracle.dgemm_variant(A[I], B[:, J], k, split, accumulate)
+    assert np.array_equal(got[torch.from_numpy(I).cuda()][:, torch.from_numpy(J).cuda()].cpu().numpy(), want)

@@ -99,6 +99,7 @@ constexpr int64_t CHUNK_PARALLEL_MAX_BLOCKS = 4096;
 constexpr int64_t GRID_WAIT_MIN_INNER = 8192 + 512;
 // Sets of blocks the rounds of the queue schedule take in turn (see run_schedule).
 constexpr int64_t QUEUE_SETS = 3;
+constexpr int64_t QUEUE_XCD_WORDS = 8 * 40;  // per-XCD ticket batches of the queue (see k_gemm)
 constexpr int64_t BLOCK_BYTES = 4 * 256 * 256;
 inline int64_t chunks_of(int k, int64_t r)
 {
@@ -127,7 +128,7 @@ inline int64_t partial_blocks(int64_t m, int64_t n, int64_t p, int k)
     if (T >= 256 && w * 256 * BLOCK_BYTES < ((int64_t)1 << 31) && T * w < ((int64_t)1 << 30)) {
         const int64_t rounds = (T + 255) / 256;
         const int64_t queue = (rounds < QUEUE_SETS ? rounds : QUEUE_SETS) * w * 256 +
-                              (4 * (T + rounds + 1) + BLOCK_BYTES - 1) / BLOCK_BYTES;
+                              (4 * (T + rounds + 2 + QUEUE_XCD_WORDS) + BLOCK_BYTES - 1) / BLOCK_BYTES;
         if (queue > blocks) blocks = queue;
     }
     return blocks;
@@ -247,7 +248,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         const int64_t stride = tiles < ozk::QUEUE_ROUND_TILES ? tiles : ozk::QUEUE_ROUND_TILES;
         if (w * stride * BLOCK_BYTES >= ((int64_t)1 << 31)) return 0;  // 32-bit byte offsets inside a set of blocks
         const int64_t rounds = (tiles + ozk::QUEUE_ROUND_TILES - 1) / ozk::QUEUE_ROUND_TILES;
-        const int64_t counter_blocks = (4 * (tiles + rounds + 1) + BLOCK_BYTES - 1) / BLOCK_BYTES;
+        const int64_t counter_blocks = (4 * (tiles + rounds + 2 + QUEUE_XCD_WORDS) + BLOCK_BYTES - 1) / BLOCK_BYTES;
         int64_t sets = rounds < QUEUE_SETS ? rounds : QUEUE_SETS;
         while (sets > 1 && sets * w * stride + counter_blocks > partial_capacity) --sets;
         if (sets * w * stride + counter_blocks > partial_capacity) return 0;
@@ -257,7 +258,9 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         const int64_t stride = tiles < ozk::QUEUE_ROUND_TILES ? tiles : ozk::QUEUE_ROUND_TILES;
         const int64_t rounds = (tiles + ozk::QUEUE_ROUND_TILES - 1) / ozk::QUEUE_ROUND_TILES;
         int32_t* const ctr = partial + sets * w * stride * (BLOCK_BYTES / 4);
-        hipError_t e = ozk::launch_fill_zero_i32(tiles + rounds + 1, ctr, st);
+        // counters: one per tile, one per round, the flag; then, 8-byte aligned, the per-XCD ticket batches
+        const int64_t xq_at = (tiles + rounds + 2) & ~(int64_t)1;
+        hipError_t e = ozk::launch_fill_zero_i32(xq_at + QUEUE_XCD_WORDS, ctr, st);
         if (e != hipSuccess) return OZIMMU_ERR_HIP;
         ozk::GemmArgs a = make_args(m, n, p, SA, k, SB, k, 2, k + 1, r_eff, 0, 0, scratch, num_cu);
         a.tile_count = (int)tiles;
@@ -269,6 +272,8 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         const int64_t TM = ozl::rows_padded(m) / ozl::TILE_R, TP = ozl::rows_padded(p) / ozl::TILE_R;
         a.queue_block_rounds = (tiles == T && TM % 16 == 0 && TP % 16 == 0) ? 1 : 0;
         a.done = reinterpret_cast<unsigned*>(ctr);
+        // batches of 32 tickets per XCD when every compute unit of the 8-XCD chip this is written for has a workgroup
+        a.xq = (tiles >= num_cu && num_cu == 256) ? reinterpret_cast<unsigned*>(ctr) + xq_at : nullptr;
         a.D = D;
         a.ldd = ldd;
         a.eA = eA;

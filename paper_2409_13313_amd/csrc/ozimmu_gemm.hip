@@ -143,78 +143,94 @@ __device__ inline void static_for(F&& f)
     }
 }
 
-// Steps (iv) and (v) for one tile by one workgroup (the queue schedule): the tile's chunk sums lie in `w` dense
-// 256 x 256 INT32 blocks, `cstride` elements apart, in schedule order; every element gets them added in that order
-// with one rounded FP64 addition each (Algorithm 6), exactly as k_accumulate_chunks does.  Thread t takes columns
-// 4 (t % 64) .. + 3 of rows t / 64 + 4 i.  A step covers 8 rows and up to 8 chunks: 16 loads of 16 bytes per thread,
-// issued two steps ahead of their use, so that the loads of a step fly while the previous one is added up.
+// Layout of a 256 x 256 INT32 block of the queue schedule: "lane-major".  The four accumulators 4q .. 4q + 3 of
+// 32 x 32 tile (i, j) of thread t (wave t / 64 = 2 wm + wn, lane l = t % 64) are the 16 bytes at int index
+// (((i * 4 + j) * 4 + q) * 256 + t) * 4; they belong to rows wm * 128 + i * 32 + 8 q + 4 (l / 32) + 0 .. 3 and
+// column wn * 128 + j * 32 + l % 32 of the block.  A workgroup writes a block with 64 fully coalesced 16-byte
+// stores per thread (256 4-byte stores in row-major order cost 10 us more per work item), and thread t of the
+// workgroup that adds the tile up reads back what a thread t wrote.
+constexpr int QBLOCK_GROUP_BYTES = 256 * 16;  // one (i, j, q) group of all 256 threads
+
+// Steps (iv) and (v) for one tile by one workgroup (the queue schedule): the tile's chunk sums lie in `w` lane-major
+// INT32 blocks, `cstride` elements apart, in schedule order; every element gets them added in that order with one
+// rounded FP64 addition each (Algorithm 6), exactly as k_accumulate_chunks does.  A step covers two register
+// groups (8 rows x 1 column per thread) and up to 8 chunks: 16 loads of 16 bytes per thread, issued two steps
+// ahead of their use, so that the loads of a step fly while the previous one is added up (three steps: spills).
 // The loads are buffer loads of agent scope (they see what other XCDs have written through) and streaming (the
 // 2 MiB of a tile must not displace the operand tiles that the XCD's workgroups share in L2: with plain or merely
-// agent-scope loads the whole launch ran 5 % slower); D is stored non-temporally, 16 bytes per store when aligned.
+// agent-scope loads the whole launch ran 5 % slower); D is stored non-temporally, 256 contiguous bytes per half wave.
 // lds_rows: 256 ints of LDS for the row exponents.
 __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* blocks, int64_t cstride, int w, int tm,
                                        int tp, int* lds_rows)
 {
     typedef int v4si __attribute__((ext_vector_type(4)));
-    const int t = threadIdx.x, cg = t & 63, sub = t >> 6;
-    const int64_t j0 = (int64_t)tp * 256 + 4 * cg;
+    // (the thread index is made opaque to the optimiser: what is derived from it below is then computed here, per
+    // call, and not at kernel entry, from where it would live - and be spilled - across the MFMA loop)
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave >> 1, wn = wave & 1, lr = lane & 31, lh = lane >> 5;
+    const int64_t col0 = (int64_t)tp * 256 + wn * 128 + lr;  // this lane's column in column tile j: col0 + 32 j
     int eb[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) eb[c] = (j0 + c < a.p) ? a.eB[j0 + c] : 0;
+    for (int j = 0; j < 4; ++j) eb[j] = (col0 + 32 * j < a.p) ? a.eB[col0 + 32 * j] : 0;
     {
         const int64_t gr = (int64_t)tm * 256 + t;
         lds_rows[t] = gr < a.m ? a.eA[gr] : 0;
     }
     __syncthreads();
     const bool last_c = a.finish && a.cbeta != 0.0;
+    double* const obase = a.finish ? a.Cout : a.D;
+    const int64_t opitch = a.finish ? a.ldco : a.ldd;
     const int nbatch = (w + 7) / 8;
     const int nstep = 32 * nbatch;
     v4si v[2][8][2];
     double d[2][4];
     int g = a.g_lo, c0 = 1;
     bool first = true;
-
-    // buffer descriptor over the tile's blocks: offsets are lane part (vector) + chunk part (scalar); the cache
-    // policy bits ask for agent scope (sc1) and streaming (nt)
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(blocks), 0, 0x7fffffff, 0x00020000);
     constexpr int POLICY = (1 << 4) | (1 << 1);
     auto issue = [&](auto BUF, int s) {
         constexpr int buf = decltype(BUF)::value;
-        const int rg = s / nbatch, cq = (s - rg * nbatch) * 8;
+        const int u = s / nbatch, cq = (s - u * nbatch) * 8;
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
-            const int cb = (cq + b < w) ? cq + b : w - 1;  // (past the last chunk: read it again, unused)
-            const int soff = (int)((int64_t)cb * cstride * 4);
+            const int cb = (cq + b < w) ? cq + b : w - 1;
 #pragma unroll
-            for (int rr = 0; rr < 2; ++rr) {
-                const int voff = ((rg * 8 + 4 * rr + sub) * 256 + 4 * cg) * 4;
-                v[buf][b][rr] = __builtin_bit_cast(v4si, __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, POLICY));
+            for (int qq = 0; qq < 2; ++qq) {
+                const int soff = (int)((int64_t)cb * cstride * 4) + (u * 2 + qq) * QBLOCK_GROUP_BYTES;
+                v[buf][b][qq] = __builtin_bit_cast(v4si, __builtin_amdgcn_raw_buffer_load_b128(rsrc, t * 16, soff, POLICY));
             }
         }
     };
     auto consume = [&](auto BUF, int s) {
         constexpr int buf = decltype(BUF)::value;
-        const int rg = s / nbatch, bq = s - rg * nbatch, cq = bq * 8;
+        const int u = s / nbatch, bq = s - u * nbatch, cq = bq * 8;
+        const int i = u >> 3, j = (u >> 1) & 3, half = u & 1;
         if (bq == 0) {
             g = a.g_lo;
             c0 = 1;
             first = true;
         }
-        int ea[2];
+        const int ebj = j == 0 ? eb[0] : j == 1 ? eb[1] : j == 2 ? eb[2] : eb[3];
+        int ea[2][4];
 #pragma unroll
-        for (int rr = 0; rr < 2; ++rr) ea[rr] = lds_rows[rg * 8 + 4 * rr + sub];
+        for (int qq = 0; qq < 2; ++qq)
+#pragma unroll
+            for (int ss = 0; ss < 4; ++ss) ea[qq][ss] = lds_rows[wm * 128 + i * 32 + 8 * (2 * half + qq) + 4 * lh + ss];
         const int nb = (w - cq) < 8 ? (w - cq) : 8;
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
             if (b < nb) {
                 const int shift = 2 - a.beta * g;
 #pragma unroll
-                for (int rr = 0; rr < 2; ++rr)
+                for (int qq = 0; qq < 2; ++qq)
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const double term = ldexp((double)v[buf][b][rr][c], ea[rr] + eb[c] + shift);
-                        d[rr][c] = first ? term : d[rr][c] + term;
+                    for (int ss = 0; ss < 4; ++ss) {
+                        const double term = ldexp((double)v[buf][b][qq][ss], ea[qq][ss] + ebj + shift);
+                        d[qq][ss] = first ? term : d[qq][ss] + term;
                     }
                 first = false;
                 c0 += a.r;
@@ -225,41 +241,30 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
             }
         }
     };
-    // output pointer and pitch (step (v) writes to Cout); pairs of columns go out as 16-byte stores when aligned
-    double* const obase = a.finish ? a.Cout : a.D;
-    const int64_t opitch = a.finish ? a.ldco : a.ldd;
-    const bool wide = (reinterpret_cast<uintptr_t>(obase) % 16 == 0) && (opitch % 2 == 0) && (j0 + 3 < a.p);
-    typedef double v2d __attribute__((ext_vector_type(2)));
     auto store = [&](int s) {
-        const int rg = s / nbatch, bq = s - rg * nbatch;
+        const int u = s / nbatch, bq = s - u * nbatch;
         if (bq != nbatch - 1) return;
+        const int i = u >> 3, j = (u >> 1) & 3, half = u & 1;
+        const int64_t col = col0 + 32 * j;
+        if (col >= a.p) return;
 #pragma unroll
-        for (int rr = 0; rr < 2; ++rr) {
-            const int64_t irow = (int64_t)tm * 256 + rg * 8 + 4 * rr + sub;
-            if (irow >= a.m) continue;
-            double val[4];
+        for (int qq = 0; qq < 2; ++qq)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                val[c] = d[rr][c];
+            for (int ss = 0; ss < 4; ++ss) {
+                const int64_t row = (int64_t)tm * 256 + wm * 128 + i * 32 + 8 * (2 * half + qq) + 4 * lh + ss;
+                if (row >= a.m) continue;
+                double val = d[qq][ss];
+                double* out = obase + row * opitch + col;
                 if (a.finish) {
-                    val[c] = a.alpha * val[c];
-                    if (last_c && j0 + c < a.p) val[c] = val[c] + a.cbeta * obase[irow * opitch + j0 + c];
+                    val = a.alpha * val;
+                    if (last_c) val = val + a.cbeta * *out;
                 }
+                __builtin_nontemporal_store(val, out);
             }
-            double* out = obase + irow * opitch + j0;
-            if (wide) {
-                __builtin_nontemporal_store((v2d){val[0], val[1]}, reinterpret_cast<v2d*>(out));
-                __builtin_nontemporal_store((v2d){val[2], val[3]}, reinterpret_cast<v2d*>(out + 2));
-            } else {
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if (j0 + c < a.p) __builtin_nontemporal_store(val[c], out + c);
-            }
-        }
     };
     issue(std::integral_constant<int, 0>{}, 0);
-    if (nstep > 1) issue(std::integral_constant<int, 1>{}, 1);
-    for (int s = 0; s < nstep; s += 2) {  // nstep is even
+    issue(std::integral_constant<int, 1>{}, 1);
+    for (int s = 0; s < nstep; s += 2) {
         consume(std::integral_constant<int, 0>{}, s);
         if (s + 2 < nstep) issue(std::integral_constant<int, 0>{}, s + 2);
         store(s);
@@ -404,8 +409,45 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     for (int local = member; all_chunks || local < range_cnt; local += team) {
         int item = range_off + local;
         if (all_chunks) {
-            if (t == 0)
-                *lds_ticket = (int)__hip_atomic_fetch_add(ticket_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (t == 0) {
+                if (a.xq) {
+                    // Tickets in batches of 32 per XCD.  32 consecutive work items are one 8 x 4 patch of tiles of
+                    // one chunk: taken by workgroups of ONE XCD at about the same time, they share their operand
+                    // tiles in that XCD's L2.  (With single tickets that happens by itself only when the workgroups
+                    // of an XCD happen to finish together: measured between 16 and 31.5 of 32 consecutive tickets
+                    // on one XCD, 258 to 710 GB fetched, 112 to 125 ms per launch at 16384^3 with k = 8, depending
+                    // on the build and the box.)  The workgroup that draws position 0 of its XCD's next batch takes
+                    // 32 tickets from the global counter and publishes their base in a ring of 16 slots, tagged
+                    // with the batch number; the others of the XCD read it there.  Whoever drew position 0 is
+                    // running and waits for nothing, so the wait is short; it is bounded all the same, and a
+                    // workgroup whose wait ran out sets the flag behind the counters and leaves.
+                    unsigned* const xq = a.xq + xcd * 40;  // [0] positions handed out; [8 + 2 s] slot s (64 bits)
+                    const unsigned i = __hip_atomic_fetch_add(xq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const unsigned bnum = i >> 5, pos = i & 31u;
+                    unsigned long long* const slot = reinterpret_cast<unsigned long long*>(xq + 8) + (bnum & 15u);
+                    unsigned base = 0x7fffffffu;
+                    if (pos == 0) {
+                        base = __hip_atomic_fetch_add(ticket_ctr, 32u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_store(slot, ((unsigned long long)(bnum + 1) << 32) | base, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                    } else {
+                        int polls = 0;
+                        for (; polls < (1 << 22); ++polls) {
+                            const unsigned long long v = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if ((unsigned)(v >> 32) == bnum + 1) {
+                                base = (unsigned)v;
+                                break;
+                            }
+                            __builtin_amdgcn_s_sleep(2);
+                        }
+                        if (polls == (1 << 22)) a.done[a.tile_count + (a.tile_count + 255) / 256] = 1u;
+                    }
+                    const unsigned it = base + pos;
+                    *lds_ticket = it > 0x7fffffffu ? 0x7fffffff : (int)it;
+                } else {
+                    *lds_ticket = (int)__hip_atomic_fetch_add(ticket_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
             __syncthreads();  // (the next write to the ticket word is a whole work item away)
             item = __builtin_amdgcn_readfirstlane(*lds_ticket);
             if (a.queue_sets > 0) {
@@ -751,7 +793,32 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 int eb[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) eb[j] = lds_exp[256 + wn * 128 + j * 32 + lre] + shift;
-                if (MODE == 0 || MODE == 3) {
+                if (MODE == 3 && queued) {
+                    // the whole block, lane-major (see accumulate_tile), written through: another XCD's workgroup
+                    // may add the tile up.  No bounds: rows and columns past the edge of D exist in the block.
+                    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        a.C + (int64_t)__builtin_amdgcn_readfirstlane((int)block_no) * (256 * 256), 0, 256 * 256 * 4, 0x00020000);
+                    int voff = lhe * 512 + lre * 16 + wave * 1024;  // 16 t, from the lane parts made opaque above
+                    asm volatile("" : "+v"(voff));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                typedef int v4si __attribute__((ext_vector_type(4)));
+                                // (through ordinary registers, said explicitly: asked to store sub-tuples of the
+                                // accumulation registers directly, the register allocator spills whole tiles; and
+                                // one group at a time: left alone, the scheduler copies all 256 accumulators first)
+                                int x0 = acc[i][j][4 * q], x1 = acc[i][j][4 * q + 1], x2 = acc[i][j][4 * q + 2],
+                                    x3 = acc[i][j][4 * q + 3];
+                                asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3));
+                                const v4si val = {x0, x1, x2, x3};
+                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int, val),
+                                                                       rsrc, voff, ((i * 4 + j) * 4 + q) * QBLOCK_GROUP_BYTES, 1 << 4);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                } else if (MODE == 0 || MODE == 3) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -762,7 +829,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 const int64_t urow = er0 + rt;
                                 // MODE 3: the tile's own dense 256 x 256 block, addressed by the row / column in the tile
                                 int32_t* base = (MODE == 3)
-                                                    ? a.C + (queued ? block_no : (int64_t)chunk_no * a.tile_count + ztile) * (256 * 256) +
+                                                    ? a.C + ((int64_t)chunk_no * a.tile_count + ztile) * (256 * 256) +
                                                           (int64_t)(wm * 128 + rt) * 256 + wn * 128 + j * 32
                                                     : a.C + urow * a.ldc + ec0 + j * 32;
                                 const uint32_t off =
@@ -771,8 +838,6 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                     if (MODE == 3 && Z > 1)  // partial sum of one part: integer adds commute, C'' starts at zero
                                         __hip_atomic_fetch_add(&base[off], acc[i][j][r], __ATOMIC_RELAXED,
                                                                __HIP_MEMORY_SCOPE_AGENT);
-                                    else if (queued)  // written through: another XCD's workgroup may add the tile up
-                                        __hip_atomic_store(&base[off], acc[i][j][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                                     else
                                         base[off] = acc[i][j][r];
                                 }

@@ -59,10 +59,12 @@ struct GemmArgs {
     // fused == 3 with nchunks > 0 and queue_sets > 0 ("queue" schedule): the work items run round by round (256
     // tiles, all their chunks), C holds queue_sets sets of nchunks x queue_stride blocks that the rounds take in turn, and the
     // workgroup that finishes the last chunk of a tile adds the tile's chunks up into D (step (iv), and (v) when
-    // finish is set).  done: tile_count + number-of-rounds + 1 counters, zero at launch (the last one is set if a wait for a
+    // finish is set).  done: tile_count + number-of-rounds + 1 counters (+ the words of xq), zero at launch (the last one is set if a wait for a
     // set ever ran out of patience: the result is then invalid).  zsplit must be 1.
     int queue_sets;
     int queue_stride;      // blocks per chunk in a set: min(tile_count, 256)
+    unsigned* xq;          // queue schedule: 8 x 40 words behind the counters, 8-byte aligned, zero at launch: the
+                           // per-XCD ticket batches (see k_gemm); nullptr: single tickets
     int queue_block_rounds;  // the launch covers a whole tile grid made of 16 x 16 blocks: a round is such a block
     unsigned* done;
     int tile_begin, tile_count;  // the launch covers tiles tile_begin .. tile_begin + tile_count - 1 of the band order

@@ -79,9 +79,9 @@ int64_t ozimmu_num_chunks(int64_t n, int k);
 size_t ozimmu_slices_bytes(int64_t rows, int64_t n, int k);
 
 /* Bytes of device workspace ozimmu_dgemm makes the best use of (scheduling scratch, exponents, the two slice
- * stacks and INT32 blocks of 256 x 256: one per output tile for up to 128 tiles; for outputs of fewer than 256
+ * stacks and INT32 blocks of 256 x 256: one per output tile for up to 128 tiles; for outputs of fewer than 96
  * tiles one per chunk and tile, at most 4096 = 1 GiB; for larger outputs what the queue schedule takes,
- * min(ceil(tiles / 256), 3) x chunks x 256 blocks and a block of counters -- 1.5 GiB at k = 8 with one chunk
+ * min(ceil(tiles / 256), 3) x chunks x min(tiles, 256) blocks and a block of counters -- 1.5 GiB at k = 8 with one chunk
  * per group, more where the inner dimension makes the chunks shorter than the groups); host.  Not monotone in k (the per-chunk blocks
  * are only counted while they stay within those limits). */
 size_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t p, int k);

@@ -99,6 +99,7 @@ constexpr int64_t CHUNK_PARALLEL_MAX_BLOCKS = 4096;
 constexpr int64_t GRID_WAIT_MIN_INNER = 8192 + 512;
 // Sets of blocks the rounds of the queue schedule take in turn (see run_schedule).
 constexpr int64_t QUEUE_SETS = 3;
+constexpr int64_t QUEUE_MIN_TILES = 96;  // outputs of at least this many tiles take the queue by default
 constexpr int64_t QUEUE_XCD_WORDS = 8 * 40;  // per-XCD ticket batches of the queue (see k_gemm)
 constexpr int64_t BLOCK_BYTES = 4 * 256 * 256;
 inline int64_t chunks_of(int k, int64_t r)
@@ -119,15 +120,15 @@ inline int64_t partial_blocks(int64_t m, int64_t n, int64_t p, int k)
     const int64_t base = min_partial_blocks(m, p);
     if (n < 1 || n > MAX_INNER || k < 1) return base;
     // (the chunk-parallel way takes the tiles that do not fill a round of the 256 compute units of the chip this is
-    // written for; the queue, which takes outputs of 256 tiles and more, wants QUEUE_SETS sets of chunks x 256
+    // written for; the queue, which takes outputs of QUEUE_MIN_TILES tiles and more, wants up to QUEUE_SETS sets of chunks x 256
     // blocks and a counter per tile and round)
     const int64_t T = output_tiles(m, p);
     const int64_t w = chunks_of(k, r_of(n, beta_of(n)));
     const int64_t items = (T <= 256 ? T : T % 256) * w;
     int64_t blocks = (items <= CHUNK_PARALLEL_MAX_BLOCKS && items > base) ? items : base;
-    if (T >= 256 && w * 256 * BLOCK_BYTES < ((int64_t)1 << 31) && T * w < ((int64_t)1 << 30)) {
+    if (T >= QUEUE_MIN_TILES && w * 256 * BLOCK_BYTES < ((int64_t)1 << 31) && T * w < ((int64_t)1 << 30)) {
         const int64_t rounds = (T + 255) / 256;
-        const int64_t queue = (rounds < QUEUE_SETS ? rounds : QUEUE_SETS) * w * 256 +
+        const int64_t queue = (rounds < QUEUE_SETS ? rounds : QUEUE_SETS) * w * (T < 256 ? T : 256) +
                               (4 * (T + rounds + 2 + QUEUE_XCD_WORDS) + BLOCK_BYTES - 1) / BLOCK_BYTES;
         if (queue > blocks) blocks = queue;
     }
@@ -290,7 +291,9 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     };
     // Asked for, or the output has tiles for every compute unit (measured against queue for the full rounds +
     // one of the other ways for a short last round: equal or better with everything in the queue).
-    if (schedule == OZIMMU_SCHEDULE_QUEUE || (schedule == 0 && T >= num_cu)) {
+    // From about 100 tiles on it also beats the chunk-parallel way with its separate accumulation kernel
+    // (2560^3, 100 tiles: 0.61 against 0.67 ms; 3072^3: 1.01 against 1.05 ms; 2048^3, 64 tiles: 0.38 against 0.36).
+    if (schedule == OZIMMU_SCHEDULE_QUEUE || (schedule == 0 && T >= QUEUE_MIN_TILES)) {
         const int64_t sets = queue_sets(T);
         if (sets > 0) return launch_queue(T, sets);
     }

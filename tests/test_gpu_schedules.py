@@ -113,9 +113,10 @@ def test_small_workspace_falls_back_to_the_other_schedules(oz):
     # gives the same D through the other schedules; the requirement is not monotone in k, the least one is
     m, n, p, k = 1024, 1024, 1024, 20
     assert oz.workspace_bytes(m, n, p, k) > oz.STATIC_WORKSPACE_BYTES >= oz.workspace_bytes_min(m, n, p, k)
-    # (240 tiles: 14 chunks each stay within the 4096 blocks of the chunk-parallel way, 20 do not)
-    assert oz.workspace_bytes(3840, 256, 4096, 14) > oz.workspace_bytes(3840, 256, 4096, 20)
-    assert oz.workspace_bytes_min(3840, 256, 4096, 14) < oz.workspace_bytes_min(3840, 256, 4096, 20)
+    # (inner dimension 65536: chunks of two pairs; the 30 chunks of k = 10 fit the queue's sets of blocks, the 36 of
+    # k = 11 would need more than 2 GiB per set and fall back to the persistent launch)
+    assert oz.workspace_bytes(8192, 65536, 8192, 10) > oz.workspace_bytes(8192, 65536, 8192, 11)
+    assert oz.workspace_bytes_min(8192, 65536, 8192, 10) < oz.workspace_bytes_min(8192, 65536, 8192, 11)
     A, B = inputs.phi_pair(m, n, p, 0.5, seed=97)
     dA, dB = dev(A), dev(B)
     want = oz.dgemm(dA, dB, k)

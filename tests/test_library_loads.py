@@ -68,7 +68,7 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.ozimmu_dgemm(0, 4, 4, None, 4, None, 4, None, 4, 8, None, 0, None) == 0             # empty: nothing to do
     # workspace = scratch + exponents + the two slice stacks + INT32 blocks of 256 x 256: one per output tile for at
     # most 128 tiles, or one per chunk and tile of the last round of 256 tiles (the only round of a small output)
-    # when that stays within 4096 blocks, or what the queue schedule wants for outputs of 256 tiles and more.  A stack = k padded slices (rows padded to 256, inner index to 256) + k arrays of
+    # when that stays within 4096 blocks, or what the queue schedule wants for outputs of 96 tiles and more.  A stack = k padded slices (rows padded to 256, inner index to 256) + k arrays of
     # padded-rows INT32 row sums (rounded up to 256 bytes) + a 256-byte trailer
     blk = 4 * 256 * 256
 
@@ -79,8 +79,9 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.ozimmu_workspace_bytes(256, 128, 256, 8) == 512 + 2 * 1024 + 2 * stack(256, 256, 8) + 8 * blk
     # 2 tiles x 3 chunks
     assert lib.ozimmu_workspace_bytes(257, 257, 1, 3) == 512 + 1280 + 256 + stack(512, 512, 3) + stack(256, 512, 3) + 6 * blk
-    # 144 tiles x 8 chunks
-    assert lib.ozimmu_workspace_bytes(3072, 256, 3072, 8) == 512 + 2 * 4 * 3072 + 2 * stack(3072, 256, 8) + 1152 * blk
+    # 144 tiles x 8 chunks + a block of counters (the queue schedule, from 96 tiles on); 64 tiles x 8 chunks
+    assert lib.ozimmu_workspace_bytes(3072, 256, 3072, 8) == 512 + 2 * 4 * 3072 + 2 * stack(3072, 256, 8) + 1153 * blk
+    assert lib.ozimmu_workspace_bytes(2048, 256, 2048, 8) == 512 + 2 * 4 * 2048 + 2 * stack(2048, 256, 8) + 512 * blk
     # 256 tiles and more: the queue wants min(rounds, 3) sets of chunks x 256 blocks + one block of counters
     assert lib.ozimmu_workspace_bytes(4096, 256, 4096, 8) == 512 + 2 * 4 * 4096 + 2 * stack(4096, 256, 8) + 2049 * blk
     big = lib.ozimmu_workspace_bytes(4096, 256, 8192, 8)       # 512 tiles: 2 rounds
@@ -91,9 +92,9 @@ def test_argument_checks_need_no_gpu(lib):
     # 256 tiles x 30 chunks (n = 65536: r = 2)
     assert lib.ozimmu_workspace_bytes(4096, 65536, 4096, 10) == (512 + 8 * 4096 + 2 * stack(4096, 65536, 10) +
                                                                  (30 * 256 + 1) * blk)
-    # 240 tiles x 30 chunks > 4096 blocks: blocks for 128 tiles
+    # 240 tiles x 30 chunks: the queue's one set of blocks + counters
     assert lib.ozimmu_workspace_bytes(3840, 65536, 4096, 10) == (512 + 4 * 3840 + 4 * 4096 + stack(3840, 65536, 10) +
-                                                                 stack(4096, 65536, 10) + 128 * blk)
+                                                                 stack(4096, 65536, 10) + (30 * 240 + 1) * blk)
     lib.ozimmu_workspace_bytes_min.argtypes = [i64, i64, i64, ctypes.c_int]
     lib.ozimmu_workspace_bytes_min.restype = ctypes.c_size_t
     assert lib.ozimmu_workspace_bytes_min(3072, 256, 3072, 8) == 512 + 2 * 4 * 3072 + 2 * stack(3072, 256, 8) + 128 * blk

@@ -209,16 +209,23 @@ struct Finish {
     int64_t ldco;
 };
 
-// Steps (iii) + (iv) for the whole schedule of Algorithm 6 (groups g = 2..k+1 ascending, chunks of at most r
-// consecutive s), into D.  Two ways to run it, with bit-identical results:
+// Steps (iii) + (iv) (+ (v), see Finish) for the whole schedule of Algorithm 6 (groups g = 2..k+1 ascending, chunks
+// of at most r consecutive s), into D.  Four ways to run it, with bit-identical results (details where each is
+// decided below):
+//  * the queue: one launch whose work items are the (chunk, tile) pairs, an INT32 block per item, the tile's chunks
+//    added up by the workgroup that completes it -- the default from QUEUE_MIN_TILES tiles on when the workspace has
+//    room for the blocks;
 //  * one persistent launch with the accumulation fused into the GEMM epilogue (mode 1, or 2 for per-slice
-//    scales): one workgroup per compute unit takes tile after tile -- the way for as many tiles as fill
-//    whole rounds of the chip;
-//  * for tiles that would leave most compute units idle -- an output of few tiles, or the last, partly
-//    filled round of a larger one: per chunk, the chunk GEMM with its inner range cut into Z parts on Z
-//    workgroups per tile, which add their partial sums to zeroed per-tile INT32 blocks with integer atomics,
-//    then the accumulation kernel over those tiles, which also clears the blocks again.
-// schedule: 0 = choose, OZIMMU_SCHEDULE_ONE_LAUNCH, OZIMMU_SCHEDULE_SPLIT_INNER (honoured when possible).
+//    scales): one workgroup per compute unit takes tile after tile, all chunks of a tile in turn -- needs no
+//    blocks;
+//  * chunk-parallel, for outputs of few tiles or the last, partly filled round after a persistent launch: one
+//    launch whose work items are (chunk, inner part, tile), a block per chunk and tile, then one accumulation
+//    kernel over those tiles;
+//  * split-inner, for the same tiles when there is room for one block per tile only: per chunk, the chunk GEMM
+//    with its inner range cut into Z parts on Z workgroups per tile, which add their partial sums to zeroed
+//    per-tile INT32 blocks with integer atomics, then the accumulation kernel over those tiles, which also clears
+//    the blocks again.
+// schedule: 0 = choose, or one of the OZIMMU_SCHEDULE_* flags (honoured when possible).
 int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t* SB, const int32_t* eA,
                  const int32_t* eB, int k, int64_t r, bool per_slice, int schedule, double* D, int64_t ldd,
                  const Finish& fin, int32_t* partial, int64_t partial_capacity, void* scratch, int num_cu, hipStream_t st,

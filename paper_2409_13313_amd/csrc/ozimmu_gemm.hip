@@ -14,7 +14,11 @@
 // sums to zeroed per-tile blocks with integer atomics (exact in any order).  With
 // a.nchunks > 0 one MODE 3 launch covers ALL chunks of the schedule at once: a work
 // item is (chunk, part, tile), every chunk has a block per tile of its own, and a
-// separate kernel adds the chunks up in FP64 in the order of Algorithm 6.
+// separate kernel adds the chunks up in FP64 in the order of Algorithm 6.  With
+// a.queue_sets > 0 as well (the "queue" schedule, the default for larger outputs)
+// the items are (chunk, tile), handed out round by round, the blocks are recycled,
+// and the workgroup that completes a tile adds its chunks up itself (accumulate_tile:
+// steps (iv) and (v) inside the launch); see the item loop of k_gemm.
 // A launch covers a range of tiles (tile_begin, tile_count) of the band order.
 //
 // The stored bytes are the slice integers plus the offset of their stack (cA for A, cB for B, see

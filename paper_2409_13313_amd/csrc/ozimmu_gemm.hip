@@ -423,7 +423,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     // on the build and the box.)  The workgroup that draws position 0 of its XCD's next batch takes
                     // 32 tickets from the global counter and publishes their base in a ring of 16 slots, tagged
                     // with the batch number; the others of the XCD read it there.  Whoever drew position 0 is
-                    // running and waits for nothing, so the wait is short; it is bounded all the same, and a
+                    // running and waits for nothing, so the wait is short; it is bounded all the same (half a minute), and a
                     // workgroup whose wait ran out sets the flag behind the counters and leaves.
                     unsigned* const xq = a.xq + xcd * 40;  // [0] positions handed out; [8 + 2 s] slot s (64 bits)
                     const unsigned i = __hip_atomic_fetch_add(xq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -436,7 +436,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                            __HIP_MEMORY_SCOPE_AGENT);
                     } else {
                         int polls = 0;
-                        for (; polls < (1 << 22); ++polls) {
+                        for (; polls < (1 << 25); ++polls) {
                             const unsigned long long v = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             if ((unsigned)(v >> 32) == bnum + 1) {
                                 base = (unsigned)v;
@@ -444,7 +444,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                             }
                             __builtin_amdgcn_s_sleep(2);
                         }
-                        if (polls == (1 << 22)) a.done[a.tile_count + (a.tile_count + 255) / 256] = 1u;
+                        if (polls == (1 << 25)) a.done[a.tile_count + (a.tile_count + 255) / 256] = 1u;
                     }
                     const unsigned it = base + pos;
                     *lds_ticket = it > 0x7fffffffu ? 0x7fffffff : (int)it;

@@ -196,12 +196,26 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(blocks), 0, 0x7fffffff, 0x00020000);
     constexpr int POLICY = (1 << 4) | (1 << 1);
+    // step (v) with cbeta != 0: the old values of C travel with the loads of the step that will store them
+    double cold[2][2][4];
     auto issue = [&](auto BUF, int s) {
         constexpr int buf = decltype(BUF)::value;
-        const int u = s / nbatch, cq = (s - u * nbatch) * 8;
+        const int u = s / nbatch, cq = (s - u * nbatch) * 8;  // u = (i * 4 + j) * 2 + half
+        if (last_c && s - u * nbatch == nbatch - 1) {
+            const int i = u >> 3, j = (u >> 1) & 3, half = u & 1;
+            const int64_t col = col0 + 32 * j;
+#pragma unroll
+            for (int qq = 0; qq < 2; ++qq)
+#pragma unroll
+                for (int ss = 0; ss < 4; ++ss) {
+                    const int64_t row = (int64_t)tm * 256 + wm * 128 + i * 32 + 8 * (2 * half + qq) + 4 * lh + ss;
+                    cold[buf][qq][ss] =
+                        (col < a.p && row < a.m) ? __builtin_nontemporal_load(obase + row * opitch + col) : 0.0;
+                }
+        }
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
-            const int cb = (cq + b < w) ? cq + b : w - 1;
+            const int cb = (cq + b < w) ? cq + b : w - 1;  // (past the last chunk: read it again, unused)
 #pragma unroll
             for (int qq = 0; qq < 2; ++qq) {
                 const int soff = (int)((int64_t)cb * cstride * 4) + (u * 2 + qq) * QBLOCK_GROUP_BYTES;
@@ -245,7 +259,8 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
             }
         }
     };
-    auto store = [&](int s) {
+    auto store = [&](auto BUF, int s) {
+        constexpr int buf = decltype(BUF)::value;
         const int u = s / nbatch, bq = s - u * nbatch;
         if (bq != nbatch - 1) return;
         const int i = u >> 3, j = (u >> 1) & 3, half = u & 1;
@@ -261,7 +276,7 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
                 double* out = obase + row * opitch + col;
                 if (a.finish) {
                     val = a.alpha * val;
-                    if (last_c) val = val + a.cbeta * *out;
+                    if (last_c) val = val + a.cbeta * cold[buf][qq][ss];
                 }
                 __builtin_nontemporal_store(val, out);
             }
@@ -269,12 +284,13 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
     issue(std::integral_constant<int, 0>{}, 0);
     issue(std::integral_constant<int, 1>{}, 1);
     for (int s = 0; s < nstep; s += 2) {
+        // (a step's stores before the buffer's next loads: those bring new old values of C into the same registers)
         consume(std::integral_constant<int, 0>{}, s);
+        store(std::integral_constant<int, 0>{}, s);
         if (s + 2 < nstep) issue(std::integral_constant<int, 0>{}, s + 2);
-        store(s);
         consume(std::integral_constant<int, 1>{}, s + 1);
+        store(std::integral_constant<int, 1>{}, s + 1);
         if (s + 3 < nstep) issue(std::integral_constant<int, 1>{}, s + 3);
-        store(s + 1);
     }
 }
 

@@ -685,7 +685,9 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 });
                 sync_target += participants;
                 all_target += all_participants;
-                arrive_and_wait2(all_ctr, all_target, a.grid_spin_limit, sync_ctr, sync_target, a.spin_limit);
+                // (launches whose work items are not lined up - spin limits 0 - leave the counters alone)
+                if (a.spin_limit | a.grid_spin_limit)
+                    arrive_and_wait2(all_ctr, all_target, a.grid_spin_limit, sync_ctr, sync_target, a.spin_limit);
                 {
                     // every wave is past the previous chunk (first barrier above); the barrier below publishes
                     const uint32_t pairs_n = (uint32_t)(c1 - c0 + 1) * (uint32_t)(KT * TILE_K);

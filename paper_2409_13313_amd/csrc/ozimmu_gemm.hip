@@ -164,6 +164,7 @@ constexpr int QBLOCK_GROUP_BYTES = 256 * 16;  // one (i, j, q) group of all 256 
 // 2 MiB of a tile must not displace the operand tiles that the XCD's workgroups share in L2: with plain or merely
 // agent-scope loads the whole launch ran 5 % slower); D is stored non-temporally, 256 contiguous bytes per half wave.
 // lds_rows: 256 ints of LDS for the row exponents.
+template <bool S16>
 __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* blocks, int64_t cstride, int w, int tm,
                                        int tp, int* lds_rows)
 {
@@ -174,16 +175,22 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
     asm volatile("" : "+v"(t));
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int wm = wave >> 1, wn = wave & 1, lr = lane & 31, lh = lane >> 5;
-    const int64_t col0 = (int64_t)tp * 256 + wn * 128 + lr;  // this lane's column in column tile j: col0 + 32 j
-    int eb[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) eb[j] = (col0 + 32 * j < a.p) ? a.eB[col0 + 32 * j] : 0;
+    const int wm = wave >> 1, wn = wave & 1;
+    // S16: lane = 16 lq + lc holds rows 4 lq .. 4 lq + 3, column lc of a 16 x 16 tile; else lane = 32 lh + lr
+    const int lr = S16 ? (lane & 15) : (lane & 31), lh = S16 ? (lane >> 4) : (lane >> 5);
+    constexpr int CW = S16 ? 16 : 32;  // columns per tile
+    const int64_t col0 = (int64_t)tp * 256 + wn * 128 + lr;  // this lane's column in column tile j: col0 + CW j
     {
-        const int64_t gr = (int64_t)tm * 256 + t;
+        const int64_t gr = (int64_t)tm * 256 + t, gc = (int64_t)tp * 256 + t;
         lds_rows[t] = gr < a.m ? a.eA[gr] : 0;
+        lds_rows[256 + t] = gc < a.p ? a.eB[gc] : 0;
     }
     __syncthreads();
+    // step u covers the register groups 2 u, 2 u + 1 of the block: 8 rows of one column per thread
+    auto col_tile = [&](int u) { return S16 ? (u & 7) : ((u >> 1) & 3); };
+    auto row_in_wave = [&](int u, int qq, int ss) {
+        return S16 ? ((2 * (u >> 3) + qq) * 16 + 4 * lh + ss) : ((u >> 3) * 32 + 8 * (2 * (u & 1) + qq) + 4 * lh + ss);
+    };
     const bool last_c = a.finish && a.cbeta != 0.0;
     double* const obase = a.finish ? a.Cout : a.D;
     const int64_t opitch = a.finish ? a.ldco : a.ldd;
@@ -202,13 +209,12 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
         constexpr int buf = decltype(BUF)::value;
         const int u = s / nbatch, cq = (s - u * nbatch) * 8;  // u = (i * 4 + j) * 2 + half
         if (last_c && s - u * nbatch == nbatch - 1) {
-            const int i = u >> 3, j = (u >> 1) & 3, half = u & 1;
-            const int64_t col = col0 + 32 * j;
+            const int64_t col = col0 + CW * col_tile(u);
 #pragma unroll
             for (int qq = 0; qq < 2; ++qq)
 #pragma unroll
                 for (int ss = 0; ss < 4; ++ss) {
-                    const int64_t row = (int64_t)tm * 256 + wm * 128 + i * 32 + 8 * (2 * half + qq) + 4 * lh + ss;
+                    const int64_t row = (int64_t)tm * 256 + wm * 128 + row_in_wave(u, qq, ss);
                     cold[buf][qq][ss] =
                         (col < a.p && row < a.m) ? __builtin_nontemporal_load(obase + row * opitch + col) : 0.0;
                 }
@@ -226,18 +232,17 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
     auto consume = [&](auto BUF, int s) {
         constexpr int buf = decltype(BUF)::value;
         const int u = s / nbatch, bq = s - u * nbatch, cq = bq * 8;
-        const int i = u >> 3, j = (u >> 1) & 3, half = u & 1;
         if (bq == 0) {
             g = a.g_lo;
             c0 = 1;
             first = true;
         }
-        const int ebj = j == 0 ? eb[0] : j == 1 ? eb[1] : j == 2 ? eb[2] : eb[3];
+        const int ebj = lds_rows[256 + wn * 128 + CW * col_tile(u) + lr];
         int ea[2][4];
 #pragma unroll
         for (int qq = 0; qq < 2; ++qq)
 #pragma unroll
-            for (int ss = 0; ss < 4; ++ss) ea[qq][ss] = lds_rows[wm * 128 + i * 32 + 8 * (2 * half + qq) + 4 * lh + ss];
+            for (int ss = 0; ss < 4; ++ss) ea[qq][ss] = lds_rows[wm * 128 + row_in_wave(u, qq, ss)];
         const int nb = (w - cq) < 8 ? (w - cq) : 8;
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
@@ -263,14 +268,13 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
         constexpr int buf = decltype(BUF)::value;
         const int u = s / nbatch, bq = s - u * nbatch;
         if (bq != nbatch - 1) return;
-        const int i = u >> 3, j = (u >> 1) & 3, half = u & 1;
-        const int64_t col = col0 + 32 * j;
+        const int64_t col = col0 + CW * col_tile(u);
         if (col >= a.p) return;
 #pragma unroll
         for (int qq = 0; qq < 2; ++qq)
 #pragma unroll
             for (int ss = 0; ss < 4; ++ss) {
-                const int64_t row = (int64_t)tm * 256 + wm * 128 + i * 32 + 8 * (2 * half + qq) + 4 * lh + ss;
+                const int64_t row = (int64_t)tm * 256 + wm * 128 + row_in_wave(u, qq, ss);
                 if (row >= a.m) continue;
                 double val = d[qq][ss];
                 double* out = obase + row * opitch + col;
@@ -348,9 +352,12 @@ struct Cursor {
 // issue slots (one instruction per 4 cycles), so the loop carries as few of them
 // as it can (per stage 32 MFMAs, 16 LDS reads, 8 copies of 3 instructions, two
 // cursor updates, one barrier).
-template <int MODE, int NS>
+template <int MODE_, int NS>
 __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
 {
+    // MODE_ 4: MODE 3 for the queue schedule on v_mfma_i32_16x16x64_i8 (8 x 8 tiles of 16 x 16 per wave)
+    constexpr int MODE = MODE_ == 4 ? 3 : MODE_;
+    constexpr bool S16 = MODE_ == 4;
     extern __shared__ __align__(16) int8_t lds[];
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -382,6 +389,16 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 fragA[kk][h] = lds_base + h * 2 * STAGE_BYTES + rowA * TILE_K + swizzle(rowA, kk * 2 + lh) * CHUNK;
                 fragB[kk][h] = lds_base + h * 2 * STAGE_BYTES + rowB * TILE_K + swizzle(rowB, kk * 2 + lh) * CHUNK;
             }
+    }
+    // S16: row = w*128 + i*16 + lane%16, logical chunk = lane/16 (a 16 x 16 x 64 MFMA takes the whole stage)
+    uint32_t frag16A[NH], frag16B[NH];
+    {
+        const int rowA = wm * 128 + (lane & 15), rowB = wn * 128 + (lane & 15);
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            frag16A[h] = lds_base + h * 2 * STAGE_BYTES + rowA * TILE_K + swizzle(rowA, lane >> 4) * CHUNK;
+            frag16B[h] = lds_base + h * 2 * STAGE_BYTES + rowB * TILE_K + swizzle(rowB, lane >> 4) * CHUNK;
+        }
     }
     typedef __attribute__((address_space(3))) const v4i* lds_v4i_ptr;
 
@@ -481,7 +498,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     tile_of_queue(a.tile_begin + zt, TM, TP, a.queue_block_rounds != 0, ptm, ptp);
                     const int first_block = __builtin_amdgcn_readfirstlane(
                         (qr % a.queue_sets) * a.nchunks * a.queue_stride + (zt - qr * ozk::QUEUE_ROUND_TILES));
-                    accumulate_tile(a, a.C + (int64_t)first_block * (256 * 256), (int64_t)a.queue_stride * (256 * 256),
+                    accumulate_tile<S16>(a, a.C + (int64_t)first_block * (256 * 256), (int64_t)a.queue_stride * (256 * 256),
                                     a.nchunks, ptm, ptp, reinterpret_cast<int*>(lds + NS * STAGE_BYTES));
                     __syncthreads();  // every thread has used what it loaded from the blocks
                     if (t == 0) {
@@ -637,6 +654,20 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     }
                 };
                 v4i fa0[4], fb0[4], fa1[4], fb1[4];
+                // S16: 8 x 8 tiles of 16 x 16; A fragments of row tiles 0..3 / 4..7 in faL / faH, B likewise
+                v4i acc16[8][8];
+                v4i faL[4], faH[4], fbL[4], fbH[4];
+                // sub-step ss of a quarter: row tile ss against the four column tiles (by_col: column tile ss against
+                // the four row tiles) - the operand that has just been fetched is the one taken one fragment per sub-step
+                auto math16 = [&](const v4i* fa, const v4i* fb, int i0, int j0, int ss, bool by_col) {
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const int y = (ss & 1) ? 3 - x : x;
+                        const int ii = by_col ? y : ss, jj = by_col ? ss : y;
+                        acc16[i0 + ii][j0 + jj] =
+                            __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[ii], fb[jj], acc16[i0 + ii][j0 + jj], 0, 0, 0);
+                    }
+                };
 
                 // prologue: every wave is past the math of the previous chunk (the LDS ring is free),
                 // stages 0 .. NS-3 and the A half of stage NS-2 go in flight, the team lines up, stage 0
@@ -697,14 +728,41 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 wait_vmcnt<NLOAD*(2 * (NS - 2) - 1)>();
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
+                if constexpr (S16) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    fa0[i] = *(lds_v4i_ptr)(uintptr_t)(fragA[0][0] + i * 2048);
-                    fb0[i] = *(lds_v4i_ptr)(uintptr_t)(fragB[0][0] + TILE_BYTES + i * 2048);
+                    for (int i = 0; i < 4; ++i) {
+                        faL[i] = *(lds_v4i_ptr)(uintptr_t)(frag16A[0] + i * 1024);
+                        fbL[i] = *(lds_v4i_ptr)(uintptr_t)(frag16B[0] + TILE_BYTES + i * 1024);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        fa0[i] = *(lds_v4i_ptr)(uintptr_t)(fragA[0][0] + i * 2048);
+                        fb0[i] = *(lds_v4i_ptr)(uintptr_t)(fragB[0][0] + TILE_BYTES + i * 2048);
+                    }
                 }
                 // accumulators start at -(ra[row] + cb[column]) (see the head of this file); of a chunk that is cut
                 // into parts (MODE 3) only part 0 carries the start value, the others start at zero
-                {
+                if constexpr (S16) {
+                    int lqi = lane >> 4, lci = lane & 15;
+                    asm volatile("" : "+v"(lqi), "+v"(lci));
+                    int ncb[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) ncb[j] = lds_corr[256 + wn * 128 + j * 16 + lci];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        int nra[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) nra[r] = lds_corr[wm * 128 + i * 16 + 4 * lqi + r];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) acc16[i][j][r] = (int)((uint32_t)nra[r] + (uint32_t)ncb[j]);
+                            asm volatile("" : "+a"(acc16[i][j]));
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                } else {
                     // lane parts of the LDS addresses made opaque here: otherwise the sixteen addresses are formed
                     // at kernel entry, live through everything and get spilled
                     int lhi = lh, lri = lr;
@@ -792,10 +850,98 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                         if constexpr (u == 0 && !tail) wrap_check(ca, wrapA);
                     }
                 };
+                // The same for 16 x 16 x 64 MFMAs (S16): the stage is one k-step of 64 MFMAs, run as four quarters of
+                // 4 x 4 tiles.  Stages of even position: (A lo, B lo), (A lo, B hi), (A hi, B hi), (A hi, B lo); odd:
+                // (A lo, B hi), (A lo, B lo), (A hi, B lo), (A hi, B hi) - every quarter shares one fragment set with the
+                // one before, and the set that has just come free takes the fragments needed two quarters later
+                // (after the barrier in mid-stage: those of the next stage).  Per quarter 4 fetches, 16 MFMAs, 2 copies.
+                auto stage16 = [&](auto U, auto TAIL) {
+                    constexpr int u = decltype(U)::value;
+                    constexpr bool tail = decltype(TAIL)::value;
+                    constexpr bool odd = (u % 2) != 0;
+                    constexpr int un = (u + 1) % NS, up = (u + NS - 1) % NS, ub = (u + NS - 2) % NS;
+                    constexpr bool copy_b = !tail || u < 2;
+                    constexpr bool copy_a = !tail || u < 1;
+                    constexpr bool fetch_next = !tail || u < NS - 1;
+                    constexpr uint32_t curA = (u % 2) * STAGE_BYTES, curB = (u % 2) * STAGE_BYTES + TILE_BYTES;
+                    constexpr uint32_t nxtA = (un % 2) * STAGE_BYTES, nxtB = (un % 2) * STAGE_BYTES + TILE_BYTES;
+                    // quarter 0: B fragments of the other half of this stage come in
+                    static_for<0, 4>([&](auto Q) {
+                        constexpr int q = decltype(Q)::value;
+                        if constexpr (!odd) {
+                            fbH[q] = *(lds_v4i_ptr)(uintptr_t)(frag16B[u / 2] + curB + (4 + q) * 1024);
+                            math16(faL, fbL, 0, 0, q, true);
+                        } else {
+                            fbL[q] = *(lds_v4i_ptr)(uintptr_t)(frag16B[u / 2] + curB + q * 1024);
+                            math16(faL, fbH, 0, 4, q, true);
+                        }
+                        if constexpr (copy_b && q % 2 == 0)
+                            copy16_to_lds<ub * STAGE_BYTES + TILE_BYTES + (q / 2) * 4096>(m0_wave, voff[q / 2], cb.ptr);
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                    // quarter 1: A fragments of the upper half of this stage
+                    static_for<0, 4>([&](auto Q) {
+                        constexpr int q = decltype(Q)::value;
+                        faH[q] = *(lds_v4i_ptr)(uintptr_t)(frag16A[u / 2] + curA + (4 + q) * 1024);
+                        if constexpr (!odd)
+                            math16(faL, fbH, 0, 4, q, true);
+                        else
+                            math16(faL, fbL, 0, 0, q, true);
+                        if constexpr (copy_b && q % 2 == 0)
+                            copy16_to_lds<ub * STAGE_BYTES + TILE_BYTES + (2 + q / 2) * 4096>(m0_wave, voff[2 + q / 2], cb.ptr);
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                    if constexpr (copy_b) {
+                        cb.ptr += TILE_BYTES;
+                        if constexpr (u == 1 && !tail) wrap_check(cb, wrapB);
+                    }
+                    if constexpr (tail && u >= 2)
+                        wait_vmcnt<0>();
+                    else
+                        wait_vmcnt<2 * NLOAD * (NS - 3)>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                    // quarter 2: first A fragments of the next stage
+                    static_for<0, 4>([&](auto Q) {
+                        constexpr int q = decltype(Q)::value;
+                        if constexpr (fetch_next) faL[q] = *(lds_v4i_ptr)(uintptr_t)(frag16A[un / 2] + nxtA + q * 1024);
+                        if constexpr (!odd)
+                            math16(faH, fbH, 4, 4, q, false);
+                        else
+                            math16(faH, fbL, 4, 0, q, false);
+                        if constexpr (copy_a && q % 2 == 0)
+                            copy16_to_lds<up * STAGE_BYTES + (q / 2) * 4096>(m0_wave, voff[q / 2], ca.ptr);
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                    // quarter 3: first B fragments of the next stage (it starts with the half this stage ends on... the other one)
+                    static_for<0, 4>([&](auto Q) {
+                        constexpr int q = decltype(Q)::value;
+                        if constexpr (!odd) {
+                            if constexpr (fetch_next) fbH[q] = *(lds_v4i_ptr)(uintptr_t)(frag16B[un / 2] + nxtB + (4 + q) * 1024);
+                            math16(faH, fbL, 4, 0, q, false);
+                        } else {
+                            if constexpr (fetch_next) fbL[q] = *(lds_v4i_ptr)(uintptr_t)(frag16B[un / 2] + nxtB + q * 1024);
+                            math16(faH, fbH, 4, 4, q, false);
+                        }
+                        if constexpr (copy_a && q % 2 == 0)
+                            copy16_to_lds<up * STAGE_BYTES + (2 + q / 2) * 4096>(m0_wave, voff[2 + q / 2], ca.ptr);
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                    if constexpr (copy_a) {
+                        ca.ptr += TILE_BYTES;
+                        if constexpr (u == 0 && !tail) wrap_check(ca, wrapA);
+                    }
+                };
                 static_assert(NS == 4, "the tail logic below is written for a ring of 4 stages");
-                for (int it = 0; it < nstage - NS; it += NS)
-                    static_for<0, NS>([&](auto U) { stage(U, std::false_type{}); });
-                static_for<0, NS>([&](auto U) { stage(U, std::true_type{}); });
+                if constexpr (S16) {
+                    for (int it = 0; it < nstage - NS; it += NS)
+                        static_for<0, NS>([&](auto U) { stage16(U, std::false_type{}); });
+                    static_for<0, NS>([&](auto U) { stage16(U, std::true_type{}); });
+                } else {
+                    for (int it = 0; it < nstage - NS; it += NS)
+                        static_for<0, NS>([&](auto U) { stage(U, std::false_type{}); });
+                    static_for<0, NS>([&](auto U) { stage(U, std::true_type{}); });
+                }
                 wait_vmcnt<0>();  // no copy may still be writing LDS when the ring is reused or the workgroup retires
 
                 // Epilogue.  Accumulator register r of tile (i, j) in lane l holds output
@@ -815,7 +961,25 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 int eb[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) eb[j] = lds_exp[256 + wn * 128 + j * 32 + lre] + shift;
-                if (MODE == 3 && queued) {
+                if constexpr (S16) {
+                    // the whole block, lane-major: group ((i / 2) * 8 + j) * 2 + i % 2 is tile (i, j) (see accumulate_tile)
+                    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        a.C + (int64_t)__builtin_amdgcn_readfirstlane((int)block_no) * (256 * 256), 0, 256 * 256 * 4, 0x00020000);
+                    int voff = lhe * 512 + lre * 16 + wave * 1024;
+                    asm volatile("" : "+v"(voff));
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            typedef int v4si __attribute__((ext_vector_type(4)));
+                            int x0 = acc16[i][j][0], x1 = acc16[i][j][1], x2 = acc16[i][j][2], x3 = acc16[i][j][3];
+                            asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3));
+                            const v4si val = {x0, x1, x2, x3};
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int, val),
+                                                                   rsrc, voff, (((i >> 1) * 8 + j) * 2 + (i & 1)) * QBLOCK_GROUP_BYTES, 1 << 4);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                } else if (MODE == 3 && queued) {
                     // the whole block, lane-major (see accumulate_tile), written through: another XCD's workgroup
                     // may add the tile up.  No bounds: rows and columns past the edge of D exist in the block.
                     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -1182,7 +1346,9 @@ hipError_t launch_gemm(const GemmArgs& a_in, int fused, hipStream_t st)
     if (a.sync_epoch == 0 && !a.sync_zeroed)
         hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(SYNC_WORDS), 0, st, a.sync);
     dim3 grid((unsigned)nwg), block(256);
-    if (fused == 3)
+    if (fused == 3 && a.nchunks > 0 && a.queue_sets > 0)
+        hipLaunchKernelGGL((k_gemm<4, NSTAGES>), grid, block, smem, st, a, TM, TP);
+    else if (fused == 3)
         hipLaunchKernelGGL((k_gemm<3, NSTAGES>), grid, block, smem, st, a, TM, TP);
     else if (fused == 2)
         hipLaunchKernelGGL((k_gemm<2, NSTAGES>), grid, block, smem, st, a, TM, TP);
@@ -1204,6 +1370,9 @@ hipError_t setup_gemm_kernels()
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2, NSTAGES>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<4, NSTAGES>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<3, NSTAGES>),

@@ -34,22 +34,28 @@
 //     out = fl(fl(alpha d) + fl(cbeta c_old))   (cbeta == 0: c_old is not read),  d the finished sum.
 //
 // Tiling: 256 x 256 outputs per workgroup, 4 waves in a 2 x 2 grid, each wave
-// 128 x 128 = 4 x 4 tiles of v_mfma_i32_32x32x32_i8 (256 INT32 accumulators per
-// lane, one wave per SIMD).  A stage is one packed 16 KiB tile of A and one of B
+// 128 x 128 = 8 x 8 tiles of v_mfma_i32_16x16x64_i8 (256 INT32 accumulators per
+// lane, one wave per SIMD).  Of the two INT8 MFMA shapes of gfx950 this is the one
+// the chip sustains the higher rate on (register-only loop, slice-like bytes:
+// 4.09 against 3.47 POP/s for 32 x 32 x 32 - the same operations per cycle on paper,
+// half the accumulator traffic per operation; the whole kernel: 10 % faster).
+// A stage is one packed 16 KiB tile of A and one of B
 // (256 rows x 64 inner bytes each, see ozimmu_layout.h).  Stages travel from
 // global memory straight into a ring of NS LDS buffers with
 // global_load_lds_dwordx4 (no VGPR staging; the bank swizzle is already in the
 // packed layout, so the copy is linear), NS - 2 stages ahead of the math.
-// Operand fragments are double buffered in registers and fetched one k-step
-// ahead, across stage boundaries, so LDS latency hides behind the 16 MFMAs of
-// the current k-step.  The inner order of an integer dot product is free, so
-// each lane simply fetches 16 consecutive inner bytes.
+// One MFMA takes the 64 inner bytes of a stage, so a stage is one k-step of 64
+// MFMAs; it runs as four quarters of 4 x 4 tiles on four sets of four operand
+// fragments, each set refilled as soon as its last quarter is over, every fragment
+// 16 MFMAs ahead of its first use, across stage boundaries (see `stage` in k_gemm).
+// The inner order of an integer dot product is free, so each lane simply fetches
+// 16 consecutive inner bytes.
 //
 // Synchronisation per stage `it` (buffer it % NS), one barrier:
-//   k-step 0 math | wait until this thread's copies of stage it+1 landed |
-//   barrier | fetch fragments of stage it+1 | issue copies of stage it+NS-1 into
-//   the buffer of stage it-1 (every wave has finished reading it: its data fed
-//   MFMAs issued before the barrier) | k-step 1 math.
+//   quarters 0, 1 | wait until this thread's copies of stage it+1 landed |
+//   barrier | quarters 2, 3, fetching the first fragments of stage it+1; copies of
+//   stage it+NS-1 go into the buffer of stage it-1 (every wave has finished reading
+//   it: its data fed MFMAs issued before the barrier).
 // The LDS-writing loads are issued from inline assembly, so the compiler does
 // not track them; the vmcnt waits that order them are written out below.
 // The compiler's own memory waits use the same counter: an ordinary load (or
@@ -69,11 +75,10 @@ namespace {
 using namespace ozl;
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // A tile + B tile = 32 KiB
 constexpr int NLOAD = TILE_BYTES / (256 * 16);    // 16-byte copies per thread and operand tile = 4
-constexpr int EPI_ROWS = 2;                       // 32 x 32 tiles per batch of the plain epilogue (16 D loads in flight per lane each)
+constexpr int EPI_ROWS = 8;                       // 16 x 16 tiles per batch of the plain epilogue (4 D loads in flight per lane each)
 // behind the ring in LDS: (exponent, offset correction) of the tile's 256 rows and 256 columns; the work-item ticket
 // (64 bytes); the list of completed tiles that the workgroup still has to add up (queue schedule, 256 bytes)
 constexpr int EXP_BYTES = 2 * 256 * 8 + 64 + 256;
@@ -147,13 +152,13 @@ __device__ inline void static_for(F&& f)
     }
 }
 
-// Layout of a 256 x 256 INT32 block of the queue schedule: "lane-major".  The four accumulators 4q .. 4q + 3 of
-// 32 x 32 tile (i, j) of thread t (wave t / 64 = 2 wm + wn, lane l = t % 64) are the 16 bytes at int index
-// (((i * 4 + j) * 4 + q) * 256 + t) * 4; they belong to rows wm * 128 + i * 32 + 8 q + 4 (l / 32) + 0 .. 3 and
-// column wn * 128 + j * 32 + l % 32 of the block.  A workgroup writes a block with 64 fully coalesced 16-byte
-// stores per thread (256 4-byte stores in row-major order cost 10 us more per work item), and thread t of the
-// workgroup that adds the tile up reads back what a thread t wrote.
-constexpr int QBLOCK_GROUP_BYTES = 256 * 16;  // one (i, j, q) group of all 256 threads
+// Layout of a 256 x 256 INT32 block of the queue schedule: "lane-major".  The four accumulators of 16 x 16 tile
+// (i, j) of thread t (wave t / 64 = 2 wm + wn, lane l = t % 64) are the 16 bytes at int index
+// (G * 256 + t) * 4 with the group number G = ((i / 2) * 8 + j) * 2 + i % 2; they belong to rows
+// wm * 128 + i * 16 + 4 (l / 16) + 0 .. 3 and column wn * 128 + j * 16 + l % 16 of the block.  A workgroup writes
+// a block with 64 fully coalesced 16-byte stores per thread (256 4-byte stores in row-major order cost 10 us more
+// per work item), and thread t of the workgroup that adds the tile up reads back what a thread t wrote.
+constexpr int QBLOCK_GROUP_BYTES = 256 * 16;  // one group (a tile's accumulators of all 256 threads)
 
 // Steps (iv) and (v) for one tile by one workgroup (the queue schedule): the tile's chunk sums lie in `w` lane-major
 // INT32 blocks, `cstride` elements apart, in schedule order; every element gets them added in that order with one
@@ -162,9 +167,8 @@ constexpr int QBLOCK_GROUP_BYTES = 256 * 16;  // one (i, j, q) group of all 256 
 // ahead of their use, so that the loads of a step fly while the previous one is added up (three steps: spills).
 // The loads are buffer loads of agent scope (they see what other XCDs have written through) and streaming (the
 // 2 MiB of a tile must not displace the operand tiles that the XCD's workgroups share in L2: with plain or merely
-// agent-scope loads the whole launch ran 5 % slower); D is stored non-temporally, 256 contiguous bytes per half wave.
-// lds_rows: 256 ints of LDS for the row exponents.
-template <bool S16>
+// agent-scope loads the whole launch ran 5 % slower); D is stored non-temporally, 128 contiguous bytes per 16 lanes.
+// lds_rows: 512 ints of LDS for the row and column exponents.
 __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* blocks, int64_t cstride, int w, int tm,
                                        int tp, int* lds_rows)
 {
@@ -176,21 +180,18 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    // S16: lane = 16 lq + lc holds rows 4 lq .. 4 lq + 3, column lc of a 16 x 16 tile; else lane = 32 lh + lr
-    const int lr = S16 ? (lane & 15) : (lane & 31), lh = S16 ? (lane >> 4) : (lane >> 5);
-    constexpr int CW = S16 ? 16 : 32;  // columns per tile
-    const int64_t col0 = (int64_t)tp * 256 + wn * 128 + lr;  // this lane's column in column tile j: col0 + CW j
+    const int lc = lane & 15, lq = lane >> 4;  // the lane holds rows 4 lq .. 4 lq + 3 of column lc of a 16 x 16 tile
+    const int64_t col0 = (int64_t)tp * 256 + wn * 128 + lc;  // this lane's column in column tile j: col0 + 16 j
     {
         const int64_t gr = (int64_t)tm * 256 + t, gc = (int64_t)tp * 256 + t;
         lds_rows[t] = gr < a.m ? a.eA[gr] : 0;
         lds_rows[256 + t] = gc < a.p ? a.eB[gc] : 0;
     }
     __syncthreads();
-    // step u covers the register groups 2 u, 2 u + 1 of the block: 8 rows of one column per thread
-    auto col_tile = [&](int u) { return S16 ? (u & 7) : ((u >> 1) & 3); };
-    auto row_in_wave = [&](int u, int qq, int ss) {
-        return S16 ? ((2 * (u >> 3) + qq) * 16 + 4 * lh + ss) : ((u >> 3) * 32 + 8 * (2 * (u & 1) + qq) + 4 * lh + ss);
-    };
+    // step u covers the register groups 2 u, 2 u + 1 of the block, tiles (2 (u / 8) + qq, u % 8): 8 rows of one
+    // column per thread
+    auto col_tile = [&](int u) { return u & 7; };
+    auto row_in_wave = [&](int u, int qq, int ss) { return (2 * (u >> 3) + qq) * 16 + 4 * lq + ss; };
     const bool last_c = a.finish && a.cbeta != 0.0;
     double* const obase = a.finish ? a.Cout : a.D;
     const int64_t opitch = a.finish ? a.ldco : a.ldd;
@@ -209,7 +210,7 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
         constexpr int buf = decltype(BUF)::value;
         const int u = s / nbatch, cq = (s - u * nbatch) * 8;  // u = (i * 4 + j) * 2 + half
         if (last_c && s - u * nbatch == nbatch - 1) {
-            const int64_t col = col0 + CW * col_tile(u);
+            const int64_t col = col0 + 16 * col_tile(u);
 #pragma unroll
             for (int qq = 0; qq < 2; ++qq)
 #pragma unroll
@@ -237,7 +238,7 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
             c0 = 1;
             first = true;
         }
-        const int ebj = lds_rows[256 + wn * 128 + CW * col_tile(u) + lr];
+        const int ebj = lds_rows[256 + wn * 128 + 16 * col_tile(u) + lc];
         int ea[2][4];
 #pragma unroll
         for (int qq = 0; qq < 2; ++qq)
@@ -268,7 +269,7 @@ __device__ inline void accumulate_tile(const ozk::GemmArgs& a, const int32_t* bl
         constexpr int buf = decltype(BUF)::value;
         const int u = s / nbatch, bq = s - u * nbatch;
         if (bq != nbatch - 1) return;
-        const int64_t col = col0 + CW * col_tile(u);
+        const int64_t col = col0 + 16 * col_tile(u);
         if (col >= a.p) return;
 #pragma unroll
         for (int qq = 0; qq < 2; ++qq)
@@ -350,19 +351,15 @@ struct Cursor {
 // plus an immediate and every M0 value one scalar add: with one wave per SIMD
 // every instruction that is not an MFMA competes with the MFMAs for the wave's
 // issue slots (one instruction per 4 cycles), so the loop carries as few of them
-// as it can (per stage 32 MFMAs, 16 LDS reads, 8 copies of 3 instructions, two
+// as it can (per stage 64 MFMAs, 16 LDS reads, 8 copies of 3 instructions, two
 // cursor updates, one barrier).
-template <int MODE_, int NS>
+template <int MODE, int NS>
 __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
 {
-    // MODE_ 4: MODE 3 for the queue schedule on v_mfma_i32_16x16x64_i8 (8 x 8 tiles of 16 x 16 per wave)
-    constexpr int MODE = MODE_ == 4 ? 3 : MODE_;
-    constexpr bool S16 = MODE_ == 4;
     extern __shared__ __align__(16) int8_t lds[];
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    const int lr = lane & 31, lh = lane >> 5;
 
     const int KT = a.KT;  // a multiple of NS (inner padding granule KPAD)
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
@@ -375,29 +372,17 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     const int64_t wrapA = a.strideA - (int64_t)KT * TILE_BYTES;
     const int64_t wrapB = -a.strideB - (int64_t)KT * TILE_BYTES;
 
-    // Per-lane fragment addresses: row = w*128 + i*32 + lane%32, logical chunk = kk*2 + lane/32.  i*32 rows
-    // = i*2048 bytes and does not change the swizzle; ring buffer u adds u*32 KiB.  ds_read offsets are 16-bit
-    // immediates, so one base register serves two ring buffers (h = u / 2).
+    // Per-lane fragment addresses: row = w*128 + i*16 + lane%16, logical chunk = lane/16 (one MFMA takes the 64 inner
+    // bytes of a stage).  i*16 rows = i*1024 bytes and does not change the swizzle; ring buffer u adds u*32 KiB.
+    // ds_read offsets are 16-bit immediates, so one base register serves two ring buffers (h = u / 2).
     constexpr int NH = (NS + 1) / 2;
-    uint32_t fragA[2][NH], fragB[2][NH];
-    {
-        const int rowA = wm * 128 + lr, rowB = wn * 128 + lr;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int h = 0; h < NH; ++h) {
-                fragA[kk][h] = lds_base + h * 2 * STAGE_BYTES + rowA * TILE_K + swizzle(rowA, kk * 2 + lh) * CHUNK;
-                fragB[kk][h] = lds_base + h * 2 * STAGE_BYTES + rowB * TILE_K + swizzle(rowB, kk * 2 + lh) * CHUNK;
-            }
-    }
-    // S16: row = w*128 + i*16 + lane%16, logical chunk = lane/16 (a 16 x 16 x 64 MFMA takes the whole stage)
-    uint32_t frag16A[NH], frag16B[NH];
+    uint32_t fragA[NH], fragB[NH];
     {
         const int rowA = wm * 128 + (lane & 15), rowB = wn * 128 + (lane & 15);
 #pragma unroll
         for (int h = 0; h < NH; ++h) {
-            frag16A[h] = lds_base + h * 2 * STAGE_BYTES + rowA * TILE_K + swizzle(rowA, lane >> 4) * CHUNK;
-            frag16B[h] = lds_base + h * 2 * STAGE_BYTES + rowB * TILE_K + swizzle(rowB, lane >> 4) * CHUNK;
+            fragA[h] = lds_base + h * 2 * STAGE_BYTES + rowA * TILE_K + swizzle(rowA, lane >> 4) * CHUNK;
+            fragB[h] = lds_base + h * 2 * STAGE_BYTES + rowB * TILE_K + swizzle(rowB, lane >> 4) * CHUNK;
         }
     }
     typedef __attribute__((address_space(3))) const v4i* lds_v4i_ptr;
@@ -498,7 +483,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     tile_of_queue(a.tile_begin + zt, TM, TP, a.queue_block_rounds != 0, ptm, ptp);
                     const int first_block = __builtin_amdgcn_readfirstlane(
                         (qr % a.queue_sets) * a.nchunks * a.queue_stride + (zt - qr * ozk::QUEUE_ROUND_TILES));
-                    accumulate_tile<S16>(a, a.C + (int64_t)first_block * (256 * 256), (int64_t)a.queue_stride * (256 * 256),
+                    accumulate_tile(a, a.C + (int64_t)first_block * (256 * 256), (int64_t)a.queue_stride * (256 * 256),
                                     a.nchunks, ptm, ptp, reinterpret_cast<int*>(lds + NS * STAGE_BYTES));
                     __syncthreads();  // every thread has used what it loaded from the blocks
                     if (t == 0) {
@@ -644,28 +629,18 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     c.groups_left = wr ? KT / NS : c.groups_left;
                 };
 
-                v16i acc[4][4];
-                // the 4 MFMAs of A row tile i for one k-step
-                auto math_row = [&](const v4i* fa, const v4i* fb, int i) {
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        const int j = (i & 1) ? 3 - jj : jj;  // boustrophedon: one operand stays put between MFMAs
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
-                    }
-                };
-                v4i fa0[4], fb0[4], fa1[4], fb1[4];
-                // S16: 8 x 8 tiles of 16 x 16; A fragments of row tiles 0..3 / 4..7 in faL / faH, B likewise
-                v4i acc16[8][8];
+                // 8 x 8 tiles of 16 x 16 per wave; A fragments of row tiles 0..3 / 4..7 in faL / faH, B likewise
+                v4i acc[8][8];
                 v4i faL[4], faH[4], fbL[4], fbH[4];
                 // sub-step ss of a quarter: row tile ss against the four column tiles (by_col: column tile ss against
                 // the four row tiles) - the operand that has just been fetched is the one taken one fragment per sub-step
-                auto math16 = [&](const v4i* fa, const v4i* fb, int i0, int j0, int ss, bool by_col) {
+                auto math = [&](const v4i* fa, const v4i* fb, int i0, int j0, int ss, bool by_col) {
 #pragma unroll
                     for (int x = 0; x < 4; ++x) {
                         const int y = (ss & 1) ? 3 - x : x;
                         const int ii = by_col ? y : ss, jj = by_col ? ss : y;
-                        acc16[i0 + ii][j0 + jj] =
-                            __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[ii], fb[jj], acc16[i0 + ii][j0 + jj], 0, 0, 0);
+                        acc[i0 + ii][j0 + jj] =
+                            __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[ii], fb[jj], acc[i0 + ii][j0 + jj], 0, 0, 0);
                     }
                 };
 
@@ -728,27 +703,22 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 wait_vmcnt<NLOAD*(2 * (NS - 2) - 1)>();
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-                if constexpr (S16) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        faL[i] = *(lds_v4i_ptr)(uintptr_t)(frag16A[0] + i * 1024);
-                        fbL[i] = *(lds_v4i_ptr)(uintptr_t)(frag16B[0] + TILE_BYTES + i * 1024);
-                    }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        fa0[i] = *(lds_v4i_ptr)(uintptr_t)(fragA[0][0] + i * 2048);
-                        fb0[i] = *(lds_v4i_ptr)(uintptr_t)(fragB[0][0] + TILE_BYTES + i * 2048);
-                    }
+                for (int i = 0; i < 4; ++i) {
+                    faL[i] = *(lds_v4i_ptr)(uintptr_t)(fragA[0] + i * 1024);
+                    fbL[i] = *(lds_v4i_ptr)(uintptr_t)(fragB[0] + TILE_BYTES + i * 1024);
                 }
                 // accumulators start at -(ra[row] + cb[column]) (see the head of this file); of a chunk that is cut
                 // into parts (MODE 3) only part 0 carries the start value, the others start at zero
-                if constexpr (S16) {
+                {
+                    // lane parts of the LDS addresses made opaque here: otherwise the addresses are formed at kernel
+                    // entry, live through everything and get spilled
                     int lqi = lane >> 4, lci = lane & 15;
                     asm volatile("" : "+v"(lqi), "+v"(lci));
                     int ncb[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j) ncb[j] = lds_corr[256 + wn * 128 + j * 16 + lci];
+                    const bool carries = (MODE != 3) || zpart == 0;
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         int nra[4];
@@ -757,29 +727,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
 #pragma unroll
-                            for (int r = 0; r < 4; ++r) acc16[i][j][r] = (int)((uint32_t)nra[r] + (uint32_t)ncb[j]);
-                            asm volatile("" : "+a"(acc16[i][j]));
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                    }
-                } else {
-                    // lane parts of the LDS addresses made opaque here: otherwise the sixteen addresses are formed
-                    // at kernel entry, live through everything and get spilled
-                    int lhi = lh, lri = lr;
-                    asm volatile("" : "+v"(lhi), "+v"(lri));
-                    int ncb[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) ncb[j] = lds_corr[256 + wn * 128 + j * 32 + lri];
-                    const bool carries = (MODE != 3) || zpart == 0;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        int nra[16];
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) nra[r] = lds_corr[wm * 128 + i * 32 + 8 * (r / 4) + (r % 4) + 4 * lhi];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) acc[i][j][r] = carries ? (int)((uint32_t)nra[r] + (uint32_t)ncb[j]) : 0;
+                            for (int r = 0; r < 4; ++r) acc[i][j][r] = carries ? (int)((uint32_t)nra[r] + (uint32_t)ncb[j]) : 0;
                             // the tile goes to its accumulation registers now, not when the first MFMA asks for it
                             // (256 start values waiting in ordinary registers would not fit)
                             asm volatile("" : "+a"(acc[i][j]));
@@ -788,74 +736,18 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     }
                 }
 
-                // One stage whose ring buffer index U is a compile-time constant.  32 MFMAs, 16 fragment
-                // fetches and 8 copies, interleaved as (2 fetches, 4 MFMAs, 1 copy).  The stage copied in
-                // position u is NS-1 (A half) or NS-2 (B half) ahead, so a cursor reaches the end of a slice
-                // in one fixed position of the unrolled group: A in position 0, B in position 1.  In the last
-                // group of a chunk (TAIL) the copies that would run past the chunk are left out.
+                // One stage whose ring buffer index U is a compile-time constant: one k-step of 64 MFMAs (a
+                // 16 x 16 x 64 MFMA takes the 64 inner bytes of a stage at once), run as four quarters of 4 x 4 tiles.
+                // Stages in even position: (A lo, B lo), (A lo, B hi), (A hi, B hi), (A hi, B lo); odd: (A lo, B hi),
+                // (A lo, B lo), (A hi, B lo), (A hi, B hi) - every quarter shares one fragment set with the one
+                // before, and the set that has just come free takes the fragments needed two quarters later (after
+                // the barrier in mid-stage: those of the next stage).  A quarter takes the set that was fetched last
+                // one fragment per sub-step (by columns when that is a B set), so that every fragment is fetched four
+                // sub-steps = 16 MFMAs ahead of its first use.  Per sub-step 1 fetch, 4 MFMAs and, every other time,
+                // 1 copy.  The stage copied in position u is NS-1 (A half) or NS-2 (B half) ahead, so a cursor reaches
+                // the end of a slice in one fixed position of the unrolled group: A in position 0, B in position 1.
+                // In the last group of a chunk (TAIL) the copies that would run past the chunk are left out.
                 auto stage = [&](auto U, auto TAIL) {
-                    constexpr int u = decltype(U)::value;          // ring buffer of this stage
-                    constexpr bool tail = decltype(TAIL)::value;
-                    constexpr int un = (u + 1) % NS;               // ... of the next stage
-                    constexpr int up = (u + NS - 1) % NS;          // ... of the previous stage (free: refill with stage it+NS-1)
-                    constexpr int ub = (u + NS - 2) % NS;          // ... of stage it+NS-2 (its B half goes in now)
-                    constexpr bool copy_b = !tail || u < 2;        // stage it+NS-2 still inside the chunk
-                    constexpr bool copy_a = !tail || u < 1;        // stage it+NS-1 still inside the chunk
-                    constexpr bool fetch_next = !tail || u < NS - 1;
-                    // k-step 0 of this stage; fragments of k-step 1 on their way; B half of stage it+NS-2
-                    static_for<0, 4>([&](auto Q) {
-                        constexpr int q = decltype(Q)::value;
-                        // B fragments first (every MFMA row of the next k-step needs all four), then A
-                        if constexpr (q < 2) {
-                            fb1[2 * q] = *(lds_v4i_ptr)(uintptr_t)(fragB[1][u / 2] + (u % 2) * STAGE_BYTES + TILE_BYTES + (2 * q) * 2048);
-                            fb1[2 * q + 1] = *(lds_v4i_ptr)(uintptr_t)(fragB[1][u / 2] + (u % 2) * STAGE_BYTES + TILE_BYTES + (2 * q + 1) * 2048);
-                        } else {
-                            fa1[2 * q - 4] = *(lds_v4i_ptr)(uintptr_t)(fragA[1][u / 2] + (u % 2) * STAGE_BYTES + (2 * q - 4) * 2048);
-                            fa1[2 * q - 3] = *(lds_v4i_ptr)(uintptr_t)(fragA[1][u / 2] + (u % 2) * STAGE_BYTES + (2 * q - 3) * 2048);
-                        }
-                        math_row(fa0, fb0, q);
-                        if constexpr (copy_b)
-                            copy16_to_lds<ub * STAGE_BYTES + TILE_BYTES + q * 4096>(m0_wave, voff[q], cb.ptr);
-                        __builtin_amdgcn_sched_barrier(0);  // keep the (fetch, math, copy) order as written
-                    });
-                    if constexpr (copy_b) {
-                        cb.ptr += TILE_BYTES;
-                        if constexpr (u == 1 && !tail) wrap_check(cb, wrapB);
-                    }
-                    // stage it+1 complete in LDS for every wave; every wave done reading stage it-1
-                    if constexpr (tail && u >= 2)
-                        wait_vmcnt<0>();
-                    else
-                        wait_vmcnt<2 * NLOAD * (NS - 3)>();
-                    __builtin_amdgcn_s_barrier();
-                    asm volatile("" ::: "memory");
-                    // k-step 1 of this stage; first fragments of stage it+1 on their way; A half of stage it+NS-1
-                    static_for<0, 4>([&](auto Q) {
-                        constexpr int q = decltype(Q)::value;
-                        if constexpr (fetch_next) {
-                            if constexpr (q < 2) {
-                                fb0[2 * q] = *(lds_v4i_ptr)(uintptr_t)(fragB[0][un / 2] + (un % 2) * STAGE_BYTES + TILE_BYTES + (2 * q) * 2048);
-                                fb0[2 * q + 1] = *(lds_v4i_ptr)(uintptr_t)(fragB[0][un / 2] + (un % 2) * STAGE_BYTES + TILE_BYTES + (2 * q + 1) * 2048);
-                            } else {
-                                fa0[2 * q - 4] = *(lds_v4i_ptr)(uintptr_t)(fragA[0][un / 2] + (un % 2) * STAGE_BYTES + (2 * q - 4) * 2048);
-                                fa0[2 * q - 3] = *(lds_v4i_ptr)(uintptr_t)(fragA[0][un / 2] + (un % 2) * STAGE_BYTES + (2 * q - 3) * 2048);
-                            }
-                        }
-                        math_row(fa1, fb1, q);
-                        if constexpr (copy_a) copy16_to_lds<up * STAGE_BYTES + q * 4096>(m0_wave, voff[q], ca.ptr);
-                        __builtin_amdgcn_sched_barrier(0);
-                    });
-                    if constexpr (copy_a) {
-                        ca.ptr += TILE_BYTES;
-                        if constexpr (u == 0 && !tail) wrap_check(ca, wrapA);
-                    }
-                };
-                // The same for 16 x 16 x 64 MFMAs (S16): the stage is one k-step of 64 MFMAs, run as four quarters of
-                // 4 x 4 tiles.  Stages of even position: (A lo, B lo), (A lo, B hi), (A hi, B hi), (A hi, B lo); odd:
-                // (A lo, B hi), (A lo, B lo), (A hi, B lo), (A hi, B hi) - every quarter shares one fragment set with the
-                // one before, and the set that has just come free takes the fragments needed two quarters later
-                // (after the barrier in mid-stage: those of the next stage).  Per quarter 4 fetches, 16 MFMAs, 2 copies.
-                auto stage16 = [&](auto U, auto TAIL) {
                     constexpr int u = decltype(U)::value;
                     constexpr bool tail = decltype(TAIL)::value;
                     constexpr bool odd = (u % 2) != 0;
@@ -869,11 +761,11 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     static_for<0, 4>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
                         if constexpr (!odd) {
-                            fbH[q] = *(lds_v4i_ptr)(uintptr_t)(frag16B[u / 2] + curB + (4 + q) * 1024);
-                            math16(faL, fbL, 0, 0, q, true);
+                            fbH[q] = *(lds_v4i_ptr)(uintptr_t)(fragB[u / 2] + curB + (4 + q) * 1024);
+                            math(faL, fbL, 0, 0, q, true);
                         } else {
-                            fbL[q] = *(lds_v4i_ptr)(uintptr_t)(frag16B[u / 2] + curB + q * 1024);
-                            math16(faL, fbH, 0, 4, q, true);
+                            fbL[q] = *(lds_v4i_ptr)(uintptr_t)(fragB[u / 2] + curB + q * 1024);
+                            math(faL, fbH, 0, 4, q, true);
                         }
                         if constexpr (copy_b && q % 2 == 0)
                             copy16_to_lds<ub * STAGE_BYTES + TILE_BYTES + (q / 2) * 4096>(m0_wave, voff[q / 2], cb.ptr);
@@ -882,11 +774,11 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     // quarter 1: A fragments of the upper half of this stage
                     static_for<0, 4>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
-                        faH[q] = *(lds_v4i_ptr)(uintptr_t)(frag16A[u / 2] + curA + (4 + q) * 1024);
+                        faH[q] = *(lds_v4i_ptr)(uintptr_t)(fragA[u / 2] + curA + (4 + q) * 1024);
                         if constexpr (!odd)
-                            math16(faL, fbH, 0, 4, q, true);
+                            math(faL, fbH, 0, 4, q, true);
                         else
-                            math16(faL, fbL, 0, 0, q, true);
+                            math(faL, fbL, 0, 0, q, true);
                         if constexpr (copy_b && q % 2 == 0)
                             copy16_to_lds<ub * STAGE_BYTES + TILE_BYTES + (2 + q / 2) * 4096>(m0_wave, voff[2 + q / 2], cb.ptr);
                         __builtin_amdgcn_sched_barrier(0);
@@ -904,24 +796,24 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     // quarter 2: first A fragments of the next stage
                     static_for<0, 4>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
-                        if constexpr (fetch_next) faL[q] = *(lds_v4i_ptr)(uintptr_t)(frag16A[un / 2] + nxtA + q * 1024);
+                        if constexpr (fetch_next) faL[q] = *(lds_v4i_ptr)(uintptr_t)(fragA[un / 2] + nxtA + q * 1024);
                         if constexpr (!odd)
-                            math16(faH, fbH, 4, 4, q, false);
+                            math(faH, fbH, 4, 4, q, false);
                         else
-                            math16(faH, fbL, 4, 0, q, false);
+                            math(faH, fbL, 4, 0, q, false);
                         if constexpr (copy_a && q % 2 == 0)
                             copy16_to_lds<up * STAGE_BYTES + (q / 2) * 4096>(m0_wave, voff[q / 2], ca.ptr);
                         __builtin_amdgcn_sched_barrier(0);
                     });
-                    // quarter 3: first B fragments of the next stage (it starts with the half this stage ends on... the other one)
+                    // quarter 3: the B fragments the next stage starts with
                     static_for<0, 4>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
                         if constexpr (!odd) {
-                            if constexpr (fetch_next) fbH[q] = *(lds_v4i_ptr)(uintptr_t)(frag16B[un / 2] + nxtB + (4 + q) * 1024);
-                            math16(faH, fbL, 4, 0, q, false);
+                            if constexpr (fetch_next) fbH[q] = *(lds_v4i_ptr)(uintptr_t)(fragB[un / 2] + nxtB + (4 + q) * 1024);
+                            math(faH, fbL, 4, 0, q, false);
                         } else {
-                            if constexpr (fetch_next) fbL[q] = *(lds_v4i_ptr)(uintptr_t)(frag16B[un / 2] + nxtB + q * 1024);
-                            math16(faH, fbH, 4, 4, q, false);
+                            if constexpr (fetch_next) fbL[q] = *(lds_v4i_ptr)(uintptr_t)(fragB[un / 2] + nxtB + q * 1024);
+                            math(faH, fbH, 4, 4, q, false);
                         }
                         if constexpr (copy_a && q % 2 == 0)
                             copy16_to_lds<up * STAGE_BYTES + (2 + q / 2) * 4096>(m0_wave, voff[2 + q / 2], ca.ptr);
@@ -933,94 +825,62 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     }
                 };
                 static_assert(NS == 4, "the tail logic below is written for a ring of 4 stages");
-                if constexpr (S16) {
-                    for (int it = 0; it < nstage - NS; it += NS)
-                        static_for<0, NS>([&](auto U) { stage16(U, std::false_type{}); });
-                    static_for<0, NS>([&](auto U) { stage16(U, std::true_type{}); });
-                } else {
-                    for (int it = 0; it < nstage - NS; it += NS)
-                        static_for<0, NS>([&](auto U) { stage(U, std::false_type{}); });
-                    static_for<0, NS>([&](auto U) { stage(U, std::true_type{}); });
-                }
+                for (int it = 0; it < nstage - NS; it += NS)
+                    static_for<0, NS>([&](auto U) { stage(U, std::false_type{}); });
+                static_for<0, NS>([&](auto U) { stage(U, std::true_type{}); });
                 wait_vmcnt<0>();  // no copy may still be writing LDS when the ring is reused or the workgroup retires
 
-                // Epilogue.  Accumulator register r of tile (i, j) in lane l holds output
-                // row 8*(r/4) + 4*(l/32) + r%4 and column l%32 of that 32 x 32 tile.  Addresses are a
-                // wave-uniform base plus a 32-bit lane offset, rebuilt for every chunk (the empty asm
-                // keeps the compiler from hoisting 64 element addresses per lane out of the chunk loops).
+                // Epilogue.  Accumulator register r of tile (i, j) in lane l holds output row 4*(l/16) + r and
+                // column l%16 of that 16 x 16 tile.  Addresses are a wave-uniform base plus a 32-bit lane offset,
+                // rebuilt for every chunk (the empty asm keeps the compiler from hoisting 64 element addresses per
+                // lane out of the chunk loops).
                 const int shift = MODE == 2 ? 2 - 2 * a.beta : 2 - a.beta * g;
                 int64_t er0 = row0, ec0 = col0;
                 asm volatile("" : "+s"(er0), "+s"(ec0));
-                // lane parts of the output coordinates, opaque to the optimiser so that the 64 per-lane row
-                // indices of a chunk are formed here and not at kernel entry (where they would be spilled)
-                int lhe = lh, lre = lr;
-                asm volatile("" : "+v"(lhe), "+v"(lre));
-                const bool lane_col_ok[4] = {ec0 + lre < a.p, ec0 + 32 + lre < a.p, ec0 + 64 + lre < a.p,
-                                             ec0 + 96 + lre < a.p};
-                // exponent + shift of this lane's column in each of the 4 column tiles
-                int eb[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) eb[j] = lds_exp[256 + wn * 128 + j * 32 + lre] + shift;
-                if constexpr (S16) {
-                    // the whole block, lane-major: group ((i / 2) * 8 + j) * 2 + i % 2 is tile (i, j) (see accumulate_tile)
+                // lane parts of the output coordinates, opaque to the optimiser so that the per-lane row indices of
+                // a chunk are formed here and not at kernel entry (where they would be spilled)
+                int lqe = lane >> 4, lce = lane & 15;
+                asm volatile("" : "+v"(lqe), "+v"(lce));
+                if (MODE == 3 && queued) {
+                    // the whole block, lane-major (see accumulate_tile), written through: another XCD's workgroup
+                    // may add the tile up.  No bounds: rows and columns past the edge of D exist in the block.
                     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
                         a.C + (int64_t)__builtin_amdgcn_readfirstlane((int)block_no) * (256 * 256), 0, 256 * 256 * 4, 0x00020000);
-                    int voff = lhe * 512 + lre * 16 + wave * 1024;
+                    int voff = lqe * 256 + lce * 16 + wave * 1024;  // 16 t, from the lane parts made opaque above
                     asm volatile("" : "+v"(voff));
 #pragma unroll
                     for (int i = 0; i < 8; ++i)
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
                             typedef int v4si __attribute__((ext_vector_type(4)));
-                            int x0 = acc16[i][j][0], x1 = acc16[i][j][1], x2 = acc16[i][j][2], x3 = acc16[i][j][3];
+                            // (through ordinary registers, said explicitly: asked to store the accumulation registers
+                            // directly, the register allocator spills whole tiles; and one group at a time: left
+                            // alone, the scheduler copies all 256 accumulators first)
+                            int x0 = acc[i][j][0], x1 = acc[i][j][1], x2 = acc[i][j][2], x3 = acc[i][j][3];
                             asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3));
                             const v4si val = {x0, x1, x2, x3};
                             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int, val),
                                                                    rsrc, voff, (((i >> 1) * 8 + j) * 2 + (i & 1)) * QBLOCK_GROUP_BYTES, 1 << 4);
                             __builtin_amdgcn_sched_barrier(0);
                         }
-                } else if (MODE == 3 && queued) {
-                    // the whole block, lane-major (see accumulate_tile), written through: another XCD's workgroup
-                    // may add the tile up.  No bounds: rows and columns past the edge of D exist in the block.
-                    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-                        a.C + (int64_t)__builtin_amdgcn_readfirstlane((int)block_no) * (256 * 256), 0, 256 * 256 * 4, 0x00020000);
-                    int voff = lhe * 512 + lre * 16 + wave * 1024;  // 16 t, from the lane parts made opaque above
-                    asm volatile("" : "+v"(voff));
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-#pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                typedef int v4si __attribute__((ext_vector_type(4)));
-                                // (through ordinary registers, said explicitly: asked to store sub-tuples of the
-                                // accumulation registers directly, the register allocator spills whole tiles; and
-                                // one group at a time: left alone, the scheduler copies all 256 accumulators first)
-                                int x0 = acc[i][j][4 * q], x1 = acc[i][j][4 * q + 1], x2 = acc[i][j][4 * q + 2],
-                                    x3 = acc[i][j][4 * q + 3];
-                                asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3));
-                                const v4si val = {x0, x1, x2, x3};
-                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int, val),
-                                                                       rsrc, voff, ((i * 4 + j) * 4 + q) * QBLOCK_GROUP_BYTES, 1 << 4);
-                                __builtin_amdgcn_sched_barrier(0);
-                            }
                 } else if (MODE == 0 || MODE == 3) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
+                    for (int j = 0; j < 8; ++j) {
+                        const bool col_ok = ec0 + 16 * j + lce < a.p;
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
+                        for (int i = 0; i < 8; ++i)
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const int rt = i * 32 + 8 * (r / 4) + (r % 4);           // uniform part of the row in the wave's block
+                            for (int r = 0; r < 4; ++r) {
+                                const int rt = i * 16 + r;  // uniform part of the row in the wave's block
                                 const int64_t urow = er0 + rt;
                                 // MODE 3: the tile's own dense 256 x 256 block, addressed by the row / column in the tile
                                 int32_t* base = (MODE == 3)
                                                     ? a.C + ((int64_t)chunk_no * a.tile_count + ztile) * (256 * 256) +
-                                                          (int64_t)(wm * 128 + rt) * 256 + wn * 128 + j * 32
-                                                    : a.C + urow * a.ldc + ec0 + j * 32;
+                                                          (int64_t)(wm * 128 + rt) * 256 + wn * 128 + j * 16
+                                                    : a.C + urow * a.ldc + ec0 + j * 16;
                                 const uint32_t off =
-                                    (uint32_t)(4 * lhe) * ((MODE == 3) ? 256u : (uint32_t)a.ldc) + (uint32_t)lre;
-                                if (lane_col_ok[j] && urow + 4 * lhe < a.m) {
+                                    (uint32_t)(4 * lqe) * ((MODE == 3) ? 256u : (uint32_t)a.ldc) + (uint32_t)lce;
+                                if (col_ok && urow + 4 * lqe < a.m) {
                                     if (MODE == 3 && Z > 1)  // partial sum of one part: integer adds commute, C'' starts at zero
                                         __hip_atomic_fetch_add(&base[off], acc[i][j][r], __ATOMIC_RELAXED,
                                                                __HIP_MEMORY_SCOPE_AGENT);
@@ -1028,6 +888,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                         base[off] = acc[i][j][r];
                                 }
                             }
+                    }
                 } else {
                     // Exponents come from LDS (the compiler cannot prove that D does not alias eA / eB and would
                     // order global exponent loads behind every store).  D is
@@ -1038,17 +899,20 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     const bool with_c = last && a.cbeta != 0.0;
                     // the FP64 addend of this chunk for accumulator (i, j, r)
                     auto addend = [&](int i, int j, int r) -> double {
-                        const int ea = lds_exp[wm * 128 + i * 32 + 8 * (r / 4) + (r % 4) + 4 * lhe];
-                        return ldexp((double)acc[i][j][r], ea + eb[j]);
+                        const int ea = lds_exp[wm * 128 + i * 16 + 4 * lqe + r];
+                        const int eb = lds_exp[256 + wn * 128 + j * 16 + lce];
+                        return ldexp((double)acc[i][j][r], ea + eb + shift);
                     };
-                    const uint32_t off = (uint32_t)(4 * lhe) * (uint32_t)a.ldd + (uint32_t)lre;
+                    const uint32_t off = (uint32_t)(4 * lqe) * (uint32_t)a.ldd + (uint32_t)lce;
                     // Later chunks of a tile that lies wholly inside D (and D aligned for 16-byte copies): the old
                     // values of D come in through the LDS ring, which is idle now, with the same global -> LDS
                     // copies as the operands.  They need no registers, so the next half block (64 rows x 32
                     // columns of this wave) is already on its way while the current one is added and stored, and
                     // no load ever waits for a store to be acknowledged.  Wave w owns ring buffer w (32 KiB = two
-                    // half blocks).  Copy t of a half block brings rows 4t .. 4t+3: lane l row l / 16, columns
-                    // 2 (l % 16), + 1, i.e. the half block lands row-major with 256 bytes per row.
+                    // half blocks).  Copy t of a half block brings rows 4t .. 4t+3 into 1 KiB: lane l row l / 16,
+                    // columns 2 c, 2 c + 1 with c = l % 16 for even t and (l % 16) ^ 8 for odd t.  The swap of the two
+                    // 16-column halves in every other copy keeps the reads below off each other's banks: lanes
+                    // 0 .. 15 read 128 bytes of one row, lanes 16 .. 31 the same columns four rows (one copy) on.
                     const bool staged = !first && !with_c && a.dma_ok && (int64_t)tm * 256 + 256 <= a.m &&
                                         (int64_t)tp * 256 + 256 <= a.p;
                     if (staged) {
@@ -1058,8 +922,12 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                         // kernel entry and held in registers through the main loop)
                         uint32_t ln = (uint32_t)lane;
                         asm volatile("" : "+v"(ln));
-                        const uint32_t dvoff = ((ln >> 4) * (uint32_t)a.ldd + (ln & 15u) * 2u) * 8u;
-                        const uint32_t rd_lane = region + (ln >> 5) * 1024u + (ln & 31u) * 8u;
+                        const uint32_t dvoff[2] = {((ln >> 4) * (uint32_t)a.ldd + (ln & 15u) * 2u) * 8u,
+                                                   ((ln >> 4) * (uint32_t)a.ldd + ((ln & 15u) ^ 8u) * 2u) * 8u};
+                        // this lane's element of column tile jj (0, 1) of the half block, row 4 (ln / 16) of row tile 0
+                        const uint32_t lq1 = (ln >> 4) & 1u, lc = ln & 15u;
+                        const uint32_t rd_lane[2] = {region + (ln >> 4) * 1024u + (lq1 * 8u + (lc >> 1)) * 16u + (lc & 1u) * 8u,
+                                                     region + (ln >> 4) * 1024u + ((lq1 ^ 1u) * 8u + (lc >> 1)) * 16u + (lc & 1u) * 8u};
                         const int64_t row_step = 4 * a.ldd;  // elements between the rows of consecutive copies
                         auto issue = [&](auto HB) {          // half block hb = 2 j + h into buffer hb % 2
                             constexpr int hb = decltype(HB)::value, j = hb / 2, h = hb % 2;
@@ -1067,7 +935,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                             static_for<0, 16>([&](auto TT) {
                                 constexpr int tt = decltype(TT)::value;
                                 asm volatile("" : "+s"(gp));  // one running pointer, not sixteen precomputed ones
-                                copy16_to_lds_nt<(hb % 2) * 16384 + tt * 1024>(region, dvoff, gp);
+                                copy16_to_lds_nt<(hb % 2) * 16384 + tt * 1024>(region, dvoff[tt % 2], gp);
                                 gp += row_step;
                             });
                         };
@@ -1086,18 +954,27 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                                 wait_vmcnt<48>();
                             asm volatile("" ::: "memory");
 #pragma unroll
-                            for (int i = 0; i < 2; ++i) {
-                                double old[16];
+                            for (int ip = 0; ip < 2; ++ip) {  // two row tiles at a time: 16 values per lane
+                                double old[2][2][4];
 #pragma unroll
-                                for (int r = 0; r < 16; ++r)
-                                    old[r] = *(lds_f64_ptr)(uintptr_t)(rd_lane + (hb % 2) * 16384 +
-                                                                       (i * 32 + 8 * (r / 4) + (r % 4)) * 256);
+                                for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-                                for (int r = 0; r < 16; ++r) {
-                                    const int64_t urow = er0 + (2 * h + i) * 32 + 8 * (r / 4) + (r % 4);
-                                    double* base = a.D + urow * a.ldd + ec0 + j * 32;
-                                    __builtin_nontemporal_store(alpha * (old[r] + addend(2 * h + i, j, r)), &base[off]);
-                                }
+                                    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                                        for (int r = 0; r < 4; ++r)
+                                            old[ii][jj][r] = *(lds_f64_ptr)(uintptr_t)(rd_lane[jj] + (hb % 2) * 16384 +
+                                                                                       (2 * ip + ii) * 4096 + r * 256);
+#pragma unroll
+                                for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                                    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                                        for (int r = 0; r < 4; ++r) {
+                                            const int i = 4 * h + 2 * ip + ii, jt = 2 * j + jj;
+                                            const int64_t urow = er0 + i * 16 + r;
+                                            double* base = a.D + urow * a.ldd + ec0 + jt * 16;
+                                            __builtin_nontemporal_store(alpha * (old[ii][jj][r] + addend(i, jt, r)), &base[off]);
+                                        }
                                 __builtin_amdgcn_sched_barrier(0);
                             }
                             // the buffer is read out (the sums above needed every value): refill it
@@ -1107,54 +984,55 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                         });
                     } else {
                         // Edge tiles, first chunks, unaligned D, and the last chunk when it also reads the old C:
-                        // per column of 32 x 32 tiles and per batch of ROWS row tiles, 16 ROWS loads of D (and of C)
+                        // per column of 16 x 16 tiles and per batch of ROWS row tiles, 4 ROWS loads of D (and of C)
                         // in flight, then the adds and stores.
                         auto plain = [&](auto ROWS, auto WITH_C, auto LAST) {
                             constexpr int rows = decltype(ROWS)::value;
                             constexpr bool wc = decltype(WITH_C)::value;
                             constexpr bool fin = decltype(LAST)::value;
-                            const uint32_t offc = (uint32_t)(4 * lhe) * (uint32_t)a.ldco + (uint32_t)lre;
+                            const uint32_t offc = (uint32_t)(4 * lqe) * (uint32_t)a.ldco + (uint32_t)lce;
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) {
+                            for (int j = 0; j < 8; ++j) {
+                                const bool col_ok = ec0 + 16 * j + lce < a.p;
 #pragma unroll
-                                for (int ih = 0; ih < 4; ih += rows) {
-                                    double old[rows][16], cold[wc ? rows : 1][16];
+                                for (int ih = 0; ih < 8; ih += rows) {
+                                    double old[rows][4], cold[wc ? rows : 1][4];
                                     if (!first) {
 #pragma unroll
                                         for (int i = 0; i < rows; ++i)
 #pragma unroll
-                                            for (int r = 0; r < 16; ++r) {
-                                                const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
-                                                const double* base = a.D + urow * a.ldd + ec0 + j * 32;
-                                                old[i][r] = (lane_col_ok[j] && urow + 4 * lhe < a.m) ? __builtin_nontemporal_load(&base[off]) : 0.0;
+                                            for (int r = 0; r < 4; ++r) {
+                                                const int64_t urow = er0 + (ih + i) * 16 + r;
+                                                const double* base = a.D + urow * a.ldd + ec0 + j * 16;
+                                                old[i][r] = (col_ok && urow + 4 * lqe < a.m) ? __builtin_nontemporal_load(&base[off]) : 0.0;
                                             }
                                     }
                                     if constexpr (wc) {
 #pragma unroll
                                         for (int i = 0; i < rows; ++i)
 #pragma unroll
-                                            for (int r = 0; r < 16; ++r) {
-                                                const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
-                                                const double* cbase = a.Cout + urow * a.ldco + ec0 + j * 32;
-                                                cold[i][r] = (lane_col_ok[j] && urow + 4 * lhe < a.m) ? __builtin_nontemporal_load(&cbase[offc]) : 0.0;
+                                            for (int r = 0; r < 4; ++r) {
+                                                const int64_t urow = er0 + (ih + i) * 16 + r;
+                                                const double* cbase = a.Cout + urow * a.ldco + ec0 + j * 16;
+                                                cold[i][r] = (col_ok && urow + 4 * lqe < a.m) ? __builtin_nontemporal_load(&cbase[offc]) : 0.0;
                                             }
                                     }
                                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                                     for (int i = 0; i < rows; ++i) {
 #pragma unroll
-                                        for (int r = 0; r < 16; ++r) {
-                                            const int64_t urow = er0 + (ih + i) * 32 + 8 * (r / 4) + (r % 4);
+                                        for (int r = 0; r < 4; ++r) {
+                                            const int64_t urow = er0 + (ih + i) * 16 + r;
                                             const double term = addend(ih + i, j, r);
                                             double val = first ? term : (old[i][r] + term);
                                             if constexpr (fin) {
                                                 val = a.alpha * val;                                   // t1 = fl(alpha d)
                                                 if constexpr (wc) val = val + a.cbeta * cold[i][r];    // fl(t1 + fl(cbeta c))
-                                                double* cbase = a.Cout + urow * a.ldco + ec0 + j * 32;
-                                                if (lane_col_ok[j] && urow + 4 * lhe < a.m) __builtin_nontemporal_store(val, &cbase[offc]);
+                                                double* cbase = a.Cout + urow * a.ldco + ec0 + j * 16;
+                                                if (col_ok && urow + 4 * lqe < a.m) __builtin_nontemporal_store(val, &cbase[offc]);
                                             } else {
-                                                double* base = a.D + urow * a.ldd + ec0 + j * 32;
-                                                if (lane_col_ok[j] && urow + 4 * lhe < a.m) __builtin_nontemporal_store(val, &base[off]);
+                                                double* base = a.D + urow * a.ldd + ec0 + j * 16;
+                                                if (col_ok && urow + 4 * lqe < a.m) __builtin_nontemporal_store(val, &base[off]);
                                             }
                                         }
                                     }
@@ -1163,7 +1041,7 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                             }
                         };
                         if (with_c)
-                            plain(std::integral_constant<int, 1>{}, std::true_type{}, std::true_type{});
+                            plain(std::integral_constant<int, EPI_ROWS / 2>{}, std::true_type{}, std::true_type{});
                         else if (last)
                             plain(std::integral_constant<int, EPI_ROWS>{}, std::false_type{}, std::true_type{});
                         else
@@ -1346,9 +1224,7 @@ hipError_t launch_gemm(const GemmArgs& a_in, int fused, hipStream_t st)
     if (a.sync_epoch == 0 && !a.sync_zeroed)
         hipLaunchKernelGGL(k_fill_u32_gemm, dim3(1), dim3(SYNC_WORDS), 0, st, a.sync);
     dim3 grid((unsigned)nwg), block(256);
-    if (fused == 3 && a.nchunks > 0 && a.queue_sets > 0)
-        hipLaunchKernelGGL((k_gemm<4, NSTAGES>), grid, block, smem, st, a, TM, TP);
-    else if (fused == 3)
+    if (fused == 3)
         hipLaunchKernelGGL((k_gemm<3, NSTAGES>), grid, block, smem, st, a, TM, TP);
     else if (fused == 2)
         hipLaunchKernelGGL((k_gemm<2, NSTAGES>), grid, block, smem, st, a, TM, TP);
@@ -1370,9 +1246,6 @@ hipError_t setup_gemm_kernels()
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2, NSTAGES>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<4, NSTAGES>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<3, NSTAGES>),

@@ -31,17 +31,18 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def mfma_rate_probe(iters: int, value_lo: int, value_hi: int, reps: int = 2) -> float:
-    """Sustained v_mfma_i32_32x32x32_i8 rate of this chip in TOP/s for register operands uniform in
-    [value_lo, value_hi]: the register-only loop of bench_mfma_probe.hip (a measurement aid outside the
-    library); the last of `reps` timed launches counts."""
+def mfma_rate_probe(shape: int, iters: int, value_lo: int, value_hi: int, reps: int = 2) -> float:
+    """Sustained rate of this chip in TOP/s on v_mfma_i32_16x16x64_i8 (shape 16: the instruction of the GEMM
+    phase) or v_mfma_i32_32x32x32_i8 (shape 32) for register operands uniform in [value_lo, value_hi]: the
+    register-only loop of bench_mfma_probe.hip (a measurement aid outside the library); the last of `reps`
+    timed launches counts."""
     import ctypes
     import torch
     path = os.path.join(ROOT, "libbench_mfma_probe.so")
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is missing: run __graft_entry__.build()")
     lib = ctypes.CDLL(path)
-    lib.bench_mfma_rate_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+    lib.bench_mfma_rate_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                           ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     lib.bench_mfma_rate_probe.restype = ctypes.c_int
     out = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -50,7 +51,7 @@ def mfma_rate_probe(iters: int, value_lo: int, value_hi: int, reps: int = 2) -> 
     for _ in range(reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        rc = lib.bench_mfma_rate_probe(iters, value_lo, value_hi, out.data_ptr(), ctypes.byref(ops),
+        rc = lib.bench_mfma_rate_probe(shape, iters, value_lo, value_hi, out.data_ptr(), ctypes.byref(ops),
                                        torch.cuda.current_stream().cuda_stream)
         if rc != 0:
             raise RuntimeError(f"bench_mfma_rate_probe returned {rc}")
@@ -196,16 +197,21 @@ def main() -> int:
 
     if not args.no_ceiling:
         # what this chip sustains on the instruction the GEMM phase is made of, measured now on this machine:
-        # a register-only v_mfma_i32_32x32x32_i8 loop on every CU, operands uniform in [-64, 64] like
-        # round-to-nearest slices (the sustained clock depends on the operand statistics), and on zeros
-        sliceslike = mfma_rate_probe(300000, -64, 64)
-        zeros = mfma_rate_probe(300000, 0, 0)
+        # a register-only v_mfma_i32_16x16x64_i8 loop on every CU, operands uniform in [-1, 127] like the stored
+        # bytes of round-to-nearest slices (the sustained clock depends on the operand statistics), and on zeros;
+        # for comparison the other INT8 shape, 32 x 32 x 32, on the same bytes
+        sliceslike = mfma_rate_probe(16, 150000, -1, 127)
+        zeros = mfma_rate_probe(16, 150000, 0, 0)
+        other_shape = mfma_rate_probe(32, 300000, -1, 127)
         result["roofline"]["sustained_mfma_rate"] = {
-            "unit": "TOP/s", "operands_uniform_in_-64..64": round(sliceslike, 1), "operands_zero": round(zeros, 1),
-            "what": "bench_mfma_probe.hip: register-only MFMA loop, 4 waves on every CU, about 0.1 s per launch",
+            "unit": "TOP/s", "operands_uniform_in_-1..127": round(sliceslike, 1), "operands_zero": round(zeros, 1),
+            "v_mfma_i32_32x32x32_i8_on_-1..127": round(other_shape, 1),
+            "what": ("bench_mfma_probe.hip: register-only v_mfma_i32_16x16x64_i8 loop, 4 waves on every CU, "
+                     "about 0.1 s per launch"),
             "gemm_phase_frac_of_it": round(gemm_tops / sliceslike, 4)}
-        log(f"register-only MFMA loop on this box: {sliceslike:.0f} TOP/s with slice-like operands, {zeros:.0f} TOP/s "
-            f"with zeros; the GEMM phase runs at {100.0 * gemm_tops / sliceslike:.1f} % of the former")
+        log(f"register-only MFMA loop on this box: {sliceslike:.0f} TOP/s with slice-like operands ({other_shape:.0f} "
+            f"on 32x32x32), {zeros:.0f} TOP/s with zeros; the GEMM phase runs at "
+            f"{100.0 * gemm_tops / sliceslike:.1f} % of the first")
 
     if not args.no_native and hasattr(torch, "_int_mm"):
         # context: the INT8 GEMM of the vendor library on one slice-pair-sized product with slice-like

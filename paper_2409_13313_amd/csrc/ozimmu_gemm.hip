@@ -372,17 +372,24 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
     const int64_t wrapA = a.strideA - (int64_t)KT * TILE_BYTES;
     const int64_t wrapB = -a.strideB - (int64_t)KT * TILE_BYTES;
 
-    // Per-lane fragment addresses: row = w*128 + i*16 + lane%16, logical chunk = lane/16 (one MFMA takes the 64 inner
-    // bytes of a stage).  i*16 rows = i*1024 bytes and does not change the swizzle; ring buffer u adds u*32 KiB.
+    // Per-lane fragment addresses: row = w*128 + i*16 + lane%16; one MFMA takes the 64 inner bytes of a stage, the
+    // lanes l/16 = 0, 1, 2, 3 supplying its logical chunks 0, 3, 1, 2 (the same for A and B: the inner order of an
+    // integer dot product is free).  That order keeps the fetches off each other's banks: a ds_read_b128 serves 16
+    // lanes per cycle, and these are not consecutive ones - lanes 0-3, 12-15, 20-23, 24-27 go together, then 4-11,
+    // 16-19, 28-31, and the same in the upper half (measured with single-wave probes under SQ_LDS_BANK_CONFLICT); with
+    // rows 0-3, 12-15 of one chunk and rows 4-11 of another in a cycle, the chunk pairs (0, 3) and (1, 2) are the ones
+    // whose swizzled positions c ^ (row / 4 % 4) never meet.  (Chunks in lane order: every fetch takes 8 cycles
+    // instead of 4.)  i*16 rows = i*1024 bytes and does not change the swizzle; ring buffer u adds u*32 KiB.
     // ds_read offsets are 16-bit immediates, so one base register serves two ring buffers (h = u / 2).
     constexpr int NH = (NS + 1) / 2;
     uint32_t fragA[NH], fragB[NH];
     {
         const int rowA = wm * 128 + (lane & 15), rowB = wn * 128 + (lane & 15);
+        const int chunk = (0x9c >> (2 * (lane >> 4))) & 3;  // 0, 3, 1, 2
 #pragma unroll
         for (int h = 0; h < NH; ++h) {
-            fragA[h] = lds_base + h * 2 * STAGE_BYTES + rowA * TILE_K + swizzle(rowA, lane >> 4) * CHUNK;
-            fragB[h] = lds_base + h * 2 * STAGE_BYTES + rowB * TILE_K + swizzle(rowB, lane >> 4) * CHUNK;
+            fragA[h] = lds_base + h * 2 * STAGE_BYTES + rowA * TILE_K + swizzle(rowA, chunk) * CHUNK;
+            fragB[h] = lds_base + h * 2 * STAGE_BYTES + rowB * TILE_K + swizzle(rowB, chunk) * CHUNK;
         }
     }
     typedef __attribute__((address_space(3))) const v4i* lds_v4i_ptr;

@@ -12,8 +12,10 @@
 // is the LDS bank swizzle of the GEMM kernel applied ahead of time: a tile is
 // copied to LDS as a plain linear 16 KiB copy (which is what the
 // global-load-to-LDS instruction can do: lane i lands at base + 16 i), and the
-// 16-byte operand fetches of v_mfma_i32_32x32x32_i8 (consecutive rows, one
-// logical chunk) of any 16 consecutive lanes cover all 64 LDS banks once.
+// 16-byte operand fetches of v_mfma_i32_16x16x64_i8 (16 consecutive rows; the
+// four groups of 16 lanes take logical chunks 0, 3, 1, 2) cover all 64 LDS banks
+// once in each of the four cycles a ds_read_b128 takes (see k_gemm for the lanes
+// that share a cycle).
 //
 // Stored bytes are OFFSET-ENCODED: a stack carries one offset c and the byte of
 // an element is q + c, q being the slice integer of the method (inner padding

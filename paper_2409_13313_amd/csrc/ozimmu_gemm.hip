@@ -116,18 +116,25 @@ __device__ inline void tile_of_queue(int lin, int TM, int TP, bool block_rounds,
     tp = sbc * 16 + (patch % 4) * 4 + mem / 8;
 }
 
-// One 16-byte-per-lane copy global -> LDS: lane i of the wave writes LDS bytes
-// [m0_base + IMM + 16 i, +16) with the 16 bytes at gbase + voff (voff per lane).
+// Global -> LDS copies, 16 bytes per lane: lane i of the wave writes LDS bytes [M0 + offset + 16 i, + 16) with
+// the 16 bytes at gbase + voff + offset (voff per lane; the instruction's offset moves both addresses alike).
 // M0 carries the LDS address; one wait state must separate its write from the copy.
-template <int IMM>
-__device__ inline void copy16_to_lds(uint32_t m0_base, uint32_t voff, const int8_t* gbase)
+// Quarter Q of a wave's 4 KiB of an operand tile: the wave's lanes copy bytes [4096 w + 1024 Q + 16 lane, + 16) of
+// the tile to the same place of the LDS buffer at m0_base + IMM; M0 is set for quarter 0 and used by the other three
+// (nothing else in the main loop touches M0), so that three of four copies are a single instruction between two
+// MFMAs (with M0 set up for every copy: 1 % slower at 16384^3).
+template <int IMM, int Q>
+__device__ inline void copy_tile_quarter(uint32_t m0_base, uint32_t voff, const int8_t* gbase)
 {
-    asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(m0_base), "n"(IMM),
-                 "v"(voff), "s"(gbase)
-                 : "memory", "scc");
+    if constexpr (Q == 0)
+        asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(m0_base), "n"(IMM),
+                     "v"(voff), "s"(gbase)
+                     : "memory", "scc");
+    else
+        asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(voff), "s"(gbase), "n"(Q * 1024) : "memory");
 }
 
-// The same with the non-temporal hint (data that is read once).
+// One copy with an M0 of its own and the non-temporal hint (data that is read once).
 template <int IMM>
 __device__ inline void copy16_to_lds_nt(uint32_t m0_base, uint32_t voff, const void* gbase)
 {
@@ -363,10 +370,9 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
 
     const int KT = a.KT;  // a multiple of NS (inner padding granule KPAD)
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
-    const uint32_t m0_wave = lds_base + (uint32_t)wave * 1024u;
-    uint32_t voff[NLOAD];  // lane offset of quarter q of a tile copy
-#pragma unroll
-    for (int q = 0; q < NLOAD; ++q) voff[q] = (uint32_t)t * 16u + q * 4096u;
+    // operand tile copies: wave w brings bytes [4096 w, 4096 w + 4096) of a tile, 1 KiB per copy
+    const uint32_t m0_tile = lds_base + (uint32_t)wave * 4096u;
+    const uint32_t voff_tile = (uint32_t)wave * 4096u + (uint32_t)lane * 16u;
     // moving on to the next slice pair of a chunk: A slice s -> s+1, B slice g-s -> g-s-1, inner tile KT-1 -> 0
     // (on top of the usual step of one tile)
     const int64_t wrapA = a.strideA - (int64_t)KT * TILE_BYTES;
@@ -390,6 +396,8 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
         for (int h = 0; h < NH; ++h) {
             fragA[h] = lds_base + h * 2 * STAGE_BYTES + rowA * TILE_K + swizzle(rowA, chunk) * CHUNK;
             fragB[h] = lds_base + h * 2 * STAGE_BYTES + rowB * TILE_K + swizzle(rowB, chunk) * CHUNK;
+            // (registers of their own: otherwise the second base is re-made from the first by an add inside the loop)
+            asm volatile("" : "+v"(fragA[h]), "+v"(fragB[h]));
         }
     }
     typedef __attribute__((address_space(3))) const v4i* lds_v4i_ptr;
@@ -629,11 +637,15 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 Cursor cb = {a.SB + (int64_t)(g - c0 - 1 - pair0) * a.strideB + (int64_t)tp * rowblock_bytes(KT) +
                                  (int64_t)kt0 * TILE_BYTES,
                              (KT - kt0) / NS};
-                // a cursor that has just copied the last inner tile of a slice jumps to the next slice pair
-                auto wrap_check = [&](Cursor& c, int64_t extra) {
-                    const bool wr = (--c.groups_left == 0);
-                    c.ptr += wr ? extra : (int64_t)0;
+                // A cursor that has just copied the last inner tile of a slice jumps to the next slice pair.  The
+                // bookkeeping is cut into pieces of two or three scalar instructions that the stage below puts into
+                // different gaps between MFMAs (in one piece at the end of the stage it made a bubble of a dozen
+                // instructions: 0.5 % of the launch): count the group and note whether the slice ends ...
+                auto wrap_count = [&](Cursor& c) -> bool { return --c.groups_left == 0; };
+                // ... and the cursor's step for this stage
+                auto wrap_step = [&](Cursor& c, bool wr, int64_t extra) -> int64_t {
                     c.groups_left = wr ? KT / NS : c.groups_left;
+                    return wr ? extra + TILE_BYTES : (int64_t)TILE_BYTES;
                 };
 
                 // 8 x 8 tiles of 16 x 16 per wave; A fragments of row tiles 0..3 / 4..7 in faL / faH, B likewise
@@ -641,9 +653,9 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 v4i faL[4], faH[4], fbL[4], fbH[4];
                 // sub-step ss of a quarter: row tile ss against the four column tiles (by_col: column tile ss against
                 // the four row tiles) - the operand that has just been fetched is the one taken one fragment per sub-step
-                auto math = [&](const v4i* fa, const v4i* fb, int i0, int j0, int ss, bool by_col) {
+                auto math = [&](const v4i* fa, const v4i* fb, int i0, int j0, int ss, bool by_col, int x0, int x1) {
 #pragma unroll
-                    for (int x = 0; x < 4; ++x) {
+                    for (int x = x0; x < x1; ++x) {
                         const int y = (ss & 1) ? 3 - x : x;
                         const int ii = by_col ? y : ss, jj = by_col ? ss : y;
                         acc[i0 + ii][j0 + jj] =
@@ -685,13 +697,13 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     constexpr int sidx = decltype(S)::value;
                     static_for<0, NLOAD>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
-                        copy16_to_lds<sidx * STAGE_BYTES + q * 4096>(m0_wave, voff[q], ca.ptr);
+                        copy_tile_quarter<sidx * STAGE_BYTES, q>(m0_tile, voff_tile, ca.ptr);
                     });
                     ca.ptr += TILE_BYTES;
                     if constexpr (sidx < NS - 2) {
                         static_for<0, NLOAD>([&](auto Q) {
                             constexpr int q = decltype(Q)::value;
-                            copy16_to_lds<sidx * STAGE_BYTES + TILE_BYTES + q * 4096>(m0_wave, voff[q], cb.ptr);
+                            copy_tile_quarter<sidx * STAGE_BYTES + TILE_BYTES, q>(m0_tile, voff_tile, cb.ptr);
                         });
                         cb.ptr += TILE_BYTES;
                     }
@@ -764,36 +776,40 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     constexpr bool fetch_next = !tail || u < NS - 1;
                     constexpr uint32_t curA = (u % 2) * STAGE_BYTES, curB = (u % 2) * STAGE_BYTES + TILE_BYTES;
                     constexpr uint32_t nxtA = (un % 2) * STAGE_BYTES, nxtB = (un % 2) * STAGE_BYTES + TILE_BYTES;
+                    // the B set the stage starts on (column tiles j_first ..) and the other one
+                    v4i* const fb_first = odd ? fbH : fbL;
+                    v4i* const fb_other = odd ? fbL : fbH;
+                    constexpr int j_first = odd ? 4 : 0, j_other = odd ? 0 : 4;
+                    // a sub-step: one fetch, two MFMAs, a copy or a piece of cursor bookkeeping (taking turns), two
+                    // MFMAs - a 4-pass MFMA leaves three issue slots behind it, and whatever does not fit delays the next
+                    constexpr bool wraps_b = copy_b && u == 1 && !tail, wraps_a = copy_a && u == 0 && !tail;
+                    bool wr_b = false, wr_a = false;
+                    int64_t step_b = TILE_BYTES, step_a = TILE_BYTES;
                     // quarter 0: B fragments of the other half of this stage come in
                     static_for<0, 4>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
-                        if constexpr (!odd) {
-                            fbH[q] = *(lds_v4i_ptr)(uintptr_t)(fragB[u / 2] + curB + (4 + q) * 1024);
-                            math(faL, fbL, 0, 0, q, true);
-                        } else {
-                            fbL[q] = *(lds_v4i_ptr)(uintptr_t)(fragB[u / 2] + curB + q * 1024);
-                            math(faL, fbH, 0, 4, q, true);
-                        }
+                        fb_other[q] = *(lds_v4i_ptr)(uintptr_t)(fragB[u / 2] + curB + (j_other + q) * 1024);
+                        math(faL, fb_first, 0, j_first, q, true, 0, 2);
+                        __builtin_amdgcn_sched_barrier(0);
                         if constexpr (copy_b && q % 2 == 0)
-                            copy16_to_lds<ub * STAGE_BYTES + TILE_BYTES + (q / 2) * 4096>(m0_wave, voff[q / 2], cb.ptr);
+                            copy_tile_quarter<ub * STAGE_BYTES + TILE_BYTES, q / 2>(m0_tile, voff_tile, cb.ptr);
+                        if constexpr (wraps_b && q == 1) wr_b = wrap_count(cb);
+                        if constexpr (wraps_b && q == 3) step_b = wrap_step(cb, wr_b, wrapB);
+                        math(faL, fb_first, 0, j_first, q, true, 2, 4);
                         __builtin_amdgcn_sched_barrier(0);
                     });
                     // quarter 1: A fragments of the upper half of this stage
                     static_for<0, 4>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
                         faH[q] = *(lds_v4i_ptr)(uintptr_t)(fragA[u / 2] + curA + (4 + q) * 1024);
-                        if constexpr (!odd)
-                            math(faL, fbH, 0, 4, q, true);
-                        else
-                            math(faL, fbL, 0, 0, q, true);
+                        math(faL, fb_other, 0, j_other, q, true, 0, 2);
+                        __builtin_amdgcn_sched_barrier(0);
                         if constexpr (copy_b && q % 2 == 0)
-                            copy16_to_lds<ub * STAGE_BYTES + TILE_BYTES + (2 + q / 2) * 4096>(m0_wave, voff[2 + q / 2], cb.ptr);
+                            copy_tile_quarter<ub * STAGE_BYTES + TILE_BYTES, 2 + q / 2>(m0_tile, voff_tile, cb.ptr);
+                        if constexpr (copy_b && q == 3) cb.ptr += step_b;
+                        math(faL, fb_other, 0, j_other, q, true, 2, 4);
                         __builtin_amdgcn_sched_barrier(0);
                     });
-                    if constexpr (copy_b) {
-                        cb.ptr += TILE_BYTES;
-                        if constexpr (u == 1 && !tail) wrap_check(cb, wrapB);
-                    }
                     if constexpr (tail && u >= 2)
                         wait_vmcnt<0>();
                     else
@@ -804,32 +820,28 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     static_for<0, 4>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
                         if constexpr (fetch_next) faL[q] = *(lds_v4i_ptr)(uintptr_t)(fragA[un / 2] + nxtA + q * 1024);
-                        if constexpr (!odd)
-                            math(faH, fbH, 4, 4, q, false);
-                        else
-                            math(faH, fbL, 4, 0, q, false);
+                        math(faH, fb_other, 4, j_other, q, false, 0, 2);
+                        __builtin_amdgcn_sched_barrier(0);
                         if constexpr (copy_a && q % 2 == 0)
-                            copy16_to_lds<up * STAGE_BYTES + (q / 2) * 4096>(m0_wave, voff[q / 2], ca.ptr);
+                            copy_tile_quarter<up * STAGE_BYTES, q / 2>(m0_tile, voff_tile, ca.ptr);
+                        if constexpr (wraps_a && q == 1) wr_a = wrap_count(ca);
+                        if constexpr (wraps_a && q == 3) step_a = wrap_step(ca, wr_a, wrapA);
+                        math(faH, fb_other, 4, j_other, q, false, 2, 4);
                         __builtin_amdgcn_sched_barrier(0);
                     });
-                    // quarter 3: the B fragments the next stage starts with
+                    // quarter 3: the B fragments the next stage starts with (its first set is this stage's other one)
                     static_for<0, 4>([&](auto Q) {
                         constexpr int q = decltype(Q)::value;
-                        if constexpr (!odd) {
-                            if constexpr (fetch_next) fbH[q] = *(lds_v4i_ptr)(uintptr_t)(fragB[un / 2] + nxtB + (4 + q) * 1024);
-                            math(faH, fbL, 4, 0, q, false);
-                        } else {
-                            if constexpr (fetch_next) fbL[q] = *(lds_v4i_ptr)(uintptr_t)(fragB[un / 2] + nxtB + q * 1024);
-                            math(faH, fbH, 4, 4, q, false);
-                        }
+                        if constexpr (fetch_next)
+                            fb_other[q] = *(lds_v4i_ptr)(uintptr_t)(fragB[un / 2] + nxtB + (j_other + q) * 1024);
+                        math(faH, fb_first, 4, j_first, q, false, 0, 2);
+                        __builtin_amdgcn_sched_barrier(0);
                         if constexpr (copy_a && q % 2 == 0)
-                            copy16_to_lds<up * STAGE_BYTES + (2 + q / 2) * 4096>(m0_wave, voff[2 + q / 2], ca.ptr);
+                            copy_tile_quarter<up * STAGE_BYTES, 2 + q / 2>(m0_tile, voff_tile, ca.ptr);
+                        if constexpr (copy_a && q == 3) ca.ptr += step_a;
+                        math(faH, fb_first, 4, j_first, q, false, 2, 4);
                         __builtin_amdgcn_sched_barrier(0);
                     });
-                    if constexpr (copy_a) {
-                        ca.ptr += TILE_BYTES;
-                        if constexpr (u == 0 && !tail) wrap_check(ca, wrapA);
-                    }
                 };
                 static_assert(NS == 4, "the tail logic below is written for a ring of 4 stages");
                 for (int it = 0; it < nstage - NS; it += NS)

@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch of the GEMM kernel at the L2 / fabric boundary, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script, each scaled by the same counter on a plain copy (profiles/k_gemm_16384_k8_traffic.md).
 # Counters cannot be read from inside this process: the figure exists for the shapes profiled, else null.
-MEASURED_TRAFFIC_BYTES = {(16384, 16384, 16384, 8): 261.7e9 + 10.74e9}
+MEASURED_TRAFFIC_BYTES = {(16384, 16384, 16384, 8): 281.0e9 + 10.74e9}
 
 
 def log(*a):

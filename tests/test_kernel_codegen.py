@@ -46,5 +46,15 @@ def test_no_compiler_made_memory_wait_inside_the_mfma_loop(tmp_path):
         # LDS data in the steady state must leave the three youngest fetches pending
         lgkm = [int(re.search(r"lgkmcnt\((\d+)\)", l).group(1)) for l in steady if "s_waitcnt" in l and "lgkmcnt" in l]
         assert lgkm and min(lgkm) >= 3, (mode, sorted(set(lgkm)))
+        # issue slots: with one wave per SIMD an instruction issues every 4 cycles and a 4-pass MFMA lasts 16, so three
+        # other instructions fit behind an MFMA and a longer run delays the next one (a dozen scalar instructions of
+        # cursor bookkeeping in one gap, an M0 set-up per copy: 2 to 3 % of the run time)
+        code = [l.strip() for l in steady]
+        code = [l for l in code if l and not l.startswith(";") and not l.startswith(".")]
+        at = [i for i, l in enumerate(code) if l.startswith("v_mfma")]
+        for a, b in zip(at, at[1:]):
+            gap = code[a + 1:b]
+            limit = 5 if any(l.startswith("s_barrier") for l in gap) else 3
+            assert len(gap) <= limit, (mode, gap)
         checked += 1
     assert checked == 4

@@ -296,11 +296,16 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         a.sync_zeroed = take_clean();
         return hip_status(ozk::launch_gemm(a, 3, st));
     };
-    // Asked for, or the output has tiles for every compute unit (measured against queue for the full rounds +
-    // one of the other ways for a short last round: equal or better with everything in the queue).
-    // From about 100 tiles on it also beats the chunk-parallel way with its separate accumulation kernel
-    // (2560^3, 100 tiles: 0.61 against 0.67 ms; 3072^3: 1.01 against 1.05 ms; 2048^3, 64 tiles: 0.38 against 0.36).
-    if (schedule == OZIMMU_SCHEDULE_QUEUE || (schedule == 0 && T >= QUEUE_MIN_TILES)) {
+    // Asked for, or the output has more tiles than compute units (measured against queue for the full rounds +
+    // one of the other ways for a short last round: equal or better with everything in the queue), or at least
+    // QUEUE_MIN_TILES and no room for the chunk-parallel way.  An output of one round of tiles whose blocks fit
+    // goes the chunk-parallel way further down: every compute unit gets items from the first moment, and the one
+    // accumulation kernel at the end costs less than the queue's ramp (k = 8, chunk-parallel against queue:
+    // 2560^3, 100 tiles, 0.53 against 0.58 ms; 3072^3 0.87 against 0.92; 4096^3, 256 tiles, 1.87 against 1.89;
+    // 5120^3, 400 tiles, with the queue for the full round only: 3.60 against 3.43).
+    const bool one_round_fits = !per_slice && partial && T <= num_cu && T * w <= CHUNK_PARALLEL_MAX_BLOCKS &&
+                                T * w <= partial_capacity;
+    if (schedule == OZIMMU_SCHEDULE_QUEUE || (schedule == 0 && T >= QUEUE_MIN_TILES && !one_round_fits)) {
         const int64_t sets = queue_sets(T);
         if (sets > 0) return launch_queue(T, sets);
     }
@@ -315,21 +320,21 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
     int cp_z = 1;
     if (!per_slice && partial && cand >= 1 && cand * w <= CHUNK_PARALLEL_MAX_BLOCKS && cand * w <= partial_capacity &&
         schedule != OZIMMU_SCHEDULE_ONE_LAUNCH && schedule != OZIMMU_SCHEDULE_SPLIT_INNER) {
-        // (measured on MI355X: a stage 0.68 us; prologue + epilogue of an item 15 us, 22 us when the epilogue adds
+        // (measured on MI355X: a stage 0.58 us; prologue + epilogue of an item 12 us, 19 us when the epilogue adds
         // with atomics; clearing the blocks 5 us + 0.065 us per block; the accumulation kernel 15 us + 0.058 us
         // per block)
-        const double stage_us = 0.68;
+        const double stage_us = 0.58;
         const double pairs = (double)k * (k + 1) / 2;
         const int longest = r_eff < k ? r_eff : k;  // pairs of the longest chunk
         const double blocks = (double)(cand * w);
         // one more round of the persistent launch: every tile at once, chunks in sequence, each with a fused
         // epilogue in which all workgroups update D at the same time (measured 2.0 ms at 4096^3, k = 8)
-        const double one_launch_us = 0.70 * pairs * KT + 50.0 * (double)w;
+        const double one_launch_us = 0.60 * pairs * KT + 50.0 * (double)w;
         double best = 0.0;
         int best_z = 0;
         const int zmax = KT / 4 > 0 ? KT / 4 : 1;
         for (int z = 1; z <= zmax; z *= 2) {
-            const double item_us = z > 1 ? 22.0 : 15.0;
+            const double item_us = z > 1 ? 19.0 : 12.0;
             const double total = (double)cand * (stage_us * pairs * KT + item_us * (double)w * z);
             const double longest_item = stage_us * longest * KT / z + item_us;
             // items are handed out longest first to whichever workgroup is free: the last ones end unevenly
@@ -347,6 +352,11 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             cp_z = best_z;
         }
     }
+    if (cp_tail == 0 && one_round_fits && schedule == 0 && T >= QUEUE_MIN_TILES) {
+        // (the model preferred the persistent launch to the chunk-parallel way: the queue beats that one)
+        const int64_t sets = queue_sets(T);
+        if (sets > 0) return launch_queue(T, sets);
+    }
 
     // tiles [0, T - tail) go to the persistent launch, the last `tail` tiles (band order) are cut Z ways
     int64_t tail = 0;
@@ -357,10 +367,10 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         const int64_t zmax = KT / 4;  // every part gets at least one group of 4 stages of the shortest chunk
         if (cand >= 1 && cand <= SPLIT_INNER_MAX_TILES && zmax >= 2) {
             // Time per chunk in microseconds, from measurements on MI355X: a stage of the main loop takes
-            // 0.68 us; the fused path pays about 35 us per chunk and tile for epilogue and prologue, a part of
+            // 0.58 us; the fused path pays about 35 us per chunk and tile for epilogue and prologue, a part of
             // the cut path about 15 us (atomic epilogue, prologue), and every chunk of the cut path about 15 us
             // of launches plus the accumulation pass over the tail tiles (20 bytes per element at 4.5 TB/s).
-            const double chunk_us = 0.68 * (double)k * (k + 1) / 2 * KT / (double)w;  // average chunk of one tile
+            const double chunk_us = 0.58 * (double)k * (k + 1) / 2 * KT / (double)w;  // average chunk of one tile
             const double fused_us = chunk_us + 35.0;  // one more round of the persistent launch
             const double fixed_us = 15.0 + 0.29 * (double)cand;
             double best = 0.0;
@@ -420,6 +430,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
         t.m = m;
         t.p = p;
         t.Ct = partial;
+        t.parts = cp_z;
         t.eA = eA;
         t.eB = eB;
         t.D = D;
@@ -454,6 +465,7 @@ int run_schedule(int64_t m, int64_t n, int64_t p, const int8_t* SA, const int8_t
             t.m = m;
             t.p = p;
             t.Ct = partial;
+            t.parts = Z;
             t.eA = eA;
             t.eB = eB;
             t.shift = 2 - beta * g;

@@ -9,9 +9,10 @@
 // single FP64 addition per chunk is the only rounding on the whole path.
 // MODE 2 is MODE 1 for slices that carry one scale each (Algorithm 5): every chunk
 // is one pair (s, t) and the factor is 2^(2 - 2 beta) diag(2^eA_s) . diag(2^eB_t).
-// MODE 3 is MODE 0 for tiles too few to fill the chip: the inner range of the chunk
-// is cut into Z parts that run on different workgroups and add their INT32 partial
-// sums to zeroed per-tile blocks with integer atomics (exact in any order).  With
+// MODE 3 is MODE 0 for tiles too few to fill the chip, its output one 256 x 256 block
+// per work item in the accumulators' own order (see lane_major_coords): the inner range
+// of the chunk is cut into Z parts that run on different workgroups and add their INT32
+// partial sums to zeroed per-tile blocks with integer atomics (exact in any order).  With
 // a.nchunks > 0 one MODE 3 launch covers ALL chunks of the schedule at once: a work
 // item is (chunk, part, tile), every chunk has a block per tile of its own, and a
 // separate kernel adds the chunks up in FP64 in the order of Algorithm 6.  With
@@ -159,13 +160,24 @@ __device__ inline void static_for(F&& f)
     }
 }
 
-// Layout of a 256 x 256 INT32 block of the queue schedule: "lane-major".  The four accumulators of 16 x 16 tile
+// Layout of a 256 x 256 INT32 block of a MODE 3 launch: "lane-major".  The four accumulators of 16 x 16 tile
 // (i, j) of thread t (wave t / 64 = 2 wm + wn, lane l = t % 64) are the 16 bytes at int index
 // (G * 256 + t) * 4 with the group number G = ((i / 2) * 8 + j) * 2 + i % 2; they belong to rows
 // wm * 128 + i * 16 + 4 (l / 16) + 0 .. 3 and column wn * 128 + j * 16 + l % 16 of the block.  A workgroup writes
 // a block with 64 fully coalesced 16-byte stores per thread (256 4-byte stores in row-major order cost 10 us more
 // per work item), and thread t of the workgroup that adds the tile up reads back what a thread t wrote.
 constexpr int QBLOCK_GROUP_BYTES = 256 * 16;  // one group (a tile's accumulators of all 256 threads)
+// Every MODE 3 launch leaves its blocks in this layout (the kernels that add the blocks of the other schedules up
+// read it back with the same thread numbering); launches that cut the inner range (partial sums added with integer
+// atomics) put register r of thread t of group G at int index G * 1024 + r * 256 + t instead.  Row (of register 0; registers 1 .. 3 follow) and column inside the
+// 256 x 256 block of group G of thread t:
+__device__ inline void lane_major_coords(int G, int t, int& row, int& col)
+{
+    const int wave = t >> 6, lane = t & 63;
+    const int i = 2 * (G >> 4) + (G & 1), j = (G >> 1) & 7;
+    row = (wave >> 1) * 128 + i * 16 + 4 * (lane >> 4);
+    col = (wave & 1) * 128 + j * 16 + (lane & 15);
+}
 
 // Steps (iv) and (v) for one tile by one workgroup (the queue schedule): the tile's chunk sums lie in `w` lane-major
 // INT32 blocks, `cstride` elements apart, in schedule order; every element gets them added in that order with one
@@ -860,29 +872,47 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                 // a chunk are formed here and not at kernel entry (where they would be spilled)
                 int lqe = lane >> 4, lce = lane & 15;
                 asm volatile("" : "+v"(lqe), "+v"(lce));
-                if (MODE == 3 && queued) {
-                    // the whole block, lane-major (see accumulate_tile), written through: another XCD's workgroup
-                    // may add the tile up.  No bounds: rows and columns past the edge of D exist in the block.
-                    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-                        a.C + (int64_t)__builtin_amdgcn_readfirstlane((int)block_no) * (256 * 256), 0, 256 * 256 * 4, 0x00020000);
+                if (MODE == 3) {
+                    // The whole block, lane-major (see lane_major_coords), written through: in the queue schedule
+                    // another XCD's workgroup may add the tile up.  No bounds: rows and columns past the edge of D exist
+                    // in the block.  The block: the queue's, or block (chunk, tile) of the launch.
+                    const int64_t blk = queued ? block_no : (int64_t)chunk_no * a.tile_count + ztile;
+                    int32_t* const bptr = a.C + (int64_t)__builtin_amdgcn_readfirstlane((int)blk) * (256 * 256);
                     int voff = lqe * 256 + lce * 16 + wave * 1024;  // 16 t, from the lane parts made opaque above
                     asm volatile("" : "+v"(voff));
+                    if (Z > 1) {
+                        // partial sum of one part of the inner range: integer adds commute, the block starts at zero
 #pragma unroll
-                    for (int i = 0; i < 8; ++i)
+                        for (int i = 0; i < 8; ++i)
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            typedef int v4si __attribute__((ext_vector_type(4)));
-                            // (through ordinary registers, said explicitly: asked to store the accumulation registers
-                            // directly, the register allocator spills whole tiles; and one group at a time: left
-                            // alone, the scheduler copies all 256 accumulators first)
-                            int x0 = acc[i][j][0], x1 = acc[i][j][1], x2 = acc[i][j][2], x3 = acc[i][j][3];
-                            asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3));
-                            const v4si val = {x0, x1, x2, x3};
-                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int, val),
-                                                                   rsrc, voff, (((i >> 1) * 8 + j) * 2 + (i & 1)) * QBLOCK_GROUP_BYTES, 1 << 4);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                } else if (MODE == 0 || MODE == 3) {
+                            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    // (register r of all 256 threads side by side inside the group: 64 consecutive
+                                    // integers per wave and instruction; in lane-major order, 16 bytes apart, the
+                                    // atomics take twice as long)
+                                    __hip_atomic_fetch_add(bptr + (((i >> 1) * 8 + j) * 2 + (i & 1)) * (QBLOCK_GROUP_BYTES / 4) +
+                                                               r * 256 + (voff >> 4),
+                                                           acc[i][j][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    } else {
+                        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(bptr, 0, 256 * 256 * 4, 0x00020000);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                typedef int v4si __attribute__((ext_vector_type(4)));
+                                // (through ordinary registers, said explicitly: asked to store the accumulation
+                                // registers directly, the register allocator spills whole tiles; and one group at a
+                                // time: left alone, the scheduler copies all 256 accumulators first)
+                                int x0 = acc[i][j][0], x1 = acc[i][j][1], x2 = acc[i][j][2], x3 = acc[i][j][3];
+                                asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3));
+                                const v4si val = {x0, x1, x2, x3};
+                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((__vector_size__(4 * sizeof(unsigned int)))) unsigned int, val),
+                                                                       rsrc, voff, (((i >> 1) * 8 + j) * 2 + (i & 1)) * QBLOCK_GROUP_BYTES, 1 << 4);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                    }
+                } else if (MODE == 0) {
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         const bool col_ok = ec0 + 16 * j + lce < a.p;
@@ -890,22 +920,10 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                         for (int i = 0; i < 8; ++i)
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
-                                const int rt = i * 16 + r;  // uniform part of the row in the wave's block
-                                const int64_t urow = er0 + rt;
-                                // MODE 3: the tile's own dense 256 x 256 block, addressed by the row / column in the tile
-                                int32_t* base = (MODE == 3)
-                                                    ? a.C + ((int64_t)chunk_no * a.tile_count + ztile) * (256 * 256) +
-                                                          (int64_t)(wm * 128 + rt) * 256 + wn * 128 + j * 16
-                                                    : a.C + urow * a.ldc + ec0 + j * 16;
-                                const uint32_t off =
-                                    (uint32_t)(4 * lqe) * ((MODE == 3) ? 256u : (uint32_t)a.ldc) + (uint32_t)lce;
-                                if (col_ok && urow + 4 * lqe < a.m) {
-                                    if (MODE == 3 && Z > 1)  // partial sum of one part: integer adds commute, C'' starts at zero
-                                        __hip_atomic_fetch_add(&base[off], acc[i][j][r], __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT);
-                                    else
-                                        base[off] = acc[i][j][r];
-                                }
+                                const int64_t urow = er0 + i * 16 + r;  // (the lane's row: + 4 lqe)
+                                int32_t* base = a.C + urow * a.ldc + ec0 + j * 16;
+                                const uint32_t off = (uint32_t)(4 * lqe) * (uint32_t)a.ldc + (uint32_t)lce;
+                                if (col_ok && urow + 4 * lqe < a.m) base[off] = acc[i][j][r];
                             }
                     }
                 } else {
@@ -1107,24 +1125,40 @@ __global__ __launch_bounds__(256) void k_accumulate(int64_t m, int64_t p, const 
     }
 }
 
-// Step (iv) for a range of tiles whose INT32 chunk sums lie in per-tile dense 256 x 256 blocks (the
+// Step (iv) for a range of tiles whose INT32 chunk sums lie in per-tile lane-major 256 x 256 blocks (the
 // split-inner schedule); the blocks are cleared after use for the next chunk's integer atomics.
-// A workgroup handles 8 rows of one tile, lanes along the row.  t.finish: step (v) on the result.
+// A workgroup handles two groups of a block: thread t the 8 rows x 1 column that thread t of the GEMM held there.
+// t.finish: step (v) on the result.
 __global__ __launch_bounds__(256) void k_accumulate_tiles(ozk::TileAccArgs t)
 {
-    const int local = blockIdx.x / 32, rows8 = blockIdx.x % 32;
+    const int local = blockIdx.x / 32, sub = blockIdx.x % 32;
     int tm, tp;
     tile_of_linear(t.tile_begin + local, t.TM, t.TP, tm, tp);
-    const int64_t j = (int64_t)tp * 256 + threadIdx.x;
-    int32_t* c = t.Ct + (int64_t)local * (256 * 256) + (int64_t)rows8 * 8 * 256 + threadIdx.x;
-    const bool col_ok = j < t.p;
-    const int eb = col_ok ? t.eB[j] + t.shift : 0;
-    for (int q = 0; q < 8; ++q) {
-        const int64_t i = (int64_t)tm * 256 + rows8 * 8 + q;
-        const int32_t v = c[q * 256];
-        c[q * 256] = 0;
-        if (col_ok && i < t.m) {
-            const double term = ldexp((double)v, t.eA[i] + eb);
+    typedef int v4si __attribute__((ext_vector_type(4)));
+    for (int gq = 0; gq < 2; ++gq) {
+        const int G = 2 * sub + gq;
+        int row, col;
+        lane_major_coords(G, (int)threadIdx.x, row, col);
+        v4si v;
+        if (t.parts > 1) {
+            int32_t* c = t.Ct + (int64_t)local * (256 * 256) + G * 1024 + threadIdx.x;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v[q] = c[q * 256];
+                c[q * 256] = 0;
+            }
+        } else {
+            v4si* c = reinterpret_cast<v4si*>(t.Ct + (int64_t)local * (256 * 256)) + G * 256 + threadIdx.x;
+            v = *c;
+            *c = (v4si){0, 0, 0, 0};
+        }
+        const int64_t j = (int64_t)tp * 256 + col;
+        if (j >= t.p) continue;
+        const int eb = t.eB[j] + t.shift;
+        for (int q = 0; q < 4; ++q) {
+            const int64_t i = (int64_t)tm * 256 + row + q;
+            if (i >= t.m) break;
+            const double term = ldexp((double)v[q], t.eA[i] + eb);
             double* d = t.D + i * t.ldd + j;
             double val = t.first ? term : (*d + term);
             if (t.finish) {
@@ -1139,38 +1173,60 @@ __global__ __launch_bounds__(256) void k_accumulate_tiles(ozk::TileAccArgs t)
     }
 }
 
-// Step (iv) over all chunks of the schedule for a range of tiles: chunk q's INT32 sums lie in blocks
+// Step (iv) over all chunks of the schedule for a range of tiles: chunk q's INT32 sums lie in lane-major blocks
 // Ct[q * tile_count + tile]; D = fl(...fl(fl(T_1 + T_2) + T_3)...) in schedule order (g ascending, chunks of r
 // ascending), T_q = 2^(2 - beta g) diag(2^eA) FP64(C''_q) diag(2^eB), the first addend taken as it is.
+// Work split as in k_accumulate_tiles.
 __global__ __launch_bounds__(256) void k_accumulate_chunks(ozk::TileAccArgs t, int k, int r, int beta)
 {
-    const int local = blockIdx.x / 32, rows8 = blockIdx.x % 32;
+    const int local = blockIdx.x / 32, sub = blockIdx.x % 32;
     int tm, tp;
     tile_of_linear(t.tile_begin + local, t.TM, t.TP, tm, tp);
-    const int64_t j = (int64_t)tp * 256 + threadIdx.x;
-    if (j >= t.p) return;
-    const int eb = t.eB[j];
+    typedef int v4si __attribute__((ext_vector_type(4)));
     const int64_t chunk_stride = (int64_t)t.tile_count * (256 * 256);
-    for (int q = 0; q < 8; ++q) {
-        const int64_t i = (int64_t)tm * 256 + rows8 * 8 + q;
-        if (i >= t.m) break;
-        const int32_t* c = t.Ct + (int64_t)local * (256 * 256) + (int64_t)(rows8 * 8 + q) * 256 + threadIdx.x;
-        const int e = t.eA[i] + eb;
-        double d = 0.0;
+    for (int gq = 0; gq < 2; ++gq) {
+        const int G = 2 * sub + gq;
+        int row, col;
+        lane_major_coords(G, (int)threadIdx.x, row, col);
+        const int64_t j = (int64_t)tp * 256 + col;
+        if (j >= t.p) continue;
+        const int eb = t.eB[j];
+        int e[4];
+        for (int q = 0; q < 4; ++q) {
+            const int64_t i = (int64_t)tm * 256 + row + q;
+            e[q] = i < t.m ? t.eA[i] + eb : 0;
+        }
+        const int32_t* c = t.Ct + (int64_t)local * (256 * 256) + G * 1024 + (t.parts > 1 ? (int)threadIdx.x : 4 * (int)threadIdx.x);
+        double d[4] = {0.0, 0.0, 0.0, 0.0};
         bool first = true;
         for (int g = 2; g <= k + 1; ++g)
             for (int c0 = 1; c0 <= g - 1; c0 += r, c += chunk_stride) {
-                const double term = ldexp((double)*c, e + 2 - beta * g);
-                d = first ? term : d + term;
+                v4si v;
+                if (t.parts > 1) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) v[q] = c[q * 256];
+                } else {
+                    v = *reinterpret_cast<const v4si*>(c);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const double term = ldexp((double)v[q], e[q] + 2 - beta * g);
+                    d[q] = first ? term : d[q] + term;
+                }
                 first = false;
             }
-        double* out = t.D + i * t.ldd + j;
-        if (t.finish) {
-            d = t.alpha * d;
-            out = t.Cout + i * t.ldco + j;
-            if (t.cbeta != 0.0) d = d + t.cbeta * *out;
+        for (int q = 0; q < 4; ++q) {
+            const int64_t i = (int64_t)tm * 256 + row + q;
+            if (i >= t.m) break;
+            double val = d[q];
+            double* out = t.D + i * t.ldd + j;
+            if (t.finish) {
+                val = t.alpha * val;
+                out = t.Cout + i * t.ldco + j;
+                if (t.cbeta != 0.0) val = val + t.cbeta * *out;
+            }
+            *out = val;
         }
-        *out = d;
     }
 }
 

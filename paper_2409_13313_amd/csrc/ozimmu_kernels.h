@@ -46,8 +46,9 @@ struct GemmArgs {
     int g_lo, g_hi, r;
     int s0, s1;
     int64_t m, p;          // valid output extent
-    int32_t* C;            // INT32 output (mode 0, single chunk only); fused == 3: one dense 256 x 256 block per
-    int64_t ldc;           // tile of the launch, in the order of the launch's tiles (ldc unused)
+    int32_t* C;            // INT32 output (mode 0, single chunk only); fused == 3: one 256 x 256 block per tile of
+    int64_t ldc;           // the launch, in the order of the launch's tiles, each in the kernel's own element
+                           // order (launch_accumulate_tiles / _chunks read it back; ldc unused)
     double* D;             // FP64 accumulate target (mode 1)
     int64_t ldd;
     const int32_t* eA;
@@ -97,12 +98,14 @@ hipError_t launch_fill_zero_i32_2d(int64_t m, int64_t p, int32_t* C, int64_t ldc
 hipError_t launch_accumulate(int64_t m, int64_t p, const int32_t* C, int64_t ldc, const int32_t* eA,
                              const int32_t* eB, int shift, int first, double* D, int64_t ldd, hipStream_t st);
 // Step (iv) for the tiles tile_begin .. tile_begin + tile_count - 1 (band order) of one chunk (group g, slices
-// s0 .. s1 of A) from per-tile 256 x 256 INT32 blocks holding the chunk sums; the blocks are left zeroed.
+// s0 .. s1 of A) from per-tile 256 x 256 INT32 blocks holding the chunk sums (as launch_gemm with fused == 3 leaves
+// them); the blocks are left zeroed.
 // finish: step (v) as in GemmArgs.
 struct TileAccArgs {
     int tile_begin, tile_count, TM, TP;  // TM, TP are filled in by the launcher
     int64_t m, p;
     int32_t* Ct;
+    int parts;             // zsplit of the launch that left the blocks (it decides their element order)
     const int32_t* eA;
     const int32_t* eB;
     int shift, first;

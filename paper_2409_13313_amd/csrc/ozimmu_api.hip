@@ -99,7 +99,9 @@ constexpr int64_t CHUNK_PARALLEL_MAX_BLOCKS = 4096;
 constexpr int64_t GRID_WAIT_MIN_INNER = 8192 + 512;
 // Sets of blocks the rounds of the queue schedule take in turn (see run_schedule).
 constexpr int64_t QUEUE_SETS = 3;
-constexpr int64_t QUEUE_MIN_TILES = 96;  // outputs of at least this many tiles take the queue by default
+// Outputs of at least this many tiles take the queue by default, unless they are one round of tiles (one per compute
+// unit at most) whose blocks fit the chunk-parallel way.
+constexpr int64_t QUEUE_MIN_TILES = 96;
 constexpr int64_t QUEUE_XCD_WORDS = 8 * 40;  // per-XCD ticket batches of the queue (see k_gemm)
 constexpr int64_t BLOCK_BYTES = 4 * 256 * 256;
 inline int64_t chunks_of(int k, int64_t r)
@@ -213,8 +215,8 @@ struct Finish {
 // of at most r consecutive s), into D.  Four ways to run it, with bit-identical results (details where each is
 // decided below):
 //  * the queue: one launch whose work items are the (chunk, tile) pairs, an INT32 block per item, the tile's chunks
-//    added up by the workgroup that completes it -- the default from QUEUE_MIN_TILES tiles on when the workspace has
-//    room for the blocks;
+//    added up by the workgroup that completes it -- the default for outputs of more tiles than compute units (and
+//    from QUEUE_MIN_TILES tiles on where the chunk-parallel way has no room) when the workspace holds the blocks;
 //  * one persistent launch with the accumulation fused into the GEMM epilogue (mode 1, or 2 for per-slice
 //    scales): one workgroup per compute unit takes tile after tile, all chunks of a tile in turn -- needs no
 //    blocks;

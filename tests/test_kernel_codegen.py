@@ -46,6 +46,9 @@ def test_no_compiler_made_memory_wait_inside_the_mfma_loop(tmp_path):
         # LDS data in the steady state must leave the three youngest fetches pending
         lgkm = [int(re.search(r"lgkmcnt\((\d+)\)", l).group(1)) for l in steady if "s_waitcnt" in l and "lgkmcnt" in l]
         assert lgkm and min(lgkm) >= 3, (mode, sorted(set(lgkm)))
+        # three of four tile copies rely on the M0 that the first one set: nothing else in the loop may write M0
+        m0 = [l.strip() for l in loop if re.search(r"\bm0\b", l)]
+        assert m0 and all(l.startswith("s_add_u32 m0,") for l in m0), (mode, m0[:4])
         # issue slots: with one wave per SIMD an instruction issues every 4 cycles and a 4-pass MFMA lasts 16, so three
         # other instructions fit behind an MFMA and a longer run delays the next one (a dozen scalar instructions of
         # cursor bookkeeping in one gap, an M0 set-up per copy: 2 to 3 % of the run time)

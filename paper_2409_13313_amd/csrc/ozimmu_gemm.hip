@@ -1266,7 +1266,13 @@ __global__ __launch_bounds__(256) void k_axpby(int64_t m, int64_t p, double alph
 
 __global__ __launch_bounds__(256) void k_zero_i32(int64_t count, int32_t* __restrict__ x)
 {
+    // 16 bytes per thread where the array allows it (x is 16-byte aligned: blocks and counters of the workspace)
+    typedef int v4si __attribute__((ext_vector_type(4)));
     const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i0 + 3 < count && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+        *reinterpret_cast<v4si*>(x + i0) = (v4si){0, 0, 0, 0};
+        return;
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q)
         if (i0 + q < count) x[i0 + q] = 0;

@@ -137,7 +137,8 @@ enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 
 /* How the schedule is run; OR one of these into accumulate_mode (default: the library chooses).  The result
  * does not depend on it, bit for bit.
  *   OZIMMU_SCHEDULE_ONE_LAUNCH   the whole schedule in one persistent kernel with the FP64 accumulation
- *                                fused into the GEMM epilogue (what large outputs always get);
+ *                                fused into the GEMM epilogue (what large outputs get when the workspace
+ *                                has no room for the blocks of the queue);
  *   OZIMMU_SCHEDULE_SPLIT_INNER  for the tiles (256 x 256) that would leave most compute units idle -- an
  *                                output of at most 128 tiles, or the last, partly filled round of at most
  *                                128 tiles of a larger output: per chunk, the inner dimension is cut into
@@ -150,7 +151,8 @@ enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 
  *                                take (chunk, inner part, tile) work items, every chunk leaving its INT32 sums in
  *                                a block of its own, and one kernel that adds the chunks of each element in the
  *                                order of Algorithm 6.  All chunks run side by side (a 1024^3 product occupies
- *                                128 compute units instead of 16).  Chosen by default for small outputs when the
+ *                                128 compute units instead of 16).  Chosen by default for outputs of one round of
+ *                                tiles (at most one per compute unit) when the
  *                                workspace has room for the blocks (ozimmu_workspace_bytes includes them,
  *                                ozimmu_workspace_bytes_min does not); the flag forces it wherever it fits and
  *                                is ignored elsewhere. */
@@ -158,7 +160,8 @@ enum { OZIMMU_ACCUM_GROUPED = 0, OZIMMU_ACCUM_PER_PAIR = 1, OZIMMU_ACCUM_WIDE = 
  *                                (256 tiles, all their chunks, longest chunks first) through a counter; an item
  *                                leaves its INT32 sums in a block, and the workgroup that completes a tile's last
  *                                block adds the tile's chunks up in the order of Algorithm 6.  The blocks are
- *                                recycled every few rounds.  Ignored where the workspace has no room for it. */
+ *                                recycled every few rounds.  The default for outputs of more tiles than compute
+ *                                units; ignored where the workspace has no room for it. */
 enum { OZIMMU_SCHEDULE_ONE_LAUNCH = 0x100, OZIMMU_SCHEDULE_SPLIT_INNER = 0x200, OZIMMU_SCHEDULE_CHUNK_PARALLEL = 0x400,
        OZIMMU_SCHEDULE_QUEUE = 0x800 };
 int ozimmu_dgemm_variant(int64_t m, int64_t n, int64_t p,

@@ -860,6 +860,14 @@ __global__ __launch_bounds__(256) void k_gemm(ozk::GemmArgs a, int TM, int TP)
                     static_for<0, NS>([&](auto U) { stage(U, std::false_type{}); });
                 static_for<0, NS>([&](auto U) { stage(U, std::true_type{}); });
                 wait_vmcnt<0>();  // no copy may still be writing LDS when the ring is reused or the workgroup retires
+                if constexpr (MODE == 1 || MODE == 2) {
+                    // (the fused epilogues are long: left alone, the register allocator parks three tiles of
+                    // accumulators in scratch memory during the last stage and reloads them a dozen times)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) asm volatile("" : "+a"(acc[i][j]));
+                }
 
                 // Epilogue.  Accumulator register r of tile (i, j) in lane l holds output row 4*(l/16) + r and
                 // column l%16 of that 16 x 16 tile.  Addresses are a wave-uniform base plus a 32-bit lane offset,
